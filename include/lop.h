@@ -1,0 +1,158 @@
+/* lop.h - C ABI of the banded local-operator chain library for AMD MI355X (gfx950).
+ *
+ * The library executes the data-parallel hot path of Local Operation Parallelism
+ * (Intra-DP, arXiv 2507.05829, Sec. IV-A/IV-B): a chain of *local operators*
+ * (block-wise: convolution, depthwise convolution, max pooling; element-wise: bias,
+ * ReLU, ReLU6, residual add) is split into independent *row bands*. A band is a
+ * contiguous interval of final output rows (the contiguous operation interval of
+ * Sec. IV-C, "Computational Efficiency"); the rows of every earlier layer that the
+ * band needs follow from kernel size, stride, padding and dilation (Sec. IV-A) and
+ * are recomputed by neighbouring bands where they overlap (local-operation
+ * replication, Sec. IV-C), so each band's output is final and can be copied to the
+ * host while the next band computes (computation/transmission overlap, Sec. IV-B).
+ *
+ * Conventions
+ *  - Every function returns LOP_OK (0) or a negative lop_status_t; nothing throws,
+ *    aborts or prints.
+ *  - Device tensors are NHWC, dense, in the storage type of the plan (float or
+ *    bfloat16 bit patterns); accumulation is always fp32 and each layer output is
+ *    rounded once (bfloat16: round to nearest even).
+ *  - "host" / "device" in a parameter comment says where the pointer must point.
+ *  - Row intervals are half-open [lo, hi) in rows of the tensor they refer to.
+ */
+#ifndef LOP_H_
+#define LOP_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LOP_API __attribute__((visibility("default")))
+
+typedef enum {
+  LOP_OK = 0,
+  LOP_ERR_INVALID_ARG = -1, /* null pointer, n_bands < 1, non-positive size, bad input_from */
+  LOP_ERR_UNSUPPORTED = -2, /* operator / dtype / parameter combination without a kernel     */
+  LOP_ERR_SHAPE = -3,       /* channel or residual shape mismatch, window larger than input  */
+  LOP_ERR_BAND_RANGE = -4,  /* band or layer index outside the plan                          */
+  LOP_ERR_OOM = -5,         /* host or device allocation failed                              */
+  LOP_ERR_HIP = -6,         /* a HIP call failed; see lop_last_hip_error()                   */
+  LOP_ERR_NOT_READY = -7    /* plan was made with LOP_FLAG_PLAN_ONLY and cannot run          */
+} lop_status_t;
+
+/* Operator kinds (Sec. IV-A). Global operators (softmax, ...) are not local and are
+ * rejected with LOP_ERR_UNSUPPORTED. */
+typedef enum { LOP_CONV2D = 0, LOP_DWCONV2D = 1, LOP_MAXPOOL2D = 2, LOP_ELTWISE = 3 } lop_op_t;
+typedef enum { LOP_ACT_NONE = 0, LOP_ACT_RELU = 1, LOP_ACT_RELU6 = 2 } lop_act_t;
+typedef enum { LOP_F32 = 0, LOP_BF16 = 1 } lop_dtype_t;
+
+#define LOP_INPUT (-1)       /* input_from / residual_from: the chain input */
+#define LOP_NO_RESIDUAL (-2) /* residual_from: no residual                  */
+#define LOP_MAX_BANDS 64
+
+/* One vertex of the chain (the DAG of Sec. IV-C restricted to a chain with skip
+ * edges). y = act(op(x) + bias + residual); for LOP_MAXPOOL2D bias, residual and act
+ * must be absent. */
+typedef struct {
+  int op;                  /* lop_op_t                                                    */
+  int c_in, c_out;         /* DWCONV / MAXPOOL / ELTWISE: c_out == c_in                   */
+  int kh, kw, sh, sw, ph, pw, dh, dw; /* window, stride, padding, dilation (ELTWISE: ignored) */
+  int act;                 /* lop_act_t                                                   */
+  int input_from;          /* LOP_INPUT or the index of an earlier layer                  */
+  int residual_from;       /* LOP_NO_RESIDUAL, LOP_INPUT or an earlier layer of the same
+                              output shape; added before the activation                   */
+  const void* weight;      /* host; OIHW in the plan's storage type (DWCONV: C x 1 x kh x kw);
+                              copied by lop_plan, may be freed afterwards; NULL for MAXPOOL
+                              and ELTWISE                                                 */
+  const float* bias;       /* host; c_out fp32 values or NULL (= zero); copied by lop_plan */
+} lop_layer_t;
+
+typedef struct { int n, c, h, w; int dtype; /* lop_dtype_t */ } lop_tensor_desc_t;
+typedef struct { int lo, hi; } lop_rows_t;
+typedef struct lop_plan_s lop_plan_t; /* opaque */
+
+typedef struct {
+  int n_bands;
+  float wall_ms;    /* host clock from first launch to the last byte arriving        */
+  float compute_ms; /* first kernel start to last kernel end on the compute stream   */
+  float copy_ms;    /* sum of the bands' device-to-host copy durations               */
+  float band_compute_ms[LOP_MAX_BANDS];
+  float band_copy_ms[LOP_MAX_BANDS];
+} lop_timing_t;
+
+/* lop_plan flags */
+#define LOP_FLAG_NO_D2H 1u    /* never copy to the host even if a host pointer is given  */
+#define LOP_FLAG_PLAN_ONLY 2u /* integer planning only: touches no GPU, needs no weights;
+                                 lop_run_* return LOP_ERR_NOT_READY                      */
+#define LOP_FLAG_GRAPH 4u     /* lop_run_chain records its launches into a HIP graph on the
+                                 first call for a given set of pointers and replays it   */
+
+/* Build a plan: validate the chain, infer shapes, split the last layer's output rows
+ * into n_bands intervals (first H mod B bands one row longer; trailing bands may be
+ * empty when B > H), propagate each band backwards to the rows of every layer it needs
+ * (hull over all consumers of a tensor, clamped to the image), size the scratch slabs,
+ * and - unless LOP_FLAG_PLAN_ONLY - upload re-laid-out weights and biases to the
+ * current HIP device.  (Sec. IV-A block size; Sec. IV-C partitioning and contiguity.)
+ *   layers   host, n_layers entries, read only during the call
+ *   in       host, shape and storage type of the chain input
+ *   out_plan host; receives the handle, or NULL on error. Free with lop_plan_destroy. */
+LOP_API int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* in, int n_bands,
+             unsigned flags, lop_plan_t** out_plan);
+
+/* Shape queries (host only). */
+LOP_API int lop_plan_out_desc(const lop_plan_t* plan, lop_tensor_desc_t* out);
+LOP_API int lop_plan_layer_desc(const lop_plan_t* plan, int layer, lop_tensor_desc_t* out);
+LOP_API int lop_plan_n_bands(const lop_plan_t* plan);
+LOP_API int lop_plan_n_layers(const lop_plan_t* plan);
+
+/* Row intervals of a band: final output rows, chain-input rows, rows of `layer`'s
+ * output. An empty interval is reported as lo == hi. */
+LOP_API int lop_plan_band_out_rows(const lop_plan_t* plan, int band, lop_rows_t* rows);
+LOP_API int lop_plan_band_in_rows(const lop_plan_t* plan, int band, lop_rows_t* rows);
+LOP_API int lop_plan_band_layer_rows(const lop_plan_t* plan, int band, int layer, lop_rows_t* rows);
+
+/* Work counts: operations of the whole layers (useful) and summed over the bands'
+ * intervals (executed; > useful where halos are recomputed); bytes of device scratch. */
+LOP_API int lop_plan_stats(const lop_plan_t* plan, double* useful_flop, double* executed_flop,
+                   size_t* scratch_bytes);
+/* Per layer and band: operations executed and algorithmic bytes moved (rows read of the
+ * input and residual slabs, rows written, weights). */
+LOP_API int lop_plan_layer_work(const lop_plan_t* plan, int band, int layer, double* flop, double* bytes);
+
+/* Run one band (Alg. 1: compute on an operation interval, then send the finished
+ * rows): enqueue one kernel per layer on compute_stream for the band's intervals,
+ * then, if h_out is not NULL, enqueue on copy_stream the copy of the band's final rows
+ * to h_out once the kernels are done. Asynchronous.
+ *   d_in   device, whole chain input N x H x W x C; only band_in_rows(band) are read
+ *   d_out  device, whole chain output; only band_out_rows(band) are written
+ *   h_out  pinned host, whole chain output, or NULL
+ *   compute_stream, copy_stream  hipStream_t or NULL (= the plan's own streams)
+ * Bands of one plan share scratch memory: run them on one compute stream. */
+LOP_API int lop_run_band(lop_plan_t* plan, int band, const void* d_in, void* d_out, void* h_out,
+                 void* compute_stream, void* copy_stream);
+
+/* Run every band in order; band b's copy overlaps band b+1's kernels (Sec. IV-B).
+ * With timing != NULL the call records events, waits for completion and fills *timing;
+ * otherwise it is asynchronous (lop_synchronize waits). */
+LOP_API int lop_run_chain(lop_plan_t* plan, const void* d_in, void* d_out, void* h_out,
+                  void* compute_stream, lop_timing_t* timing);
+
+/* Wait for everything the plan has enqueued on its own and on the passed streams. */
+LOP_API int lop_synchronize(lop_plan_t* plan);
+
+/* Time one layer's kernel of one band in isolation: `iters` launches on the plan's
+ * compute stream between two events, on the plan's own scratch (contents are whatever
+ * the last run left). Writes the mean milliseconds per launch. Measurement aid. */
+LOP_API int lop_time_layer(lop_plan_t* plan, int band, int layer, const void* d_in, void* d_out,
+                   int iters, float* ms_per_launch);
+
+LOP_API void lop_plan_destroy(lop_plan_t* plan);
+LOP_API const char* lop_strerror(int code);
+LOP_API int lop_last_hip_error(void); /* raw hipError_t behind this thread's last LOP_ERR_HIP */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOP_H_ */

@@ -1,0 +1,317 @@
+// Dense convolution on a row interval as an implicit GEMM on the gfx950 matrix cores.
+//
+// GEMM view of the block-wise local operator (Intra-DP Sec. IV-A): rows are output
+// pixels (n, oh, ow) with oh in the band's interval, columns are output channels, the
+// reduction runs over k = (a*kw + b)*c_in + ci. Activations are NHWC so a run of
+// channels of one tap is contiguous; the im2col matrix is never materialised: each
+// workgroup gathers its 64-byte K-slices of BM pixels straight from the input slab into
+// LDS (zero where a tap falls outside the image; rows outside the slab are never needed
+// by construction and are also read as zero, so no access can leave the slab).
+//
+// Wave tiling: 256 threads = 4 wavefronts of 64 lanes, each owning TM x TN tiles of
+// 32x32 (v_mfma_f32_32x32x16_bf16, or 4 x v_mfma_f32_32x32x2_f32 for fp32). The weight
+// tile is the MFMA A operand and the pixel tile the B operand, so in the accumulator a
+// lane holds 4 consecutive output channels of one pixel: bias, residual, activation and
+// the single rounding to the storage type are applied in registers and stored as one
+// vector per pixel.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+#include "lop.h"
+
+namespace lop {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct ConvParams {
+  const void* x;
+  void* y;
+  const void* res;
+  const void* w;
+  const float* bias;
+  int x_row0, x_rows, H, W, C_in;
+  int y_row0, y_rows, W_out, C_out;
+  int r_row0, r_rows;
+  int kh, kw, sh, sw, ph, pw, dh, dw;
+  int act, out_lo, R, N;
+  int M;  // N * R * W_out
+  int K, k_pad;
+};
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == LOP_ACT_RELU) return fmaxf(v, 0.f);
+  if (act == LOP_ACT_RELU6) return fminf(fmaxf(v, 0.f), 6.f);
+  return v;
+}
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float v) { return (__bf16)v; }
+
+template <typename T>
+__device__ __forceinline__ void mma(const uint4& wa, const uint4& px, f32x16& acc);
+
+template <>
+__device__ __forceinline__ void mma<__bf16>(const uint4& wa, const uint4& px, f32x16& acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa),
+                                                __builtin_bit_cast(bf16x8, px), acc, 0, 0, 0);
+}
+
+template <>
+__device__ __forceinline__ void mma<float>(const uint4& wa, const uint4& px, f32x16& acc) {
+  const f32x4 a = __builtin_bit_cast(f32x4, wa), b = __builtin_bit_cast(f32x4, px);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
+}
+
+// BM pixels x BN channels per workgroup; WM x WN wavefronts; VEC_A: c_in is a multiple
+// of the 16-byte vector so one vector never straddles two taps.
+template <typename T, int BM, int BN, int WM, int WN, bool VEC_A>
+__global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
+  constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
+  constexpr int BKE = 4 * KE;              // reduction elements per step (64 bytes per row)
+  constexpr int ROWB = 80;                 // LDS row pitch: 64 data + 16 pad bytes
+  constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
+  constexpr int A_IT = BM / 64, B_IT = (BN + 63) / 64;
+  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && BM % 64 == 0, "tile shape");
+
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (BM + BN) * ROWB];
+  unsigned char* const As = smem;
+  unsigned char* const Bs = smem + 2 * BM * ROWB;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+  const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+  const int lrow = tid >> 2, chunk = tid & 3;
+  const T* __restrict__ xg = (const T*)p.x;
+  const T* __restrict__ wg = (const T*)p.w;
+
+  // ---- the pixels this thread gathers (fixed over the K loop)
+  int a_ih0[A_IT], a_iw0[A_IT], a_nrow[A_IT];
+  bool a_ok[A_IT];
+#pragma unroll
+  for (int i = 0; i < A_IT; ++i) {
+    const int m = m0 + lrow + 64 * i;
+    a_ok[i] = m < p.M;
+    const int mm = a_ok[i] ? m : 0;
+    const int ow = mm % p.W_out;
+    const int t = mm / p.W_out;
+    const int r = t % p.R, n = t / p.R;
+    a_ih0[i] = (p.out_lo + r) * p.sh - p.ph;
+    a_iw0[i] = ow * p.sw - p.pw;
+    a_nrow[i] = n * p.x_rows - p.x_row0;
+  }
+  // position of this thread's vector inside the reduction axis (VEC_A path)
+  int ci = 0, kwi = 0, khi = 0;
+  if (VEC_A) {
+    const int k = chunk * KE;
+    const int tap = k / p.C_in;
+    ci = k - tap * p.C_in;
+    khi = tap / p.kw;
+    kwi = tap - khi * p.kw;
+  }
+
+  uint4 ra[A_IT], rb[B_IT];
+
+  auto gather = [&](int kc) {
+    if (VEC_A) {
+#pragma unroll
+      for (int i = 0; i < A_IT; ++i) {
+        const int ih = a_ih0[i] + khi * p.dh, iw = a_iw0[i] + kwi * p.dw;
+        const bool ok = a_ok[i] && khi < p.kh && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
+                        iw >= 0 && iw < p.W;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ok) {
+          const size_t off = ((size_t)(a_nrow[i] + ih) * p.W + iw) * p.C_in + ci;
+          v = *(const uint4*)(xg + off);
+        }
+        ra[i] = v;
+      }
+      ci += BKE;
+      while (ci >= p.C_in) {
+        ci -= p.C_in;
+        if (++kwi == p.kw) { kwi = 0; ++khi; }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < A_IT; ++i) {
+        alignas(16) T e[KE];
+#pragma unroll
+        for (int j = 0; j < KE; ++j) {
+          const int k = kc * BKE + chunk * KE + j;
+          const int tap = k / p.C_in, c = k - tap * p.C_in;
+          const int a = tap / p.kw, b = tap - a * p.kw;
+          const int ih = a_ih0[i] + a * p.dh, iw = a_iw0[i] + b * p.dw;
+          const bool ok = a_ok[i] && k < p.K && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
+                          iw >= 0 && iw < p.W;
+          e[j] = ok ? xg[((size_t)(a_nrow[i] + ih) * p.W + iw) * p.C_in + c] : from_f32<T>(0.f);
+        }
+        ra[i] = *(const uint4*)e;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int row = lrow + 64 * i;
+      if (BN >= 64 || row < BN)
+        rb[i] = *(const uint4*)(wg + (size_t)(co0 + row) * p.k_pad + kc * BKE + chunk * KE);
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i)
+      *(uint4*)(As + (buf * BM + lrow + 64 * i) * ROWB + chunk * 16) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+      const int row = lrow + 64 * i;
+      if (BN >= 64 || row < BN) *(uint4*)(Bs + (buf * BN + row) * ROWB + chunk * 16) = rb[i];
+    }
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int a = 0; a < TN; ++a)
+#pragma unroll
+    for (int b = 0; b < TM; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  const int nk = p.k_pad / BKE;
+  gather(0);
+  stash(0);
+  __syncthreads();
+  for (int kc = 0; kc < nk; ++kc) {
+    const int buf = kc & 1;
+    if (kc + 1 < nk) gather(kc + 1);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      uint4 px[TM], wt[TN];
+      const int koff = ks * 32 + (lane >> 5) * 16;
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm)
+        px[tm] = *(const uint4*)(As + (buf * BM + (wm * TM + tm) * 32 + (lane & 31)) * ROWB + koff);
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+        wt[tn] = *(const uint4*)(Bs + (buf * BN + (wn * TN + tn) * 32 + (lane & 31)) * ROWB + koff);
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
+    }
+    if (kc + 1 < nk) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane holds, per 32x32 tile, pixel (lane & 31) and output channels
+  // g*8 + (lane >> 5)*4 + {0,1,2,3} for g = 0..3.
+  T* __restrict__ yg = (T*)p.y;
+  const T* __restrict__ rg = (const T*)p.res;
+  const bool vec_c = (p.C_out & 3) == 0;
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    const int m = m0 + (wm * TM + tm) * 32 + (lane & 31);
+    if (m >= p.M) continue;
+    const int ow = m % p.W_out;
+    const int t = m / p.W_out;
+    const int r = t % p.R, n = t / p.R;
+    const int oh = p.out_lo + r;
+    const size_t ypix = ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C_out;
+    const size_t rpix = rg ? ((size_t)(n * p.r_rows + oh - p.r_row0) * p.W_out + ow) * p.C_out : 0;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int co = co0 + (wn * TN + tn) * 32 + g * 8 + (lane >> 5) * 4;
+        if (co >= p.C_out) continue;
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][g * 4 + j];
+        if (vec_c) {
+          if (p.bias) {
+            const float4 b4 = *(const float4*)(p.bias + co);
+            v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+          }
+          alignas(16) T o[4];
+          if (rg) {
+            alignas(16) T rr[4];
+            if (sizeof(T) == 2) *(uint2*)rr = *(const uint2*)(rg + rpix + co);
+            else *(uint4*)rr = *(const uint4*)(rg + rpix + co);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] += to_f32(rr[j]);
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
+          if (sizeof(T) == 2) *(uint2*)(yg + ypix + co) = *(const uint2*)o;
+          else *(uint4*)(yg + ypix + co) = *(const uint4*)o;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (co + j >= p.C_out) break;
+            float u = v[j];
+            if (p.bias) u += p.bias[co + j];
+            if (rg) u += to_f32(rg[rpix + co + j]);
+            yg[ypix + co + j] = from_f32<T>(apply_act(u, p.act));
+          }
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s) {
+  dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN);
+  if (vec_a)
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, true>), grid, dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, false>), grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_typed(const ConvParams& p, hipStream_t s) {
+  constexpr int KE = 16 / (int)sizeof(T);
+  const bool vec_a = p.C_in % KE == 0;
+  auto blocks = [&](int bm, int bn) {
+    return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn);
+  };
+  // Largest tile that still gives every compute unit a workgroup; small layers fall
+  // through to smaller tiles.
+  if (p.C_out > 64 && blocks(128, 128) >= 256) return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s);
+  if (p.C_out > 32 && blocks(128, 64) >= 256) return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s);
+  if (p.C_out > 32) return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s);
+  return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s);
+}
+
+}  // namespace
+
+int conv_k_pad(int c_in, int kh, int kw, int dtype) {
+  const int bke = dtype == LOP_BF16 ? 32 : 16;
+  const int k = c_in * kh * kw;
+  return (k + bke - 1) / bke * bke;
+}
+
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream) {
+  ConvParams p;
+  p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = L.w; p.bias = L.bias;
+  p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.H = L.x.h; p.W = L.x.w; p.C_in = L.x.c;
+  p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w; p.C_out = L.y.c;
+  p.r_row0 = L.res.row0; p.r_rows = L.res.rows;
+  p.kh = L.kh; p.kw = L.kw; p.sh = L.sh; p.sw = L.sw; p.ph = L.ph; p.pw = L.pw;
+  p.dh = L.dh; p.dw = L.dw;
+  p.act = L.act; p.out_lo = L.out_lo; p.R = L.out_hi - L.out_lo; p.N = L.x.n;
+  p.M = p.N * p.R * p.W_out;
+  p.K = L.x.c * L.kh * L.kw;
+  p.k_pad = L.k_pad;
+  if (p.M <= 0) return hipSuccess;
+  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, stream) : launch_typed<float>(p, stream);
+}
+
+}  // namespace lop

@@ -1,0 +1,39 @@
+// Launch interface of the gfx950 kernels. Every kernel works on row slabs: a tensor is
+// N x rows x W x C (NHWC) holding rows [row0, row0 + rows) of an image of height h.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <cstddef>
+#include <cstdint>
+
+namespace lop {
+
+struct Slab {
+  void* ptr = nullptr;
+  int n = 0, h = 0, w = 0, c = 0;  // h: true image height
+  int row0 = 0, rows = 0;          // rows held
+};
+
+// One local operator on output rows [out_lo, out_hi): y = act(op(x) + bias + res).
+struct OpLaunch {
+  int op = 0;     // lop_op_t
+  int dtype = 0;  // lop_dtype_t
+  Slab x, y, res; // res.ptr == nullptr: no residual
+  const void* w = nullptr;      // device, kernel layout (see pack_* below)
+  const float* bias = nullptr;  // device or nullptr
+  int kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0, dh = 1, dw = 1;
+  int act = 0;
+  int out_lo = 0, out_hi = 0;
+  int k_pad = 0;  // dense conv: padded reduction length of the packed weight rows
+};
+
+// Dense conv weights are packed as [c_out_pad][k_pad], k = (a*kw + b)*c_in + ci, zero
+// padded so the kernel never guards weight loads.
+constexpr int kConvCoutPad = 128;
+int conv_k_pad(int c_in, int kh, int kw, int dtype);
+inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvCoutPad * kConvCoutPad; }
+
+// Enqueue the kernel for one operator on `stream`. Returns hipError_t.
+hipError_t launch_op(const OpLaunch& L, hipStream_t stream);
+
+}  // namespace lop

@@ -1,0 +1,470 @@
+// C ABI of the library: plan construction (host planning + weight upload), the per-band
+// scheduler (compute stream + copy stream + one event per band) and the queries.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.hpp"
+#include "lop.h"
+#include "plan_tables.hpp"
+
+namespace lop {
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream);
+hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream);
+
+hipError_t launch_op(const OpLaunch& L, hipStream_t stream) {
+  if (L.out_hi <= L.out_lo) return hipSuccess;
+  if (L.op == LOP_CONV2D) return launch_conv_igemm(L, stream);
+  return launch_rowwise_op(L, stream);
+}
+}  // namespace lop
+
+namespace {
+thread_local int g_last_hip = 0;
+
+inline int hip_fail(hipError_t e) {
+  g_last_hip = (int)e;
+  return e == hipErrorOutOfMemory ? LOP_ERR_OOM : LOP_ERR_HIP;
+}
+#define LOP_HIP(call)                            \
+  do {                                           \
+    hipError_t e_ = (call);                      \
+    if (e_ != hipSuccess) return hip_fail(e_);   \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+struct lop_plan_s {
+  lop::Tables t;
+  unsigned flags = 0;
+  bool ready = false;
+  int device = -1;
+  std::vector<void*> d_w;      // per layer packed weights (device) or nullptr
+  std::vector<float*> d_bias;  // per layer bias (device) or nullptr
+  std::vector<int> k_pad;
+  void* arena = nullptr;       // scratch slabs of one band at a time
+  size_t arena_bytes = 0;
+  std::vector<std::vector<size_t>> slab_off;  // [band][layer] byte offset into arena
+  hipStream_t s_compute = nullptr, s_copy = nullptr;
+  hipStream_t last_user_stream = nullptr;
+  std::vector<hipEvent_t> ev_done;                          // per band: kernels finished
+  std::vector<hipEvent_t> ev_copied;                        // per band: last copy finished
+  std::vector<char> copied_valid;
+  std::vector<hipEvent_t> ev_c0, ev_c1, ev_d0, ev_d1;       // timing only (lazy)
+  hipEvent_t ev_copy_tail = nullptr;                        // copy stream rejoin
+};
+
+namespace {
+
+int upload_weights(lop_plan_t* P) {
+  const lop::Tables& t = P->t;
+  const int nl = t.n_layers();
+  const bool bf = t.in.dtype == LOP_BF16;
+  P->d_w.assign(nl, nullptr);
+  P->d_bias.assign(nl, nullptr);
+  P->k_pad.assign(nl, 0);
+  for (int l = 0; l < nl; ++l) {
+    const lop::LayerInfo& L = t.layers[l];
+    const lop_layer_t& d = L.d;
+    if (d.op == LOP_CONV2D) {
+      if (!d.weight) return LOP_ERR_INVALID_ARG;
+      const int kp = lop::conv_k_pad(d.c_in, d.kh, d.kw, t.in.dtype);
+      const int cp = lop::conv_cout_pad(d.c_out);
+      P->k_pad[l] = kp;
+      const size_t esz = t.esz();
+      std::vector<unsigned char> host((size_t)cp * kp * esz, 0);
+      // OIHW -> [co][ (a*kw + b)*c_in + ci ]
+      for (int co = 0; co < d.c_out; ++co)
+        for (int ci = 0; ci < d.c_in; ++ci)
+          for (int a = 0; a < d.kh; ++a)
+            for (int b = 0; b < d.kw; ++b) {
+              const size_t src = (((size_t)co * d.c_in + ci) * d.kh + a) * d.kw + b;
+              const size_t dst = (size_t)co * kp + (size_t)(a * d.kw + b) * d.c_in + ci;
+              std::memcpy(&host[dst * esz], (const unsigned char*)d.weight + src * esz, esz);
+            }
+      LOP_HIP(hipMalloc(&P->d_w[l], host.size()));
+      LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size(), hipMemcpyHostToDevice));
+    } else if (d.op == LOP_DWCONV2D) {
+      if (!d.weight) return LOP_ERR_INVALID_ARG;
+      // C x 1 x kh x kw (storage type) -> [tap][C] fp32
+      std::vector<float> host((size_t)d.kh * d.kw * d.c_in);
+      for (int c = 0; c < d.c_in; ++c)
+        for (int tap = 0; tap < d.kh * d.kw; ++tap) {
+          const size_t src = (size_t)c * d.kh * d.kw + tap;
+          float v;
+          if (bf) {
+            const unsigned u = (unsigned)((const unsigned short*)d.weight)[src] << 16;
+            std::memcpy(&v, &u, 4);
+          } else {
+            v = ((const float*)d.weight)[src];
+          }
+          host[(size_t)tap * d.c_in + c] = v;
+        }
+      LOP_HIP(hipMalloc(&P->d_w[l], host.size() * 4));
+      LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size() * 4, hipMemcpyHostToDevice));
+    }
+    if (d.bias && d.op != LOP_MAXPOOL2D) {
+      LOP_HIP(hipMalloc((void**)&P->d_bias[l], (size_t)d.c_out * 4));
+      LOP_HIP(hipMemcpy(P->d_bias[l], d.bias, (size_t)d.c_out * 4, hipMemcpyHostToDevice));
+    }
+  }
+  return LOP_OK;
+}
+
+void size_scratch(lop_plan_t* P) {
+  const lop::Tables& t = P->t;
+  const int nl = t.n_layers();
+  P->slab_off.assign(t.n_bands, std::vector<size_t>(nl, 0));
+  size_t worst = 0;
+  for (int b = 0; b < t.n_bands; ++b) {
+    size_t off = 0;
+    for (int l = 0; l + 1 < nl; ++l) {  // the last layer writes the caller's output
+      const lop_rows_t r = t.bands[b].need[l + 1];
+      P->slab_off[b][l] = off;
+      if (r.hi > r.lo)
+        off += align_up((size_t)t.in.n * (r.hi - r.lo) * t.row_elems(l) * t.esz(), 256);
+    }
+    worst = off > worst ? off : worst;
+  }
+  P->arena_bytes = worst;
+}
+
+lop::Slab slab_of(const lop_plan_t* P, int band, int tensor, const void* d_in, void* d_out) {
+  const lop::Tables& t = P->t;
+  const int nl = t.n_layers();
+  lop::Slab s;
+  s.n = t.in.n;
+  s.h = t.tensor_h(tensor);
+  if (tensor < 0) {
+    s.ptr = const_cast<void*>(d_in);
+    s.w = t.in.w; s.c = t.in.c; s.row0 = 0; s.rows = t.in.h;
+  } else {
+    s.w = t.layers[tensor].w_out;
+    s.c = t.layers[tensor].d.c_out;
+    if (tensor == nl - 1) {
+      s.ptr = d_out; s.row0 = 0; s.rows = s.h;
+    } else {
+      const lop_rows_t r = t.bands[band].need[tensor + 1];
+      s.ptr = (char*)P->arena + P->slab_off[band][tensor];
+      s.row0 = r.lo; s.rows = r.hi - r.lo;
+    }
+  }
+  return s;
+}
+
+lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in, void* d_out) {
+  const lop::Tables& t = P->t;
+  const lop::LayerInfo& L = t.layers[l];
+  lop::OpLaunch o;
+  o.op = L.d.op;
+  o.dtype = t.in.dtype;
+  o.x = slab_of(P, band, L.d.input_from, d_in, d_out);
+  o.y = slab_of(P, band, l, d_in, d_out);
+  if (L.d.residual_from != LOP_NO_RESIDUAL) o.res = slab_of(P, band, L.d.residual_from, d_in, d_out);
+  o.w = P->d_w[l];
+  o.bias = P->d_bias[l];
+  o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
+  o.ph = L.d.ph; o.pw = L.d.pw; o.dh = L.d.dh; o.dw = L.d.dw;
+  o.act = L.d.act;
+  o.out_lo = t.bands[band].need[l + 1].lo;
+  o.out_hi = t.bands[band].need[l + 1].hi;
+  o.k_pad = P->k_pad[l];
+  return o;
+}
+
+int enqueue_band_kernels(lop_plan_t* P, int band, const void* d_in, void* d_out, hipStream_t cs) {
+  const int nl = P->t.n_layers();
+  for (int l = 0; l < nl; ++l) {
+    const lop_rows_t r = P->t.bands[band].need[l + 1];
+    if (r.hi <= r.lo) continue;
+    const lop::OpLaunch o = make_launch(P, band, l, d_in, d_out);
+    LOP_HIP(lop::launch_op(o, cs));
+  }
+  return LOP_OK;
+}
+
+// Copy the band's final rows of every image to the host buffer (same NHWC layout).
+int enqueue_band_copy(lop_plan_t* P, int band, const void* d_out, void* h_out, hipStream_t s) {
+  const lop::Tables& t = P->t;
+  const lop_rows_t r = t.bands[band].need[t.n_layers()];
+  if (r.hi <= r.lo) return LOP_OK;
+  const lop::LayerInfo& L = t.layers.back();
+  const size_t row_b = (size_t)t.row_elems(t.n_layers() - 1) * t.esz();
+  const size_t img_b = row_b * L.h_out;
+  const size_t off = row_b * r.lo, len = row_b * (r.hi - r.lo);
+  if (t.in.n == 1) {
+    LOP_HIP(hipMemcpyAsync((char*)h_out + off, (const char*)d_out + off, len,
+                           hipMemcpyDeviceToHost, s));
+  } else {
+    LOP_HIP(hipMemcpy2DAsync((char*)h_out + off, img_b, (const char*)d_out + off, img_b, len,
+                             t.in.n, hipMemcpyDeviceToHost, s));
+  }
+  return LOP_OK;
+}
+
+int ensure_timing_events(lop_plan_t* P) {
+  if (!P->ev_c0.empty()) return LOP_OK;
+  const int nb = P->t.n_bands;
+  for (auto* v : {&P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1}) {
+    v->assign(nb, nullptr);
+    for (int b = 0; b < nb; ++b) LOP_HIP(hipEventCreate(&(*v)[b]));
+  }
+  return LOP_OK;
+}
+
+bool band_empty(const lop_plan_t* P, int band) {
+  const lop_rows_t r = P->t.bands[band].need[P->t.n_layers()];
+  return r.hi <= r.lo;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* in, int n_bands,
+             unsigned flags, lop_plan_t** out_plan) {
+  if (!out_plan) return LOP_ERR_INVALID_ARG;
+  *out_plan = nullptr;
+  lop_plan_t* P = new (std::nothrow) lop_plan_t;
+  if (!P) return LOP_ERR_OOM;
+  int rc = lop::build_tables(layers, n_layers, in, n_bands, P->t);
+  if (rc != LOP_OK) { delete P; return rc; }
+  P->flags = flags;
+  size_scratch(P);
+  if (!(flags & LOP_FLAG_PLAN_ONLY)) {
+    auto setup = [&]() -> int {
+      LOP_HIP(hipGetDevice(&P->device));
+      int r = upload_weights(P);
+      if (r != LOP_OK) return r;
+      if (P->arena_bytes) LOP_HIP(hipMalloc(&P->arena, P->arena_bytes));
+      LOP_HIP(hipStreamCreateWithFlags(&P->s_compute, hipStreamNonBlocking));
+      LOP_HIP(hipStreamCreateWithFlags(&P->s_copy, hipStreamNonBlocking));
+      P->ev_done.assign(P->t.n_bands, nullptr);
+      for (auto& e : P->ev_done) LOP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      P->ev_copied.assign(P->t.n_bands, nullptr);
+      P->copied_valid.assign(P->t.n_bands, 0);
+      for (auto& e : P->ev_copied) LOP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      LOP_HIP(hipEventCreateWithFlags(&P->ev_copy_tail, hipEventDisableTiming));
+      return LOP_OK;
+    };
+    rc = setup();
+    if (rc != LOP_OK) { lop_plan_destroy(P); return rc; }
+    P->ready = true;
+  }
+  *out_plan = P;
+  return LOP_OK;
+}
+
+void lop_plan_destroy(lop_plan_t* P) {
+  if (!P) return;
+  if (P->s_compute) (void)hipStreamSynchronize(P->s_compute);
+  if (P->s_copy) (void)hipStreamSynchronize(P->s_copy);
+  for (void* w : P->d_w) if (w) (void)hipFree(w);
+  for (float* b : P->d_bias) if (b) (void)hipFree(b);
+  if (P->arena) (void)hipFree(P->arena);
+  for (auto* v : {&P->ev_done, &P->ev_copied, &P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1})
+    for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
+  if (P->ev_copy_tail) (void)hipEventDestroy(P->ev_copy_tail);
+  if (P->s_compute) (void)hipStreamDestroy(P->s_compute);
+  if (P->s_copy) (void)hipStreamDestroy(P->s_copy);
+  delete P;
+}
+
+int lop_plan_out_desc(const lop_plan_t* P, lop_tensor_desc_t* out) {
+  if (!P || !out) return LOP_ERR_INVALID_ARG;
+  return lop_plan_layer_desc(P, P->t.n_layers() - 1, out);
+}
+
+int lop_plan_layer_desc(const lop_plan_t* P, int layer, lop_tensor_desc_t* out) {
+  if (!P || !out) return LOP_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= P->t.n_layers()) return LOP_ERR_BAND_RANGE;
+  const lop::LayerInfo& L = P->t.layers[layer];
+  *out = {L.n, L.d.c_out, L.h_out, L.w_out, P->t.in.dtype};
+  return LOP_OK;
+}
+
+int lop_plan_n_bands(const lop_plan_t* P) { return P ? P->t.n_bands : LOP_ERR_INVALID_ARG; }
+int lop_plan_n_layers(const lop_plan_t* P) { return P ? P->t.n_layers() : LOP_ERR_INVALID_ARG; }
+
+int lop_plan_band_layer_rows(const lop_plan_t* P, int band, int layer, lop_rows_t* rows) {
+  if (!P || !rows) return LOP_ERR_INVALID_ARG;
+  if (band < 0 || band >= P->t.n_bands || layer < -1 || layer >= P->t.n_layers())
+    return LOP_ERR_BAND_RANGE;
+  lop_rows_t r = P->t.bands[band].need[layer + 1];
+  if (r.hi <= r.lo) r = {0, 0};
+  *rows = r;
+  return LOP_OK;
+}
+
+int lop_plan_band_out_rows(const lop_plan_t* P, int band, lop_rows_t* rows) {
+  if (!P || !rows) return LOP_ERR_INVALID_ARG;
+  if (band < 0 || band >= P->t.n_bands) return LOP_ERR_BAND_RANGE;
+  *rows = P->t.bands[band].need[P->t.n_layers()];  // split intervals keep lo == hi when empty
+  return LOP_OK;
+}
+
+int lop_plan_band_in_rows(const lop_plan_t* P, int band, lop_rows_t* rows) {
+  return lop_plan_band_layer_rows(P, band, -1, rows);
+}
+
+int lop_plan_stats(const lop_plan_t* P, double* useful, double* executed, size_t* scratch) {
+  if (!P) return LOP_ERR_INVALID_ARG;
+  double u = 0, e = 0;
+  for (int l = 0; l < P->t.n_layers(); ++l) {
+    u += P->t.layer_flop(l, P->t.layers[l].h_out);
+    for (int b = 0; b < P->t.n_bands; ++b) {
+      const lop_rows_t r = P->t.bands[b].need[l + 1];
+      if (r.hi > r.lo) e += P->t.layer_flop(l, r.hi - r.lo);
+    }
+  }
+  if (useful) *useful = u;
+  if (executed) *executed = e;
+  if (scratch) *scratch = P->arena_bytes;
+  return LOP_OK;
+}
+
+int lop_plan_layer_work(const lop_plan_t* P, int band, int layer, double* flop, double* bytes) {
+  if (!P) return LOP_ERR_INVALID_ARG;
+  if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
+    return LOP_ERR_BAND_RANGE;
+  const lop_rows_t r = P->t.bands[band].need[layer + 1];
+  if (flop) *flop = r.hi > r.lo ? P->t.layer_flop(layer, r.hi - r.lo) : 0.0;
+  if (bytes) *bytes = P->t.layer_bytes(band, layer);
+  return LOP_OK;
+}
+
+int lop_run_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h_out,
+                 void* compute_stream, void* copy_stream) {
+  if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
+  if (band < 0 || band >= P->t.n_bands) return LOP_ERR_BAND_RANGE;
+  if (!P->ready) return LOP_ERR_NOT_READY;
+  if (band_empty(P, band)) return LOP_OK;
+  hipStream_t cs = compute_stream ? (hipStream_t)compute_stream : P->s_compute;
+  hipStream_t ds = copy_stream ? (hipStream_t)copy_stream : P->s_copy;
+  if (compute_stream) P->last_user_stream = cs;
+  // the band's rows of d_out may still be in flight to the host from an earlier call
+  if (P->copied_valid[band]) LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[band], 0));
+  int rc = enqueue_band_kernels(P, band, d_in, d_out, cs);
+  if (rc != LOP_OK) return rc;
+  if (h_out && !(P->flags & LOP_FLAG_NO_D2H)) {
+    LOP_HIP(hipEventRecord(P->ev_done[band], cs));
+    LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[band], 0));
+    rc = enqueue_band_copy(P, band, d_out, h_out, ds);
+    if (rc != LOP_OK) return rc;
+    LOP_HIP(hipEventRecord(P->ev_copied[band], ds));
+    P->copied_valid[band] = 1;
+  }
+  return rc;
+}
+
+int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, void* compute_stream,
+                  lop_timing_t* timing) {
+  if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
+  if (!P->ready) return LOP_ERR_NOT_READY;
+  hipStream_t cs = compute_stream ? (hipStream_t)compute_stream : P->s_compute;
+  hipStream_t ds = P->s_copy;
+  if (compute_stream) P->last_user_stream = cs;
+  const bool copy = h_out && !(P->flags & LOP_FLAG_NO_D2H);
+  const int nb = P->t.n_bands;
+  if (timing) {
+    int rc = ensure_timing_events(P);
+    if (rc != LOP_OK) return rc;
+    LOP_HIP(hipStreamSynchronize(cs));
+    LOP_HIP(hipStreamSynchronize(ds));
+  }
+  const auto t0 = std::chrono::steady_clock::now();
+  for (int b = 0; b < nb; ++b) {
+    if (band_empty(P, b)) continue;
+    if (P->copied_valid[b]) LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[b], 0));
+    if (timing) LOP_HIP(hipEventRecord(P->ev_c0[b], cs));
+    int rc = enqueue_band_kernels(P, b, d_in, d_out, cs);
+    if (rc != LOP_OK) return rc;
+    if (timing) LOP_HIP(hipEventRecord(P->ev_c1[b], cs));
+    if (copy) {
+      LOP_HIP(hipEventRecord(P->ev_done[b], cs));
+      LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[b], 0));
+      if (timing) LOP_HIP(hipEventRecord(P->ev_d0[b], ds));
+      rc = enqueue_band_copy(P, b, d_out, h_out, ds);
+      if (rc != LOP_OK) return rc;
+      if (timing) LOP_HIP(hipEventRecord(P->ev_d1[b], ds));
+      LOP_HIP(hipEventRecord(P->ev_copied[b], ds));
+      P->copied_valid[b] = 1;
+    }
+  }
+  if (!timing) return LOP_OK;
+  LOP_HIP(hipStreamSynchronize(cs));
+  LOP_HIP(hipStreamSynchronize(ds));
+  const auto t1 = std::chrono::steady_clock::now();
+  std::memset(timing, 0, sizeof(*timing));
+  timing->n_bands = nb;
+  timing->wall_ms = std::chrono::duration<float, std::milli>(t1 - t0).count();
+  int first = -1, last = -1;
+  for (int b = 0; b < nb; ++b) {
+    if (band_empty(P, b)) continue;
+    if (first < 0) first = b;
+    last = b;
+    LOP_HIP(hipEventElapsedTime(&timing->band_compute_ms[b], P->ev_c0[b], P->ev_c1[b]));
+    if (copy) {
+      LOP_HIP(hipEventElapsedTime(&timing->band_copy_ms[b], P->ev_d0[b], P->ev_d1[b]));
+      timing->copy_ms += timing->band_copy_ms[b];
+    }
+  }
+  if (first >= 0) LOP_HIP(hipEventElapsedTime(&timing->compute_ms, P->ev_c0[first], P->ev_c1[last]));
+  return LOP_OK;
+}
+
+int lop_synchronize(lop_plan_t* P) {
+  if (!P) return LOP_ERR_INVALID_ARG;
+  if (!P->ready) return LOP_ERR_NOT_READY;
+  if (P->last_user_stream) LOP_HIP(hipStreamSynchronize(P->last_user_stream));
+  LOP_HIP(hipStreamSynchronize(P->s_compute));
+  LOP_HIP(hipStreamSynchronize(P->s_copy));
+  return LOP_OK;
+}
+
+int lop_time_layer(lop_plan_t* P, int band, int layer, const void* d_in, void* d_out, int iters,
+                   float* ms_per_launch) {
+  if (!P || !d_in || !d_out || !ms_per_launch || iters < 1) return LOP_ERR_INVALID_ARG;
+  if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
+    return LOP_ERR_BAND_RANGE;
+  if (!P->ready) return LOP_ERR_NOT_READY;
+  *ms_per_launch = 0.f;
+  const lop_rows_t r = P->t.bands[band].need[layer + 1];
+  if (r.hi <= r.lo) return LOP_OK;
+  int rc = ensure_timing_events(P);
+  if (rc != LOP_OK) return rc;
+  const lop::OpLaunch o = make_launch(P, band, layer, d_in, d_out);
+  hipStream_t cs = P->s_compute;
+  LOP_HIP(lop::launch_op(o, cs));  // warm-up
+  LOP_HIP(hipEventRecord(P->ev_c0[0], cs));
+  for (int i = 0; i < iters; ++i) LOP_HIP(lop::launch_op(o, cs));
+  LOP_HIP(hipEventRecord(P->ev_c1[0], cs));
+  LOP_HIP(hipStreamSynchronize(cs));
+  float ms = 0.f;
+  LOP_HIP(hipEventElapsedTime(&ms, P->ev_c0[0], P->ev_c1[0]));
+  *ms_per_launch = ms / iters;
+  return LOP_OK;
+}
+
+const char* lop_strerror(int code) {
+  switch (code) {
+    case LOP_OK: return "ok";
+    case LOP_ERR_INVALID_ARG: return "invalid argument";
+    case LOP_ERR_UNSUPPORTED: return "unsupported operator, type or parameter";
+    case LOP_ERR_SHAPE: return "shape mismatch";
+    case LOP_ERR_BAND_RANGE: return "band or layer index out of range";
+    case LOP_ERR_OOM: return "out of memory";
+    case LOP_ERR_HIP: return "HIP runtime error";
+    case LOP_ERR_NOT_READY: return "plan holds no device state (plan-only)";
+    default: return "unknown error";
+  }
+}
+
+int lop_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

@@ -1,0 +1,176 @@
+// Bandwidth-bound local operators on a row interval: depthwise convolution, max pooling
+// and the stand-alone element-wise operator (Intra-DP Sec. IV-A: block-wise and
+// element-wise local operators). NHWC: a thread owns one 16-byte channel vector of one
+// output pixel, consecutive threads own consecutive channel vectors, so every load and
+// store of a wavefront is one contiguous run of channels. fp32 math, one rounding.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+#include "lop.h"
+
+namespace lop {
+namespace {
+
+struct RowParams {
+  const void* x;
+  void* y;
+  const void* res;
+  const float* w;  // depthwise: [kh*kw][C] fp32
+  const float* bias;
+  int x_row0, x_rows, W, C;
+  int y_row0, y_rows, W_out;
+  int r_row0, r_rows;
+  int kh, kw, sh, sw, ph, pw, dh, dw;
+  int act, out_lo, R, N;
+  long total;  // N * R * W_out * (C / VEC)
+};
+
+__device__ __forceinline__ float act_f(float v, int act) {
+  if (act == LOP_ACT_RELU) return fmaxf(v, 0.f);
+  if (act == LOP_ACT_RELU6) return fminf(fmaxf(v, 0.f), 6.f);
+  return v;
+}
+
+template <typename T, int VEC> struct Vec;  // VEC elements of T <-> fp32 registers
+
+template <> struct Vec<float, 4> {
+  static __device__ __forceinline__ void load(const float* p, float* v) {
+    const float4 t = *(const float4*)p; v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float* v) {
+    *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct Vec<float, 1> {
+  static __device__ __forceinline__ void load(const float* p, float* v) { v[0] = *p; }
+  static __device__ __forceinline__ void store(float* p, const float* v) { *p = v[0]; }
+};
+template <> struct Vec<__bf16, 8> {
+  static __device__ __forceinline__ void load(const __bf16* p, float* v) {
+    const uint4 t = *(const uint4*)p;
+    const unsigned u[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(u[i] << 16);
+      v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(__bf16* p, const float* v) {
+    alignas(16) __bf16 o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (__bf16)v[i];
+    *(uint4*)p = *(const uint4*)o;
+  }
+};
+template <> struct Vec<__bf16, 1> {
+  static __device__ __forceinline__ void load(const __bf16* p, float* v) { v[0] = (float)*p; }
+  static __device__ __forceinline__ void store(__bf16* p, const float* v) { *p = (__bf16)v[0]; }
+};
+
+template <int VEC>
+__device__ __forceinline__ void load_f32(const float* p, float* v) {
+  if constexpr (VEC >= 4) {
+#pragma unroll
+    for (int i = 0; i < VEC; i += 4) {
+      const float4 t = *(const float4*)(p + i);
+      v[i] = t.x; v[i + 1] = t.y; v[i + 2] = t.z; v[i + 3] = t.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = p[i];
+  }
+}
+
+// OP: 0 depthwise conv, 1 max pool, 2 element-wise
+template <typename T, int VEC, int OP>
+__global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= p.total) return;
+  const int cv = p.C / VEC;
+  const int c = (int)(gid % cv) * VEC;
+  long t = gid / cv;
+  const int ow = (int)(t % p.W_out);
+  t /= p.W_out;
+  const int r = (int)(t % p.R), n = (int)(t / p.R);
+  const int oh = p.out_lo + r;
+  const T* __restrict__ xg = (const T*)p.x;
+  float acc[VEC];
+  if (OP == 2) {
+    Vec<T, VEC>::load(xg + ((size_t)(n * p.x_rows + oh - p.x_row0) * p.W + ow) * p.C + c, acc);
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = OP == 1 ? -INFINITY : 0.f;
+    const int ih0 = oh * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+    for (int a = 0; a < p.kh; ++a) {
+      const int ih = ih0 + a * p.dh;
+      if (ih < p.x_row0 || ih >= p.x_row0 + p.x_rows) continue;
+      for (int b = 0; b < p.kw; ++b) {
+        const int iw = iw0 + b * p.dw;
+        if (iw < 0 || iw >= p.W) continue;
+        float v[VEC];
+        Vec<T, VEC>::load(xg + ((size_t)(n * p.x_rows + ih - p.x_row0) * p.W + iw) * p.C + c, v);
+        if (OP == 1) {
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) acc[i] = fmaxf(acc[i], v[i]);
+        } else {
+          float wv[VEC];
+          load_f32<VEC>(p.w + (size_t)(a * p.kw + b) * p.C + c, wv);
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) acc[i] = fmaf(v[i], wv[i], acc[i]);
+        }
+      }
+    }
+  }
+  if (OP != 1) {
+    if (p.bias) {
+      float bv[VEC];
+      load_f32<VEC>(p.bias + c, bv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += bv[i];
+    }
+    if (p.res) {
+      float rv[VEC];
+      Vec<T, VEC>::load((const T*)p.res +
+                            ((size_t)(n * p.r_rows + oh - p.r_row0) * p.W_out + ow) * p.C + c, rv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += rv[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = act_f(acc[i], p.act);
+  }
+  Vec<T, VEC>::store((T*)p.y + ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C + c, acc);
+}
+
+template <typename T, int VEC>
+hipError_t launch_rowwise(RowParams& p, int op, hipStream_t s) {
+  p.total = (long)p.N * p.R * p.W_out * (p.C / VEC);
+  if (p.total <= 0) return hipSuccess;
+  const unsigned grid = (unsigned)((p.total + 255) / 256);
+  if (op == LOP_DWCONV2D)
+    hipLaunchKernelGGL((rowwise_kernel<T, VEC, 0>), dim3(grid), dim3(256), 0, s, p);
+  else if (op == LOP_MAXPOOL2D)
+    hipLaunchKernelGGL((rowwise_kernel<T, VEC, 1>), dim3(grid), dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((rowwise_kernel<T, VEC, 2>), dim3(grid), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream) {
+  RowParams p;
+  p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = (const float*)L.w; p.bias = L.bias;
+  p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.W = L.x.w; p.C = L.x.c;
+  p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w;
+  p.r_row0 = L.res.row0; p.r_rows = L.res.rows;
+  p.kh = L.kh; p.kw = L.kw; p.sh = L.sh; p.sw = L.sw; p.ph = L.ph; p.pw = L.pw;
+  p.dh = L.dh; p.dw = L.dw;
+  p.act = L.act; p.out_lo = L.out_lo; p.R = L.out_hi - L.out_lo; p.N = L.x.n;
+  if (L.dtype == LOP_BF16)
+    return p.C % 8 == 0 ? launch_rowwise<__bf16, 8>(p, L.op, stream)
+                        : launch_rowwise<__bf16, 1>(p, L.op, stream);
+  return p.C % 4 == 0 ? launch_rowwise<float, 4>(p, L.op, stream)
+                      : launch_rowwise<float, 1>(p, L.op, stream);
+}
+
+}  // namespace lop

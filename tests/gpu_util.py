@@ -1,0 +1,53 @@
+"""Helpers for the GPU parity tests: move seeded host tensors to the device in the
+library's layout (NHWC, storage type), run the C-ABI path, bring the result back NCHW."""
+import numpy as np
+import torch
+
+from paper_2507_05829_amd import lop
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # max |gpu - oracle| / max |oracle|
+
+
+def to_device_nhwc(x_nchw: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(x_nchw.transpose(0, 2, 3, 1)))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)           # exact: values are bf16-representable
+    t = t.cuda()
+    torch.cuda.synchronize()
+    return t
+
+
+def empty_out(shape_nchw, dtype: str, pinned: bool = False) -> torch.Tensor:
+    n, c, h, w = shape_nchw
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    if pinned:
+        t = torch.empty((n, h, w, c), dtype=td, pin_memory=True)
+    else:
+        t = torch.empty((n, h, w, c), dtype=td, device="cuda")
+    t.fill_(float("nan"))
+    torch.cuda.synchronize()
+    return t
+
+
+def to_nchw(t: torch.Tensor) -> np.ndarray:
+    return t.float().cpu().numpy().transpose(0, 3, 1, 2)
+
+
+def run_gpu(chain, tensors, n_bands=None, use_host=True, flags=0):
+    """Whole chain through lop_run_chain; returns (device result, host result) as NCHW."""
+    plan = lop.Plan(chain, tensors, n_bands, flags)
+    try:
+        d_in = to_device_nhwc(tensors.x, chain.dtype)
+        d_out = empty_out(plan.out_shape(), chain.dtype)
+        h_out = empty_out(plan.out_shape(), chain.dtype, pinned=True) if use_host else None
+        torch.cuda.synchronize()
+        plan.run_chain(d_in, d_out, h_out)
+        plan.synchronize()
+        return to_nchw(d_out), (to_nchw(h_out) if use_host else None)
+    finally:
+        plan.destroy()
+
+
+def rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    scale = float(np.abs(want).max())
+    return float(np.abs(got.astype(np.float64) - want.astype(np.float64)).max()) / max(scale, 1e-30)

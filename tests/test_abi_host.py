@@ -1,0 +1,138 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, its
+integer planner agrees bit for bit with the planner oracle, and argument errors come back
+as the documented codes. No kernel is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import planner as oplan
+from paper_2507_05829_amd import lop
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "lop.h")).read()
+    declared = set(re.findall(r"LOP_API\s+[\w\s\*]+?\b(lop_\w+)\s*\(", hdr))
+    assert declared == set(lop.EXPORTS)
+    lib = ctypes.CDLL(lop.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_covers_codes():
+    texts = {lop.lop_strerror(c) for c in range(0, -8, -1)}
+    assert len(texts) == 8 and "unknown error" not in texts
+    assert lop.lop_strerror(-99) == "unknown error"
+
+
+@pytest.mark.parametrize("name", list(workloads.CONFIGS))
+def test_planner_matches_oracle_bit_exact(name):
+    chain = workloads.CONFIGS[name]()
+    plan = lop.Plan(chain)                         # plan-only: no GPU needed
+    shapes = oplan.infer_shapes(chain)
+    assert plan.out_shape() == shapes[-1]
+    for l, s in enumerate(shapes):
+        assert plan.layer_shape(l) == s
+    want = oplan.plan(chain)
+    split = oplan.split_rows(shapes[-1][2], chain.n_bands)
+    for b in range(chain.n_bands):
+        assert plan.band_out_rows(b) == split[b]
+        for t in range(-1, len(chain.layers)):
+            got = plan.band_layer_rows(b, t)
+            exp = want[b][t]
+            assert got == ((0, 0) if exp is None else exp), (name, b, t)
+        assert plan.band_in_rows(b) == plan.band_layer_rows(b, -1)
+    u, e, scratch = plan.stats()
+    ou, oe = oplan.flop_counts(chain)
+    assert u == ou and e == oe
+    assert scratch > 0
+
+
+def test_planner_matches_oracle_random_chains():
+    from test_oracle_planner import _random_chain
+    rng = np.random.default_rng(5)
+    done = 0
+    while done < 100:
+        chain = _random_chain(rng)
+        if chain is None or any(L.op == "maxpool" and L.p[0] >= L.k[0] for L in chain.layers):
+            continue
+        done += 1
+        plan = lop.Plan(chain)
+        want = oplan.plan(chain)
+        for b in range(chain.n_bands):
+            for t in range(-1, len(chain.layers)):
+                exp = want[b][t]
+                assert plan.band_layer_rows(b, t) == ((0, 0) if exp is None else exp)
+
+
+def test_layer_work_counts():
+    chain = workloads.tiny_chain()
+    plan = lop.Plan(chain)
+    # band 1, layer 0: rows (7,17) = 10 rows out, reads rows (6,18) = 12 rows in
+    flop, byts = plan.layer_work(1, 0)
+    assert flop == 2 * 10 * 32 * 16 * 16 * 9
+    assert byts == 4 * (12 * 32 * 16 + 10 * 32 * 16) + 4 * 16 * 16 * 9
+
+
+def _desc(n=1, c=4, h=8, w=8, dt=lop.LOP_F32):
+    return lop.lop_tensor_desc_t(n, c, h, w, dt)
+
+
+def _layer(op=lop.LOP_CONV2D, c_in=4, c_out=4, k=3, s=1, p=1, d=1, act=0, src=-1, res=-2):
+    return lop.lop_layer_t(op, c_in, c_out, k, k, s, s, p, p, d, d, act, src, res, None, None)
+
+
+def _code(layers, desc=None, n_bands=2, flags=lop.LOP_FLAG_PLAN_ONLY):
+    try:
+        h = lop.lop_plan(layers, desc or _desc(), n_bands, flags)
+    except lop.LopError as e:
+        return e.code
+    lop.lop_plan_destroy(h)
+    return 0
+
+
+def test_error_codes():
+    assert _code([_layer()]) == 0
+    assert _code([_layer()], n_bands=0) == lop.LOP_ERR_INVALID_ARG
+    assert _code([_layer()], n_bands=65) == lop.LOP_ERR_INVALID_ARG
+    assert _code([_layer()], desc=_desc(h=0)) == lop.LOP_ERR_INVALID_ARG
+    assert _code([_layer(src=0)]) == lop.LOP_ERR_INVALID_ARG          # forward reference
+    assert _code([_layer(s=0)]) == lop.LOP_ERR_INVALID_ARG
+    assert _code([_layer(op=9)]) == lop.LOP_ERR_UNSUPPORTED           # e.g. a global operator
+    assert _code([_layer()], desc=_desc(dt=5)) == lop.LOP_ERR_UNSUPPORTED
+    assert _code([_layer(c_in=3)]) == lop.LOP_ERR_SHAPE               # channel mismatch
+    assert _code([_layer(k=11, p=0)]) == lop.LOP_ERR_SHAPE            # window larger than input
+    assert _code([_layer(op=lop.LOP_DWCONV2D, c_out=8)]) == lop.LOP_ERR_SHAPE
+    assert _code([_layer(s=2), _layer(src=0, res=-1)]) == lop.LOP_ERR_SHAPE   # residual shape
+    assert _code([_layer(op=lop.LOP_MAXPOOL2D, act=1)]) == lop.LOP_ERR_INVALID_ARG
+    assert _code([_layer(op=lop.LOP_MAXPOOL2D, k=2, p=2)]) == lop.LOP_ERR_UNSUPPORTED
+    # a plan that needs weights but has none
+    assert _code([_layer()], flags=0) in (lop.LOP_ERR_INVALID_ARG, lop.LOP_ERR_HIP)
+
+
+def test_band_range_and_not_ready():
+    h = lop.lop_plan([_layer()], _desc(), 2, lop.LOP_FLAG_PLAN_ONLY)
+    try:
+        with pytest.raises(lop.LopError) as e:
+            lop.lop_plan_band_out_rows(h, 2)
+        assert e.value.code == lop.LOP_ERR_BAND_RANGE
+        with pytest.raises(lop.LopError) as e:
+            lop.lop_plan_band_layer_rows(h, 0, 1)
+        assert e.value.code == lop.LOP_ERR_BAND_RANGE
+        with pytest.raises(lop.LopError) as e:
+            lop.lop_run_band(h, 0, 1, 1)          # dummy non-null addresses, never touched
+        assert e.value.code == lop.LOP_ERR_NOT_READY
+        with pytest.raises(lop.LopError) as e:
+            lop.lop_run_chain(h, 1, 1)
+        assert e.value.code == lop.LOP_ERR_NOT_READY
+        with pytest.raises(lop.LopError) as e:
+            lop.lop_run_chain(h, None, 1)
+        assert e.value.code == lop.LOP_ERR_INVALID_ARG
+    finally:
+        lop.lop_plan_destroy(h)
+    lop.lop_plan_destroy(None)                   # destroying NULL is a no-op
