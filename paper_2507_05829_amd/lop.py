@@ -15,6 +15,10 @@ from ctypes import POINTER, Structure, byref, c_char_p, c_double, c_float, c_int
 from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
+# torch ships its own HIP runtime; it has to be in the process before liblop.so is
+# loaded so that both resolve to the same runtime (device pointers and streams are
+# shared between them).
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblop.so")
