@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Throughput of the banded local-operator chain on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch: plan-driven kernels for every
+band and layer plus the per-band device-to-host copies, pipelined (band b's copy under band
+b+1's kernels, and the last copy under the next step's first band). Inputs are resident in
+HBM before the timed region. Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_f32": 157.3, "mfma_bf16": 2500.0, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet18")
+    ap.add_argument("--also", default="tiny,vgg16,detector720p,mbv2",
+                    help="comma list of further workloads reported under 'also' (fewer steps)")
+    ap.add_argument("--bands", type=int, default=None, help="override the workload's band count")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--profile-iters", type=int, default=10)
+    return ap.parse_args()
+
+
+def device_tensors(torch, chain, tensors, plan, n_buf=2):
+    import numpy as np
+    x = torch.from_numpy(np.ascontiguousarray(tensors.x.transpose(0, 2, 3, 1)))
+    td = torch.bfloat16 if chain.dtype == "bf16" else torch.float32
+    d_in = x.to(td).cuda()
+    n, c, h, w = plan.out_shape()
+    d_out = [torch.zeros((n, h, w, c), dtype=td, device="cuda") for _ in range(n_buf)]
+    h_out = [torch.zeros((n, h, w, c), dtype=td, pin_memory=True) for _ in range(n_buf)]
+    torch.cuda.synchronize()
+    return d_in, d_out, h_out
+
+
+def timed_steps(torch, plan, d_in, d_out, h_out, steps, warmup, copy=True):
+    """Steady state: `steps` chains back to back, double-buffered outputs."""
+    for i in range(warmup):
+        plan.run_chain(d_in, d_out[i % 2], h_out[i % 2] if copy else None)
+    plan.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        plan.run_chain(d_in, d_out[i % 2], h_out[i % 2] if copy else None)
+    plan.synchronize()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def timed_copies(torch, plan, d_out, h_out, steps, warmup):
+    for i in range(warmup):
+        plan.copy_chain(d_out[i % 2], h_out[i % 2])
+    plan.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        plan.copy_chain(d_out[i % 2], h_out[i % 2])
+    plan.synchronize()
+    return time.perf_counter() - t0
+
+
+def kernel_table(plan, d_in, d_out, iters):
+    """Per kernel variant: launches per step, mean duration, algorithmic work."""
+    ms = plan.profile_chain(d_in, d_out, iters)
+    groups = {}
+    for b in range(plan.n_bands):
+        for l in range(plan.n_layers):
+            name = plan.layer_kernel(b, l)
+            if not name:
+                continue
+            flop, byts = plan.layer_work(b, l)
+            g = groups.setdefault(name, dict(name=name, launches=0, ms=0.0, flop=0.0, bytes=0.0))
+            g["launches"] += 1
+            g["ms"] += float(ms[b, l])
+            g["flop"] += flop
+            g["bytes"] += byts
+    out = []
+    for g in sorted(groups.values(), key=lambda g: -g["ms"]):
+        t = g["ms"] * 1e-3
+        out.append(dict(name=g["name"], launches=g["launches"], total_ms=round(g["ms"], 4),
+                        avg_us=round(g["ms"] * 1e3 / g["launches"], 3),
+                        tflops=round(g["flop"] / t / 1e12, 3) if t > 0 else None,
+                        gbs=round(g["bytes"] / t / 1e9, 1) if t > 0 else None,
+                        flop_per_launch=g["flop"] / g["launches"],
+                        bytes_per_launch=g["bytes"] / g["launches"]))
+    return out
+
+
+def roofline_of(k, dtype):
+    """Bound of a kernel variant: matrix cores for the dense convolution unless its
+    arithmetic intensity is below the ridge point; HBM for the row-wise kernels."""
+    mf_peak = PEAK["mfma_bf16"] if dtype == "bf16" else PEAK["mfma_f32"]
+    ai = k["flop_per_launch"] / max(k["bytes_per_launch"], 1.0)
+    ridge = mf_peak * 1e12 / (PEAK["hbm"] * 1e9)
+    if k["name"].startswith("conv_igemm") and ai >= ridge:
+        a = k["tflops"]
+        return dict(bound="mfma", achieved=a, peak=mf_peak, unit="TFLOP/s",
+                    frac=round(a / mf_peak, 4), traffic=None, kernel=k["name"],
+                    avg_us=k["avg_us"], launches_per_step=k["launches"])
+    a = k["gbs"]
+    return dict(bound="hbm", achieved=a, peak=PEAK["hbm"], unit="GB/s",
+                frac=round(a / PEAK["hbm"], 4), traffic=None, kernel=k["name"],
+                avg_us=k["avg_us"], launches_per_step=k["launches"])
+
+
+def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters):
+    chain = workloads.CONFIGS[name]()
+    if bands:
+        chain.n_bands = bands
+    tensors = workloads.make_tensors(chain)
+    plan = lop.Plan(chain, tensors)
+    d_in, d_out, h_out = device_tensors(torch, chain, tensors, plan)
+    n_img = chain.in_shape[0]
+    useful, executed, scratch = plan.stats()
+
+    t_c = timed_steps(torch, plan, d_in, d_out, h_out, steps, warmup, copy=True)
+    t_a = timed_steps(torch, plan, d_in, d_out, h_out, steps, min(warmup, 5), copy=False)
+    t_b = timed_copies(torch, plan, d_out, h_out, steps, min(warmup, 5))
+    hidden_steady = 1.0 - max(0.0, t_c - t_a) / t_b
+
+    # single request: one chain at a time, host clock around launch .. last byte
+    lat, lat_nc, cp = [], [], []
+    for i in range(min(steps, 30)):
+        tm = plan.run_chain(d_in, d_out[0], h_out[0], timing=True)
+        lat.append(tm.wall_ms)
+        cp.append(tm.copy_ms)
+        tm = plan.run_chain(d_in, d_out[0], None, timing=True)
+        lat_nc.append(tm.wall_ms)
+    lat.sort(); lat_nc.sort(); cp.sort()
+    med = lambda v: v[len(v) // 2]
+    hidden_single = 1.0 - max(0.0, med(lat) - med(lat_nc)) / max(med(cp), 1e-9)
+
+    kernels = kernel_table(plan, d_in, d_out[0], profile_iters)
+    res = dict(
+        workload=name, dtype=chain.dtype, n_bands=plan.n_bands, n_layers=plan.n_layers,
+        images_per_s=n_img * steps / t_c, ms_per_step=t_c / steps * 1e3,
+        ms_per_step_no_d2h=t_a / steps * 1e3, ms_copies_only=t_b / steps * 1e3,
+        d2h_hidden_steady=round(hidden_steady, 4), d2h_hidden_single=round(hidden_single, 4),
+        d2h_hidden_single_bound=round((plan.n_bands - 1) / plan.n_bands, 4),
+        latency_ms_single=round(med(lat), 4), latency_ms_single_no_d2h=round(med(lat_nc), 4),
+        useful_gflop=round(useful / 1e9, 4), executed_over_useful=round(executed / useful, 4),
+        useful_tflops=round(useful * steps / t_c / 1e12, 3),
+        executed_tflops=round(executed * steps / t_c / 1e12, 3),
+        scratch_mb=round(scratch / 2 ** 20, 2),
+        kernels=[{k: v for k, v in kk.items() if not k.endswith("_per_launch")} for kk in kernels],
+    )
+    roof = roofline_of(kernels[0], chain.dtype)
+    plan.destroy()
+    return chain, tensors, res, roof
+
+
+def cpu_baseline(chain, tensors, budget_s):
+    """The oracle as it stands, on the host cores, unbanded whole images."""
+    from oracle import reference
+    reference.build()
+    times = []
+    t_all = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        reference.run_chain(chain, tensors)
+        times.append(time.perf_counter() - t0)
+        if len(times) >= 3 or time.perf_counter() - t_all > budget_s:
+            break
+    times.sort()
+    t = times[len(times) // 2]
+    return dict(value=round(chain.in_shape[0] / t, 4), unit="images/s",
+                cores=reference.num_threads(), kind="oracle",
+                sample=f"{len(times)} whole unbanded {chain.name} image(s) "
+                       f"{'x'.join(map(str, chain.in_shape))}, median {t:.3f} s each")
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py measures one GPU only: the path has no multi-GPU part "
+              "(bands would shard with no exchange); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads
+    from paper_2507_05829_amd import lop
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (there is no CPU fallback)", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    chain, tensors, res, roof = run_workload(torch, lop, workloads, a.workload, a.steps, a.warmup,
+                                             a.bands, a.profile_iters)
+    also = []
+    for name in [s for s in a.also.split(",") if s and s != a.workload]:
+        heavy = name == "mbv2"
+        _, _, r, rf = run_workload(torch, lop, workloads, name, 10 if heavy else max(a.steps // 4, 10),
+                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters)
+        r["roofline"] = rf
+        also.append(r)
+
+    line = {
+        "metric": "images/sec for banded conv chain (steady state, per-band D2H pipelined)",
+        "value": round(res["images_per_s"], 3), "unit": "images/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(res["ms_per_step"], 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if chain.dtype == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload} {'x'.join(map(str, chain.in_shape))} "
+                               f"{chain.dtype}, {res['n_bands']} row bands, {res['n_layers']} layers",
+                   "images_per_step": chain.in_shape[0], "independent_bands": True},
+        "roofline": roof,
+        "detail": res,
+        "also": also,
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(chain, tensors, a.cpu_seconds)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

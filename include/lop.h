@@ -148,6 +148,20 @@ LOP_API int lop_synchronize(lop_plan_t* plan);
 LOP_API int lop_time_layer(lop_plan_t* plan, int band, int layer, const void* d_in, void* d_out,
                    int iters, float* ms_per_launch);
 
+/* Name of the kernel variant that runs `layer` for `band` (empty string for an empty
+ * interval), copied into name[size]. Measurement aid: lets a profile be grouped by kernel. */
+LOP_API int lop_plan_layer_kernel(const lop_plan_t* plan, int band, int layer, char* name, size_t size);
+
+/* Run the whole chain `iters` times on the plan's compute stream with an event before and
+ * after every kernel and write the mean milliseconds of each (band, layer) launch to
+ * layer_ms[band * n_layers + layer] (host, n_bands * n_layers floats). No host copies.
+ * Synchronous. Measurement aid. */
+LOP_API int lop_profile_chain(lop_plan_t* plan, const void* d_in, void* d_out, int iters, float* layer_ms);
+
+/* Enqueue only the bands' device-to-host copies, back to back on the plan's copy stream
+ * (the transmission leg alone, to measure how much of it the pipelined run hides). */
+LOP_API int lop_copy_chain(lop_plan_t* plan, const void* d_out, void* h_out);
+
 LOP_API void lop_plan_destroy(lop_plan_t* plan);
 LOP_API const char* lop_strerror(int code);
 LOP_API int lop_last_hip_error(void); /* raw hipError_t behind this thread's last LOP_ERR_HIP */

@@ -27,6 +27,9 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #define ORACLE_OK 0
 #define ORACLE_ERR_SLAB (-1)
@@ -34,6 +37,15 @@
 
 enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_RELU6 = 2 };
 enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+/* Threads the parallel loops below will use (for reporting next to timings). */
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
 
 /* Round a double to the nearest bfloat16 value (8 significant bits, float32
  * exponent range), ties to even; the result is returned as a double that is

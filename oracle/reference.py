@@ -58,6 +58,10 @@ def _fp(a: Optional[np.ndarray]):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
 def round_bf16(v: float) -> float:
     return lib().oracle_round_bf16(float(v))
 

@@ -275,30 +275,33 @@ hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s) {
   return hipGetLastError();
 }
 
+enum Shape { S128x128, S128x64, S64x64, S128x32 };
+
+// Largest tile that still gives every compute unit a workgroup; small layers fall
+// through to smaller tiles.
+Shape pick_shape(const ConvParams& p) {
+  auto blocks = [&](int bm, int bn) {
+    return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn);
+  };
+  if (p.C_out > 64 && blocks(128, 128) >= 256) return S128x128;
+  if (p.C_out > 32 && blocks(128, 64) >= 256) return S128x64;
+  if (p.C_out > 32) return S64x64;
+  return S128x32;
+}
+
 template <typename T>
 hipError_t launch_typed(const ConvParams& p, hipStream_t s) {
   constexpr int KE = 16 / (int)sizeof(T);
   const bool vec_a = p.C_in % KE == 0;
-  auto blocks = [&](int bm, int bn) {
-    return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn);
-  };
-  // Largest tile that still gives every compute unit a workgroup; small layers fall
-  // through to smaller tiles.
-  if (p.C_out > 64 && blocks(128, 128) >= 256) return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s);
-  if (p.C_out > 32 && blocks(128, 64) >= 256) return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s);
-  if (p.C_out > 32) return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s);
-  return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s);
+  switch (pick_shape(p)) {
+    case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s);
+    case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s);
+    case S64x64: return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s);
+    default: return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s);
+  }
 }
 
-}  // namespace
-
-int conv_k_pad(int c_in, int kh, int kw, int dtype) {
-  const int bke = dtype == LOP_BF16 ? 32 : 16;
-  const int k = c_in * kh * kw;
-  return (k + bke - 1) / bke * bke;
-}
-
-hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream) {
+ConvParams make_params(const OpLaunch& L) {
   ConvParams p;
   p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = L.w; p.bias = L.bias;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.H = L.x.h; p.W = L.x.w; p.C_in = L.x.c;
@@ -310,8 +313,37 @@ hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream) {
   p.M = p.N * p.R * p.W_out;
   p.K = L.x.c * L.kh * L.kw;
   p.k_pad = L.k_pad;
+  return p;
+}
+
+}  // namespace
+
+int conv_k_pad(int c_in, int kh, int kw, int dtype) {
+  const int bke = dtype == LOP_BF16 ? 32 : 16;
+  const int k = c_in * kh * kw;
+  return (k + bke - 1) / bke * bke;
+}
+
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream) {
+  const ConvParams p = make_params(L);
   if (p.M <= 0) return hipSuccess;
   return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, stream) : launch_typed<float>(p, stream);
+}
+
+const char* conv_igemm_name(const OpLaunch& L) {
+  const ConvParams p = make_params(L);
+  const bool bf = L.dtype == LOP_BF16;
+  const bool vec = p.C_in % (bf ? 8 : 4) == 0;
+  static const char* names[2][2][4] = {
+      {{"conv_igemm<f32,128x128,gather>", "conv_igemm<f32,128x64,gather>",
+        "conv_igemm<f32,64x64,gather>", "conv_igemm<f32,128x32,gather>"},
+       {"conv_igemm<f32,128x128>", "conv_igemm<f32,128x64>", "conv_igemm<f32,64x64>",
+        "conv_igemm<f32,128x32>"}},
+      {{"conv_igemm<bf16,128x128,gather>", "conv_igemm<bf16,128x64,gather>",
+        "conv_igemm<bf16,64x64,gather>", "conv_igemm<bf16,128x32,gather>"},
+       {"conv_igemm<bf16,128x128>", "conv_igemm<bf16,128x64>", "conv_igemm<bf16,64x64>",
+        "conv_igemm<bf16,128x32>"}}};
+  return names[bf][vec][pick_shape(p)];
 }
 
 }  // namespace lop

@@ -35,5 +35,7 @@ inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvC
 
 // Enqueue the kernel for one operator on `stream`. Returns hipError_t.
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream);
+// Short name of the kernel variant launch_op would pick (static storage).
+const char* kernel_name(const OpLaunch& L);
 
 }  // namespace lop

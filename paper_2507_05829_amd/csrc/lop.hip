@@ -15,10 +15,17 @@ namespace lop {
 hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream);
 hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream);
 
+const char* conv_igemm_name(const OpLaunch& L);
+const char* rowwise_name(const OpLaunch& L);
+
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream) {
   if (L.out_hi <= L.out_lo) return hipSuccess;
   if (L.op == LOP_CONV2D) return launch_conv_igemm(L, stream);
   return launch_rowwise_op(L, stream);
+}
+
+const char* kernel_name(const OpLaunch& L) {
+  return L.op == LOP_CONV2D ? conv_igemm_name(L) : rowwise_name(L);
 }
 }  // namespace lop
 
@@ -448,6 +455,67 @@ int lop_time_layer(lop_plan_t* P, int band, int layer, const void* d_in, void* d
   float ms = 0.f;
   LOP_HIP(hipEventElapsedTime(&ms, P->ev_c0[0], P->ev_c1[0]));
   *ms_per_launch = ms / iters;
+  return LOP_OK;
+}
+
+int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, size_t size) {
+  if (!P || !name || size == 0) return LOP_ERR_INVALID_ARG;
+  if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
+    return LOP_ERR_BAND_RANGE;
+  const lop_rows_t r = P->t.bands[band].need[layer + 1];
+  const char* n = "";
+  if (r.hi > r.lo) n = lop::kernel_name(make_launch(P, band, layer, nullptr, nullptr));
+  std::strncpy(name, n, size - 1);
+  name[size - 1] = 0;
+  return LOP_OK;
+}
+
+int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, float* layer_ms) {
+  if (!P || !d_in || !d_out || !layer_ms || iters < 1) return LOP_ERR_INVALID_ARG;
+  if (!P->ready) return LOP_ERR_NOT_READY;
+  const int nb = P->t.n_bands, nl = P->t.n_layers();
+  hipStream_t cs = P->s_compute;
+  std::vector<hipEvent_t> ev((size_t)nb * nl * 2, nullptr);
+  int rc = LOP_OK;
+  auto run = [&]() -> int {
+    for (auto& e : ev) LOP_HIP(hipEventCreate(&e));
+    for (int i = 0; i < nb * nl; ++i) layer_ms[i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+      for (int b = 0; b < nb; ++b)
+        for (int l = 0; l < nl; ++l) {
+          const lop_rows_t r = P->t.bands[b].need[l + 1];
+          if (r.hi <= r.lo) continue;
+          const lop::OpLaunch o = make_launch(P, b, l, d_in, d_out);
+          const size_t i = ((size_t)b * nl + l) * 2;
+          LOP_HIP(hipEventRecord(ev[i], cs));
+          LOP_HIP(lop::launch_op(o, cs));
+          LOP_HIP(hipEventRecord(ev[i + 1], cs));
+        }
+      LOP_HIP(hipStreamSynchronize(cs));
+      for (int b = 0; b < nb; ++b)
+        for (int l = 0; l < nl; ++l) {
+          const lop_rows_t r = P->t.bands[b].need[l + 1];
+          if (r.hi <= r.lo) continue;
+          const size_t i = ((size_t)b * nl + l) * 2;
+          float ms = 0.f;
+          LOP_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+          layer_ms[b * nl + l] += ms / iters;
+        }
+    }
+    return LOP_OK;
+  };
+  rc = run();
+  for (hipEvent_t e : ev) if (e) (void)hipEventDestroy(e);
+  return rc;
+}
+
+int lop_copy_chain(lop_plan_t* P, const void* d_out, void* h_out) {
+  if (!P || !d_out || !h_out) return LOP_ERR_INVALID_ARG;
+  if (!P->ready) return LOP_ERR_NOT_READY;
+  for (int b = 0; b < P->t.n_bands; ++b) {
+    int rc = enqueue_band_copy(P, b, d_out, h_out, P->s_copy);
+    if (rc != LOP_OK) return rc;
+  }
   return LOP_OK;
 }
 

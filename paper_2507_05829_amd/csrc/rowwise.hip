@@ -173,4 +173,16 @@ hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream) {
                       : launch_rowwise<float, 1>(p, L.op, stream);
 }
 
+const char* rowwise_name(const OpLaunch& L) {
+  const bool bf = L.dtype == LOP_BF16;
+  const bool vec = L.x.c % (bf ? 8 : 4) == 0;
+  const int o = L.op == LOP_DWCONV2D ? 0 : (L.op == LOP_MAXPOOL2D ? 1 : 2);
+  static const char* names[2][2][3] = {
+      {{"rowwise<f32,scalar,dwconv>", "rowwise<f32,scalar,maxpool>", "rowwise<f32,scalar,eltwise>"},
+       {"rowwise<f32,dwconv>", "rowwise<f32,maxpool>", "rowwise<f32,eltwise>"}},
+      {{"rowwise<bf16,scalar,dwconv>", "rowwise<bf16,scalar,maxpool>", "rowwise<bf16,scalar,eltwise>"},
+       {"rowwise<bf16,dwconv>", "rowwise<bf16,maxpool>", "rowwise<bf16,eltwise>"}}};
+  return names[bf][vec][o];
+}
+
 }  // namespace lop

@@ -38,7 +38,7 @@ EXPORTS = [
     "lop_plan_n_layers", "lop_plan_band_out_rows", "lop_plan_band_in_rows",
     "lop_plan_band_layer_rows", "lop_plan_stats", "lop_plan_layer_work", "lop_run_band",
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
-    "lop_last_hip_error",
+    "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
 ]
 
 
@@ -88,6 +88,9 @@ def _load() -> ctypes.CDLL:
         "lop_synchronize": (c_int, [P]),
         "lop_time_layer": (c_int, [P, c_int, c_int, c_void_p, c_void_p, c_int, POINTER(c_float)]),
         "lop_plan_destroy": (None, [P]),
+        "lop_plan_layer_kernel": (c_int, [P, c_int, c_int, ctypes.c_char_p, c_size_t]),
+        "lop_profile_chain": (c_int, [P, c_void_p, c_void_p, c_int, POINTER(c_float)]),
+        "lop_copy_chain": (c_int, [P, c_void_p, c_void_p]),
         "lop_strerror": (c_char_p, [c_int]),
         "lop_last_hip_error": (c_int, []),
     }
@@ -222,6 +225,24 @@ def lop_time_layer(plan, band: int, layer: int, d_in, d_out, iters: int = 20) ->
     return ms.value
 
 
+def lop_plan_layer_kernel(plan, band: int, layer: int) -> str:
+    buf = ctypes.create_string_buffer(96)
+    _check(_lib.lop_plan_layer_kernel(plan, band, layer, buf, 96), "lop_plan_layer_kernel")
+    return buf.value.decode()
+
+
+def lop_profile_chain(plan, d_in, d_out, iters: int = 5) -> np.ndarray:
+    nb, nl = lop_plan_n_bands(plan), lop_plan_n_layers(plan)
+    ms = np.zeros((nb, nl), np.float32)
+    _check(_lib.lop_profile_chain(plan, _ptr(d_in), _ptr(d_out), iters,
+                                  ms.ctypes.data_as(POINTER(c_float))), "lop_profile_chain")
+    return ms
+
+
+def lop_copy_chain(plan, d_out, h_out) -> None:
+    _check(_lib.lop_copy_chain(plan, _ptr(d_out), _ptr(h_out)), "lop_copy_chain")
+
+
 def lop_strerror(code: int) -> str:
     return _lib.lop_strerror(code).decode()
 
@@ -310,6 +331,10 @@ class Plan:
         return lop_run_chain(self.handle, d_in, d_out, h_out, compute_stream, timing)
 
     def synchronize(self): lop_synchronize(self.handle)
+
+    def layer_kernel(self, b, l): return lop_plan_layer_kernel(self.handle, b, l)
+    def profile_chain(self, d_in, d_out, iters=5): return lop_profile_chain(self.handle, d_in, d_out, iters)
+    def copy_chain(self, d_out, h_out): lop_copy_chain(self.handle, d_out, h_out)
 
     def time_layer(self, band, layer, d_in, d_out, iters=20):
         return lop_time_layer(self.handle, band, layer, d_in, d_out, iters)
