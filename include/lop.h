@@ -86,6 +86,11 @@ typedef struct {
 #define LOP_FLAG_NO_D2H 1u    /* never copy to the host even if a host pointer is given  */
 #define LOP_FLAG_PLAN_ONLY 2u /* integer planning only: touches no GPU, needs no weights;
                                  lop_run_* return LOP_ERR_NOT_READY                      */
+#define LOP_DEFAULT_LANES 4
+#define LOP_FLAG_LANES(n) (((unsigned)(n) & 0xffu) << 8) /* bands are dealt round robin to n
+                                 compute streams ("lanes", each with its own scratch) that run
+                                 concurrently; 0 = LOP_DEFAULT_LANES, capped at the number of
+                                 non-empty bands                                          */
 #define LOP_FLAG_GRAPH 4u     /* lop_run_chain records its launches into a HIP graph on the
                                  first call for a given set of pointers and replays it   */
 
@@ -129,13 +134,16 @@ LOP_API int lop_plan_layer_work(const lop_plan_t* plan, int band, int layer, dou
  *   d_out  device, whole chain output; only band_out_rows(band) are written
  *   h_out  pinned host, whole chain output, or NULL
  *   compute_stream, copy_stream  hipStream_t or NULL (= the plan's own streams)
- * Bands of one plan share scratch memory: run them on one compute stream. */
+ * Bands b and b' with b = b' (mod lanes) share scratch memory: give them the same
+ * compute stream (or NULL). Bands of different lanes may run concurrently. */
 LOP_API int lop_run_band(lop_plan_t* plan, int band, const void* d_in, void* d_out, void* h_out,
                  void* compute_stream, void* copy_stream);
 
-/* Run every band in order; band b's copy overlaps band b+1's kernels (Sec. IV-B).
- * With timing != NULL the call records events, waits for completion and fills *timing;
- * otherwise it is asynchronous (lop_synchronize waits). */
+/* Run every band: the lanes fork from compute_stream (or the plan's own main stream),
+ * each runs its bands in order, band b's copy overlaps the kernels of the bands after it
+ * (Sec. IV-B), and compute_stream waits for all lanes' kernels (not for the copies: those
+ * are complete after lop_synchronize). With timing != NULL the call records events,
+ * waits for completion and fills *timing; otherwise it is asynchronous. */
 LOP_API int lop_run_chain(lop_plan_t* plan, const void* d_in, void* d_out, void* h_out,
                   void* compute_stream, lop_timing_t* timing);
 

@@ -16,6 +16,8 @@
 // vector per pixel.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "kernels.hpp"
 #include "lop.h"
 
@@ -32,6 +34,7 @@ struct ConvParams {
   const void* res;
   const void* w;
   const float* bias;
+  float* ws;  // split-K partial sums [split][M][C_out], or nullptr
   int x_row0, x_rows, H, W, C_in;
   int y_row0, y_rows, W_out, C_out;
   int r_row0, r_rows;
@@ -39,6 +42,7 @@ struct ConvParams {
   int act, out_lo, R, N;
   int M;  // N * R * W_out
   int K, k_pad;
+  int splits, kc_per_split;
 };
 
 __device__ __forceinline__ float apply_act(float v, int act) {
@@ -72,16 +76,69 @@ __device__ __forceinline__ void mma<float>(const uint4& wa, const uint4& px, f32
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
 }
 
-// BM pixels x BN channels per workgroup; WM x WN wavefronts; VEC_A: c_in is a multiple
-// of the 16-byte vector so one vector never straddles two taps.
-template <typename T, int BM, int BN, int WM, int WN, bool VEC_A>
+// Output pixel m -> element offsets of its channel vector in y and in the residual.
+struct PixelAddr {
+  size_t y, r;
+};
+__device__ __forceinline__ PixelAddr pixel_addr(const ConvParams& p, int m) {
+  const int ow = m % p.W_out;
+  const int t = m / p.W_out;
+  const int r = t % p.R, n = t / p.R;
+  const int oh = p.out_lo + r;
+  PixelAddr a;
+  a.y = ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C_out;
+  a.r = p.res ? ((size_t)(n * p.r_rows + oh - p.r_row0) * p.W_out + ow) * p.C_out : 0;
+  return a;
+}
+
+// bias + residual + activation + the one rounding, for 4 consecutive channels of a pixel.
+template <typename T>
+__device__ __forceinline__ void finish4(const ConvParams& p, const PixelAddr& a, int co, float* v) {
+  T* __restrict__ yg = (T*)p.y;
+  const T* __restrict__ rg = (const T*)p.res;
+  if ((p.C_out & 3) == 0) {
+    if (p.bias) {
+      const float4 b4 = *(const float4*)(p.bias + co);
+      v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+    }
+    if (rg) {
+      alignas(16) T rr[4];
+      if (sizeof(T) == 2) *(uint2*)rr = *(const uint2*)(rg + a.r + co);
+      else *(uint4*)rr = *(const uint4*)(rg + a.r + co);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] += to_f32(rr[j]);
+    }
+    alignas(16) T o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
+    if (sizeof(T) == 2) *(uint2*)(yg + a.y + co) = *(const uint2*)o;
+    else *(uint4*)(yg + a.y + co) = *(const uint4*)o;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (co + j >= p.C_out) break;
+      float u = v[j];
+      if (p.bias) u += p.bias[co + j];
+      if (rg) u += to_f32(rg[a.r + co + j]);
+      yg[a.y + co + j] = from_f32<T>(apply_act(u, p.act));
+    }
+  }
+}
+
+// BM pixels x BN channels per workgroup; WM x WN wavefronts; BKB bytes of the reduction
+// axis per row and step; VEC_A: c_in is a multiple of the 16-byte vector so one vector
+// never straddles two taps. blockIdx.z selects a slice of the reduction (split-K): the
+// slices' fp32 partial tiles go to p.ws and splitk_finish_kernel adds them in slice order.
+template <typename T, int BM, int BN, int WM, int WN, int BKB, bool VEC_A>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
-  constexpr int BKE = 4 * KE;              // reduction elements per step (64 bytes per row)
-  constexpr int ROWB = 80;                 // LDS row pitch: 64 data + 16 pad bytes
+  constexpr int CH = BKB / 16;             // vectors per row and step
+  constexpr int BKE = CH * KE;             // reduction elements per step
+  constexpr int ROWB = BKB + 16;           // LDS row pitch (16 pad bytes: conflict-free b128)
+  constexpr int RPP = 256 / CH;            // rows filled per pass of the 256 threads
   constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
-  constexpr int A_IT = BM / 64, B_IT = (BN + 63) / 64;
-  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && BM % 64 == 0, "tile shape");
+  constexpr int A_IT = (BM + RPP - 1) / RPP, B_IT = (BN + RPP - 1) / RPP;
+  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (BM + BN) * ROWB];
   unsigned char* const As = smem;
@@ -90,17 +147,22 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
   const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
-  const int lrow = tid >> 2, chunk = tid & 3;
+  const int lrow = tid / CH, chunk = tid % CH;
   const T* __restrict__ xg = (const T*)p.x;
   const T* __restrict__ wg = (const T*)p.w;
+
+  const int nk_all = p.k_pad / BKE;
+  const int kc0 = blockIdx.z * p.kc_per_split;
+  const int kc1 = min(nk_all, kc0 + p.kc_per_split);
 
   // ---- the pixels this thread gathers (fixed over the K loop)
   int a_ih0[A_IT], a_iw0[A_IT], a_nrow[A_IT];
   bool a_ok[A_IT];
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
-    const int m = m0 + lrow + 64 * i;
-    a_ok[i] = m < p.M;
+    const int row = lrow + RPP * i;
+    const int m = m0 + row;
+    a_ok[i] = m < p.M && (BM % RPP == 0 || row < BM);
     const int mm = a_ok[i] ? m : 0;
     const int ow = mm % p.W_out;
     const int t = mm / p.W_out;
@@ -112,7 +174,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   // position of this thread's vector inside the reduction axis (VEC_A path)
   int ci = 0, kwi = 0, khi = 0;
   if (VEC_A) {
-    const int k = chunk * KE;
+    const int k = kc0 * BKE + chunk * KE;
     const int tap = k / p.C_in;
     ci = k - tap * p.C_in;
     khi = tap / p.kw;
@@ -159,19 +221,21 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
-      const int row = lrow + 64 * i;
-      if (BN >= 64 || row < BN)
+      const int row = lrow + RPP * i;
+      if (BN % RPP == 0 || row < BN)
         rb[i] = *(const uint4*)(wg + (size_t)(co0 + row) * p.k_pad + kc * BKE + chunk * KE);
     }
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < A_IT; ++i)
-      *(uint4*)(As + (buf * BM + lrow + 64 * i) * ROWB + chunk * 16) = ra[i];
+    for (int i = 0; i < A_IT; ++i) {
+      const int row = lrow + RPP * i;
+      if (BM % RPP == 0 || row < BM) *(uint4*)(As + (buf * BM + row) * ROWB + chunk * 16) = ra[i];
+    }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
-      const int row = lrow + 64 * i;
-      if (BN >= 64 || row < BN) *(uint4*)(Bs + (buf * BN + row) * ROWB + chunk * 16) = rb[i];
+      const int row = lrow + RPP * i;
+      if (BN % RPP == 0 || row < BN) *(uint4*)(Bs + (buf * BN + row) * ROWB + chunk * 16) = rb[i];
     }
   };
 
@@ -183,15 +247,16 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  const int nk = p.k_pad / BKE;
-  gather(0);
-  stash(0);
+  if (kc0 < kc1) {
+    gather(kc0);
+    stash(0);
+  }
   __syncthreads();
-  for (int kc = 0; kc < nk; ++kc) {
-    const int buf = kc & 1;
-    if (kc + 1 < nk) gather(kc + 1);
+  for (int kc = kc0; kc < kc1; ++kc) {
+    const int buf = (kc - kc0) & 1;
+    if (kc + 1 < kc1) gather(kc + 1);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < BKB / 32; ++ks) {
       uint4 px[TM], wt[TN];
       const int koff = ks * 32 + (lane >> 5) * 16;
 #pragma unroll
@@ -205,25 +270,18 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
     }
-    if (kc + 1 < nk) stash(buf ^ 1);
+    if (kc + 1 < kc1) stash(buf ^ 1);
     __syncthreads();
   }
 
   // ---- epilogue: lane holds, per 32x32 tile, pixel (lane & 31) and output channels
   // g*8 + (lane >> 5)*4 + {0,1,2,3} for g = 0..3.
-  T* __restrict__ yg = (T*)p.y;
-  const T* __restrict__ rg = (const T*)p.res;
-  const bool vec_c = (p.C_out & 3) == 0;
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
     const int m = m0 + (wm * TM + tm) * 32 + (lane & 31);
     if (m >= p.M) continue;
-    const int ow = m % p.W_out;
-    const int t = m / p.W_out;
-    const int r = t % p.R, n = t / p.R;
-    const int oh = p.out_lo + r;
-    const size_t ypix = ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C_out;
-    const size_t rpix = rg ? ((size_t)(n * p.r_rows + oh - p.r_row0) * p.W_out + ow) * p.C_out : 0;
+    PixelAddr pa;
+    if (!p.ws) pa = pixel_addr(p, m);
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
 #pragma unroll
@@ -233,67 +291,119 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
         float v[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][g * 4 + j];
-        if (vec_c) {
-          if (p.bias) {
-            const float4 b4 = *(const float4*)(p.bias + co);
-            v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
-          }
-          alignas(16) T o[4];
-          if (rg) {
-            alignas(16) T rr[4];
-            if (sizeof(T) == 2) *(uint2*)rr = *(const uint2*)(rg + rpix + co);
-            else *(uint4*)rr = *(const uint4*)(rg + rpix + co);
+        if (p.ws) {
+          float* dst = p.ws + ((size_t)blockIdx.z * p.M + m) * p.C_out + co;
+          if ((p.C_out & 3) == 0) {
+            *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] += to_f32(rr[j]);
+            for (int j = 0; j < 4; ++j)
+              if (co + j < p.C_out) dst[j] = v[j];
           }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
-          if (sizeof(T) == 2) *(uint2*)(yg + ypix + co) = *(const uint2*)o;
-          else *(uint4*)(yg + ypix + co) = *(const uint4*)o;
         } else {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            if (co + j >= p.C_out) break;
-            float u = v[j];
-            if (p.bias) u += p.bias[co + j];
-            if (rg) u += to_f32(rg[rpix + co + j]);
-            yg[ypix + co + j] = from_f32<T>(apply_act(u, p.act));
-          }
+          finish4<T>(p, pa, co, v);
         }
       }
     }
   }
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
-hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s) {
-  dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN);
-  if (vec_a)
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, true>), grid, dim3(256), 0, s, p);
-  else
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, false>), grid, dim3(256), 0, s, p);
-  return hipGetLastError();
+// Adds the split-K slices in slice order and applies the epilogue: one thread per 4
+// consecutive channels of a pixel.
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const ConvParams p) {
+  const int cq = (p.C_out + 3) / 4;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= (long)p.M * cq) return;
+  const int m = (int)(gid / cq), co = (int)(gid % cq) * 4;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  const float* src = p.ws + (size_t)m * p.C_out + co;
+  const size_t slice = (size_t)p.M * p.C_out;
+  if ((p.C_out & 3) == 0) {
+    int s = 0;
+    for (; s + 4 <= p.splits; s += 4) {  // four loads in flight, added in slice order
+      const float4 t0 = *(const float4*)(src + (s + 0) * slice);
+      const float4 t1 = *(const float4*)(src + (s + 1) * slice);
+      const float4 t2 = *(const float4*)(src + (s + 2) * slice);
+      const float4 t3 = *(const float4*)(src + (s + 3) * slice);
+      v[0] = (((v[0] + t0.x) + t1.x) + t2.x) + t3.x;
+      v[1] = (((v[1] + t0.y) + t1.y) + t2.y) + t3.y;
+      v[2] = (((v[2] + t0.z) + t1.z) + t2.z) + t3.z;
+      v[3] = (((v[3] + t0.w) + t1.w) + t2.w) + t3.w;
+    }
+    for (; s < p.splits; ++s) {
+      const float4 t = *(const float4*)(src + s * slice);
+      v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+    }
+  } else {
+    for (int s = 0; s < p.splits; ++s)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (co + j < p.C_out) v[j] += src[s * slice + j];
+  }
+  finish4<T>(p, pixel_addr(p, m), co, v);
 }
 
 enum Shape { S128x128, S128x64, S64x64, S128x32 };
+struct Choice {
+  Shape shape;
+  int bm, bn;
+  int splits, kc_per_split;
+};
 
-// Largest tile that still gives every compute unit a workgroup; small layers fall
-// through to smaller tiles.
-Shape pick_shape(const ConvParams& p) {
+constexpr int kBKB = 128;       // bytes of the reduction axis per row and step
+constexpr int kComputeUnits = 256;
+
+// Largest tile that still gives every compute unit a workgroup; layers too small for
+// that take the smallest tile and cut the reduction axis into slices until the grid
+// covers the chip about twice (each slice keeps at least 4 steps).
+Choice choose(const ConvParams& p, int dtype) {
   auto blocks = [&](int bm, int bn) {
     return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn);
   };
-  if (p.C_out > 64 && blocks(128, 128) >= 256) return S128x128;
-  if (p.C_out > 32 && blocks(128, 64) >= 256) return S128x64;
-  if (p.C_out > 32) return S64x64;
-  return S128x32;
+  Choice c;
+  if (p.C_out > 64 && blocks(128, 128) >= kComputeUnits) c = {S128x128, 128, 128, 1, 0};
+  else if (p.C_out > 32 && blocks(128, 64) >= kComputeUnits) c = {S128x64, 128, 64, 1, 0};
+  else if (p.C_out > 32) c = {S64x64, 64, 64, 1, 0};
+  else c = {S128x32, 128, 32, 1, 0};
+  const int bke = kBKB / (dtype == LOP_BF16 ? 2 : 4);
+  const int nk = p.k_pad / bke;
+  const long b = blocks(c.bm, c.bn);
+  int splits = 1;
+  if (b < kComputeUnits) {
+    splits = (int)((2 * kComputeUnits + b - 1) / b);
+    splits = std::min(splits, std::max(nk / 4, 1));
+    splits = std::min(splits, 64);
+  }
+  c.kc_per_split = (nk + splits - 1) / splits;
+  c.splits = (nk + c.kc_per_split - 1) / c.kc_per_split;
+  return c;
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s) {
+  dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
+  if (vec_a)
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, true>), grid, dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, false>), grid, dim3(256), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !p.ws) return e;
+  const long work = (long)p.M * ((p.C_out + 3) / 4);
+  hipLaunchKernelGGL((splitk_finish_kernel<T>), dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, p);
+  return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_typed(const ConvParams& p, hipStream_t s) {
+hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s) {
   constexpr int KE = 16 / (int)sizeof(T);
   const bool vec_a = p.C_in % KE == 0;
-  switch (pick_shape(p)) {
+  const Choice c = choose(p, dtype);
+  p.splits = c.splits;
+  p.kc_per_split = c.kc_per_split;
+  if (c.splits > 1 && !ws) return hipErrorInvalidValue;
+  p.ws = c.splits > 1 ? ws : nullptr;
+  switch (c.shape) {
     case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s);
     case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s);
     case S64x64: return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s);
@@ -304,6 +414,7 @@ hipError_t launch_typed(const ConvParams& p, hipStream_t s) {
 ConvParams make_params(const OpLaunch& L) {
   ConvParams p;
   p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = L.w; p.bias = L.bias;
+  p.ws = nullptr;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.H = L.x.h; p.W = L.x.w; p.C_in = L.x.c;
   p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w; p.C_out = L.y.c;
   p.r_row0 = L.res.row0; p.r_rows = L.res.rows;
@@ -313,37 +424,56 @@ ConvParams make_params(const OpLaunch& L) {
   p.M = p.N * p.R * p.W_out;
   p.K = L.x.c * L.kh * L.kw;
   p.k_pad = L.k_pad;
+  p.splits = 1;
+  p.kc_per_split = 0;
   return p;
 }
 
 }  // namespace
 
 int conv_k_pad(int c_in, int kh, int kw, int dtype) {
-  const int bke = dtype == LOP_BF16 ? 32 : 16;
+  const int bke = kBKB / (dtype == LOP_BF16 ? 2 : 4);
   const int k = c_in * kh * kw;
   return (k + bke - 1) / bke * bke;
 }
 
-hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream) {
+size_t conv_workspace_bytes(const OpLaunch& L) {
   const ConvParams p = make_params(L);
+  if (p.M <= 0) return 0;
+  const Choice c = choose(p, L.dtype);
+  return c.splits > 1 ? (size_t)c.splits * p.M * p.C_out * sizeof(float) : 0;
+}
+
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream) {
+  ConvParams p = make_params(L);
   if (p.M <= 0) return hipSuccess;
-  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, stream) : launch_typed<float>(p, stream);
+  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, L.dtype, (float*)L.ws, stream)
+                             : launch_typed<float>(p, L.dtype, (float*)L.ws, stream);
 }
 
 const char* conv_igemm_name(const OpLaunch& L) {
   const ConvParams p = make_params(L);
   const bool bf = L.dtype == LOP_BF16;
   const bool vec = p.C_in % (bf ? 8 : 4) == 0;
-  static const char* names[2][2][4] = {
-      {{"conv_igemm<f32,128x128,gather>", "conv_igemm<f32,128x64,gather>",
-        "conv_igemm<f32,64x64,gather>", "conv_igemm<f32,128x32,gather>"},
-       {"conv_igemm<f32,128x128>", "conv_igemm<f32,128x64>", "conv_igemm<f32,64x64>",
-        "conv_igemm<f32,128x32>"}},
-      {{"conv_igemm<bf16,128x128,gather>", "conv_igemm<bf16,128x64,gather>",
-        "conv_igemm<bf16,64x64,gather>", "conv_igemm<bf16,128x32,gather>"},
-       {"conv_igemm<bf16,128x128>", "conv_igemm<bf16,128x64>", "conv_igemm<bf16,64x64>",
-        "conv_igemm<bf16,128x32>"}}};
-  return names[bf][vec][pick_shape(p)];
+  const Choice c = choose(p, L.dtype);
+  static const char* names[2][2][2][4] = {
+      {{{"conv_igemm<f32,128x128,gather>", "conv_igemm<f32,128x64,gather>",
+         "conv_igemm<f32,64x64,gather>", "conv_igemm<f32,128x32,gather>"},
+        {"conv_igemm<f32,128x128,gather,splitk>", "conv_igemm<f32,128x64,gather,splitk>",
+         "conv_igemm<f32,64x64,gather,splitk>", "conv_igemm<f32,128x32,gather,splitk>"}},
+       {{"conv_igemm<f32,128x128>", "conv_igemm<f32,128x64>", "conv_igemm<f32,64x64>",
+         "conv_igemm<f32,128x32>"},
+        {"conv_igemm<f32,128x128,splitk>", "conv_igemm<f32,128x64,splitk>",
+         "conv_igemm<f32,64x64,splitk>", "conv_igemm<f32,128x32,splitk>"}}},
+      {{{"conv_igemm<bf16,128x128,gather>", "conv_igemm<bf16,128x64,gather>",
+         "conv_igemm<bf16,64x64,gather>", "conv_igemm<bf16,128x32,gather>"},
+        {"conv_igemm<bf16,128x128,gather,splitk>", "conv_igemm<bf16,128x64,gather,splitk>",
+         "conv_igemm<bf16,64x64,gather,splitk>", "conv_igemm<bf16,128x32,gather,splitk>"}},
+       {{"conv_igemm<bf16,128x128>", "conv_igemm<bf16,128x64>", "conv_igemm<bf16,64x64>",
+         "conv_igemm<bf16,128x32>"},
+        {"conv_igemm<bf16,128x128,splitk>", "conv_igemm<bf16,128x64,splitk>",
+         "conv_igemm<bf16,64x64,splitk>", "conv_igemm<bf16,128x32,splitk>"}}}};
+  return names[bf][vec][c.splits > 1][c.shape];
 }
 
 }  // namespace lop

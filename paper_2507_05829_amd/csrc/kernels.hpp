@@ -25,6 +25,8 @@ struct OpLaunch {
   int act = 0;
   int out_lo = 0, out_hi = 0;
   int k_pad = 0;  // dense conv: padded reduction length of the packed weight rows
+  void* ws = nullptr;  // dense conv: device scratch for split-K partial sums (may be null
+                       // only if conv_workspace_bytes() is 0 for this launch)
 };
 
 // Dense conv weights are packed as [c_out_pad][k_pad], k = (a*kw + b)*c_in + ci, zero
@@ -32,6 +34,9 @@ struct OpLaunch {
 constexpr int kConvCoutPad = 128;
 int conv_k_pad(int c_in, int kh, int kw, int dtype);
 inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvCoutPad * kConvCoutPad; }
+
+// Bytes of split-K scratch the dense conv launch needs (0: none).
+size_t conv_workspace_bytes(const OpLaunch& L);
 
 // Enqueue the kernel for one operator on `stream`. Returns hipError_t.
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream);

@@ -2,6 +2,7 @@
 // scheduler (compute stream + copy stream + one event per band) and the queries.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <chrono>
 #include <cstring>
 #include <new>
@@ -46,6 +47,15 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
 
+// One lane = one compute stream with its own scratch; bands are dealt to lanes round
+// robin and the lanes run concurrently (bands are independent of one another).
+struct Lane {
+  hipStream_t stream = nullptr;
+  void* arena = nullptr;    // scratch slabs of one band at a time
+  void* conv_ws = nullptr;  // split-K partial sums of one launch at a time
+  hipEvent_t ev_join = nullptr;
+};
+
 struct lop_plan_s {
   lop::Tables t;
   unsigned flags = 0;
@@ -54,16 +64,22 @@ struct lop_plan_s {
   std::vector<void*> d_w;      // per layer packed weights (device) or nullptr
   std::vector<float*> d_bias;  // per layer bias (device) or nullptr
   std::vector<int> k_pad;
-  void* arena = nullptr;       // scratch slabs of one band at a time
+  size_t conv_ws_bytes = 0;
   size_t arena_bytes = 0;
-  std::vector<std::vector<size_t>> slab_off;  // [band][layer] byte offset into arena
-  hipStream_t s_compute = nullptr, s_copy = nullptr;
+  std::vector<std::vector<size_t>> slab_off;  // [band][layer] byte offset into a lane's arena
+  std::vector<Lane> lanes;
+  hipStream_t s_main = nullptr, s_copy = nullptr;
   hipStream_t last_user_stream = nullptr;
+  hipEvent_t ev_fork = nullptr;
   std::vector<hipEvent_t> ev_done;                          // per band: kernels finished
   std::vector<hipEvent_t> ev_copied;                        // per band: last copy finished
   std::vector<char> copied_valid;
   std::vector<hipEvent_t> ev_c0, ev_c1, ev_d0, ev_d1;       // timing only (lazy)
-  hipEvent_t ev_copy_tail = nullptr;                        // copy stream rejoin
+  hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;
+
+  int n_lanes() const { return (int)lanes.size(); }
+  Lane& lane_of(int band) { return lanes[band % lanes.size()]; }
+  const Lane& lane_of(int band) const { return lanes[band % lanes.size()]; }
 };
 
 namespace {
@@ -157,7 +173,7 @@ lop::Slab slab_of(const lop_plan_t* P, int band, int tensor, const void* d_in, v
       s.ptr = d_out; s.row0 = 0; s.rows = s.h;
     } else {
       const lop_rows_t r = t.bands[band].need[tensor + 1];
-      s.ptr = (char*)P->arena + P->slab_off[band][tensor];
+      s.ptr = (char*)P->lane_of(band).arena + P->slab_off[band][tensor];
       s.row0 = r.lo; s.rows = r.hi - r.lo;
     }
   }
@@ -181,6 +197,7 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
   o.out_lo = t.bands[band].need[l + 1].lo;
   o.out_hi = t.bands[band].need[l + 1].hi;
   o.k_pad = P->k_pad[l];
+  o.ws = P->lane_of(band).conv_ws;
   return o;
 }
 
@@ -221,12 +238,77 @@ int ensure_timing_events(lop_plan_t* P) {
     v->assign(nb, nullptr);
     for (int b = 0; b < nb; ++b) LOP_HIP(hipEventCreate(&(*v)[b]));
   }
+  LOP_HIP(hipEventCreate(&P->ev_t0));
+  LOP_HIP(hipEventCreate(&P->ev_t1));
   return LOP_OK;
 }
 
 bool band_empty(const lop_plan_t* P, int band) {
   const lop_rows_t r = P->t.bands[band].need[P->t.n_layers()];
   return r.hi <= r.lo;
+}
+
+int setup_device(lop_plan_t* P) {
+  LOP_HIP(hipGetDevice(&P->device));
+  int rc = upload_weights(P);
+  if (rc != LOP_OK) return rc;
+  const int nb = P->t.n_bands;
+  int live = 0;
+  for (int b = 0; b < nb; ++b) live += band_empty(P, b) ? 0 : 1;
+  int want = (int)((P->flags >> 8) & 0xff);
+  if (want == 0) want = LOP_DEFAULT_LANES;
+  const int n_lanes = std::max(1, std::min(want, live));
+  P->lanes.assign(n_lanes, Lane{});
+  // the launch descriptors below only need sizes, not the scratch addresses
+  for (int b = 0; b < nb; ++b)
+    for (int l = 0; l < P->t.n_layers(); ++l) {
+      if (P->t.layers[l].d.op != LOP_CONV2D) continue;
+      const lop_rows_t rr = P->t.bands[b].need[l + 1];
+      if (rr.hi <= rr.lo) continue;
+      const size_t need = lop::conv_workspace_bytes(make_launch(P, b, l, nullptr, nullptr));
+      P->conv_ws_bytes = std::max(need, P->conv_ws_bytes);
+    }
+  for (Lane& L : P->lanes) {
+    if (P->arena_bytes) LOP_HIP(hipMalloc(&L.arena, P->arena_bytes));
+    if (P->conv_ws_bytes) {
+      LOP_HIP(hipMalloc(&L.conv_ws, P->conv_ws_bytes));
+    }
+    LOP_HIP(hipStreamCreateWithFlags(&L.stream, hipStreamNonBlocking));
+    LOP_HIP(hipEventCreateWithFlags(&L.ev_join, hipEventDisableTiming));
+  }
+  LOP_HIP(hipStreamCreateWithFlags(&P->s_main, hipStreamNonBlocking));
+  LOP_HIP(hipStreamCreateWithFlags(&P->s_copy, hipStreamNonBlocking));
+  LOP_HIP(hipEventCreateWithFlags(&P->ev_fork, hipEventDisableTiming));
+  P->ev_done.assign(nb, nullptr);
+  P->ev_copied.assign(nb, nullptr);
+  P->copied_valid.assign(nb, 0);
+  for (auto& e : P->ev_done) LOP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  for (auto& e : P->ev_copied) LOP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  LOP_HIP(hipDeviceSynchronize());
+  return LOP_OK;
+}
+
+// Kernels of one band on stream `cs`, then (optionally) its device-to-host copy on the
+// copy stream, gated by the band's "kernels finished" event.
+int enqueue_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h_out,
+                 hipStream_t cs, hipStream_t ds, bool timing) {
+  // the band's rows of d_out may still be in flight to the host from an earlier call
+  if (P->copied_valid[band]) LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[band], 0));
+  if (timing) LOP_HIP(hipEventRecord(P->ev_c0[band], cs));
+  int rc = enqueue_band_kernels(P, band, d_in, d_out, cs);
+  if (rc != LOP_OK) return rc;
+  if (timing) LOP_HIP(hipEventRecord(P->ev_c1[band], cs));
+  if (h_out && !(P->flags & LOP_FLAG_NO_D2H)) {
+    LOP_HIP(hipEventRecord(P->ev_done[band], cs));
+    LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[band], 0));
+    if (timing) LOP_HIP(hipEventRecord(P->ev_d0[band], ds));
+    rc = enqueue_band_copy(P, band, d_out, h_out, ds);
+    if (rc != LOP_OK) return rc;
+    if (timing) LOP_HIP(hipEventRecord(P->ev_d1[band], ds));
+    LOP_HIP(hipEventRecord(P->ev_copied[band], ds));
+    P->copied_valid[band] = 1;
+  }
+  return LOP_OK;
 }
 
 }  // namespace
@@ -244,22 +326,7 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
   P->flags = flags;
   size_scratch(P);
   if (!(flags & LOP_FLAG_PLAN_ONLY)) {
-    auto setup = [&]() -> int {
-      LOP_HIP(hipGetDevice(&P->device));
-      int r = upload_weights(P);
-      if (r != LOP_OK) return r;
-      if (P->arena_bytes) LOP_HIP(hipMalloc(&P->arena, P->arena_bytes));
-      LOP_HIP(hipStreamCreateWithFlags(&P->s_compute, hipStreamNonBlocking));
-      LOP_HIP(hipStreamCreateWithFlags(&P->s_copy, hipStreamNonBlocking));
-      P->ev_done.assign(P->t.n_bands, nullptr);
-      for (auto& e : P->ev_done) LOP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-      P->ev_copied.assign(P->t.n_bands, nullptr);
-      P->copied_valid.assign(P->t.n_bands, 0);
-      for (auto& e : P->ev_copied) LOP_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-      LOP_HIP(hipEventCreateWithFlags(&P->ev_copy_tail, hipEventDisableTiming));
-      return LOP_OK;
-    };
-    rc = setup();
+    rc = setup_device(P);
     if (rc != LOP_OK) { lop_plan_destroy(P); return rc; }
     P->ready = true;
   }
@@ -269,15 +336,21 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
 
 void lop_plan_destroy(lop_plan_t* P) {
   if (!P) return;
-  if (P->s_compute) (void)hipStreamSynchronize(P->s_compute);
+  for (Lane& L : P->lanes) if (L.stream) (void)hipStreamSynchronize(L.stream);
+  if (P->s_main) (void)hipStreamSynchronize(P->s_main);
   if (P->s_copy) (void)hipStreamSynchronize(P->s_copy);
   for (void* w : P->d_w) if (w) (void)hipFree(w);
   for (float* b : P->d_bias) if (b) (void)hipFree(b);
-  if (P->arena) (void)hipFree(P->arena);
   for (auto* v : {&P->ev_done, &P->ev_copied, &P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
-  if (P->ev_copy_tail) (void)hipEventDestroy(P->ev_copy_tail);
-  if (P->s_compute) (void)hipStreamDestroy(P->s_compute);
+  for (hipEvent_t e : {P->ev_fork, P->ev_t0, P->ev_t1}) if (e) (void)hipEventDestroy(e);
+  for (Lane& L : P->lanes) {
+    if (L.arena) (void)hipFree(L.arena);
+    if (L.conv_ws) (void)hipFree(L.conv_ws);
+    if (L.ev_join) (void)hipEventDestroy(L.ev_join);
+    if (L.stream) (void)hipStreamDestroy(L.stream);
+  }
+  if (P->s_main) (void)hipStreamDestroy(P->s_main);
   if (P->s_copy) (void)hipStreamDestroy(P->s_copy);
   delete P;
 }
@@ -351,77 +424,60 @@ int lop_run_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h
   if (band < 0 || band >= P->t.n_bands) return LOP_ERR_BAND_RANGE;
   if (!P->ready) return LOP_ERR_NOT_READY;
   if (band_empty(P, band)) return LOP_OK;
-  hipStream_t cs = compute_stream ? (hipStream_t)compute_stream : P->s_compute;
+  hipStream_t cs = compute_stream ? (hipStream_t)compute_stream : P->lane_of(band).stream;
   hipStream_t ds = copy_stream ? (hipStream_t)copy_stream : P->s_copy;
   if (compute_stream) P->last_user_stream = cs;
-  // the band's rows of d_out may still be in flight to the host from an earlier call
-  if (P->copied_valid[band]) LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[band], 0));
-  int rc = enqueue_band_kernels(P, band, d_in, d_out, cs);
-  if (rc != LOP_OK) return rc;
-  if (h_out && !(P->flags & LOP_FLAG_NO_D2H)) {
-    LOP_HIP(hipEventRecord(P->ev_done[band], cs));
-    LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[band], 0));
-    rc = enqueue_band_copy(P, band, d_out, h_out, ds);
-    if (rc != LOP_OK) return rc;
-    LOP_HIP(hipEventRecord(P->ev_copied[band], ds));
-    P->copied_valid[band] = 1;
-  }
-  return rc;
+  return enqueue_band(P, band, d_in, d_out, h_out, cs, ds, false);
 }
 
 int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, void* compute_stream,
                   lop_timing_t* timing) {
   if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
-  hipStream_t cs = compute_stream ? (hipStream_t)compute_stream : P->s_compute;
+  hipStream_t ms = compute_stream ? (hipStream_t)compute_stream : P->s_main;
   hipStream_t ds = P->s_copy;
-  if (compute_stream) P->last_user_stream = cs;
-  const bool copy = h_out && !(P->flags & LOP_FLAG_NO_D2H);
+  if (compute_stream) P->last_user_stream = ms;
   const int nb = P->t.n_bands;
+  const bool copy = h_out && !(P->flags & LOP_FLAG_NO_D2H);
   if (timing) {
     int rc = ensure_timing_events(P);
     if (rc != LOP_OK) return rc;
-    LOP_HIP(hipStreamSynchronize(cs));
-    LOP_HIP(hipStreamSynchronize(ds));
+    rc = lop_synchronize(P);
+    if (rc != LOP_OK) return rc;
   }
   const auto t0 = std::chrono::steady_clock::now();
+  if (timing) LOP_HIP(hipEventRecord(P->ev_t0, ms));
+  // fork: every lane starts after what is already queued on the main stream
+  LOP_HIP(hipEventRecord(P->ev_fork, ms));
+  for (Lane& L : P->lanes) LOP_HIP(hipStreamWaitEvent(L.stream, P->ev_fork, 0));
   for (int b = 0; b < nb; ++b) {
     if (band_empty(P, b)) continue;
-    if (P->copied_valid[b]) LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[b], 0));
-    if (timing) LOP_HIP(hipEventRecord(P->ev_c0[b], cs));
-    int rc = enqueue_band_kernels(P, b, d_in, d_out, cs);
+    int rc = enqueue_band(P, b, d_in, d_out, h_out, P->lane_of(b).stream, ds, timing != nullptr);
     if (rc != LOP_OK) return rc;
-    if (timing) LOP_HIP(hipEventRecord(P->ev_c1[b], cs));
-    if (copy) {
-      LOP_HIP(hipEventRecord(P->ev_done[b], cs));
-      LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[b], 0));
-      if (timing) LOP_HIP(hipEventRecord(P->ev_d0[b], ds));
-      rc = enqueue_band_copy(P, b, d_out, h_out, ds);
-      if (rc != LOP_OK) return rc;
-      if (timing) LOP_HIP(hipEventRecord(P->ev_d1[b], ds));
-      LOP_HIP(hipEventRecord(P->ev_copied[b], ds));
-      P->copied_valid[b] = 1;
-    }
+  }
+  // join: the main stream continues once every lane's kernels are done (copies are not
+  // joined so that the last copy can run under whatever the caller enqueues next)
+  for (Lane& L : P->lanes) {
+    LOP_HIP(hipEventRecord(L.ev_join, L.stream));
+    LOP_HIP(hipStreamWaitEvent(ms, L.ev_join, 0));
   }
   if (!timing) return LOP_OK;
-  LOP_HIP(hipStreamSynchronize(cs));
-  LOP_HIP(hipStreamSynchronize(ds));
+  LOP_HIP(hipEventRecord(P->ev_t1, ms));
+  int rc = lop_synchronize(P);
+  if (rc != LOP_OK) return rc;
   const auto t1 = std::chrono::steady_clock::now();
   std::memset(timing, 0, sizeof(*timing));
   timing->n_bands = nb;
   timing->wall_ms = std::chrono::duration<float, std::milli>(t1 - t0).count();
-  int first = -1, last = -1;
   for (int b = 0; b < nb; ++b) {
     if (band_empty(P, b)) continue;
-    if (first < 0) first = b;
-    last = b;
     LOP_HIP(hipEventElapsedTime(&timing->band_compute_ms[b], P->ev_c0[b], P->ev_c1[b]));
     if (copy) {
       LOP_HIP(hipEventElapsedTime(&timing->band_copy_ms[b], P->ev_d0[b], P->ev_d1[b]));
       timing->copy_ms += timing->band_copy_ms[b];
     }
   }
-  if (first >= 0) LOP_HIP(hipEventElapsedTime(&timing->compute_ms, P->ev_c0[first], P->ev_c1[last]));
+  LOP_HIP(hipEventElapsedTime(&timing->compute_ms, P->ev_t0, P->ev_t1));
   return LOP_OK;
 }
 
@@ -429,7 +485,8 @@ int lop_synchronize(lop_plan_t* P) {
   if (!P) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   if (P->last_user_stream) LOP_HIP(hipStreamSynchronize(P->last_user_stream));
-  LOP_HIP(hipStreamSynchronize(P->s_compute));
+  for (Lane& L : P->lanes) LOP_HIP(hipStreamSynchronize(L.stream));
+  LOP_HIP(hipStreamSynchronize(P->s_main));
   LOP_HIP(hipStreamSynchronize(P->s_copy));
   return LOP_OK;
 }
@@ -446,7 +503,7 @@ int lop_time_layer(lop_plan_t* P, int band, int layer, const void* d_in, void* d
   int rc = ensure_timing_events(P);
   if (rc != LOP_OK) return rc;
   const lop::OpLaunch o = make_launch(P, band, layer, d_in, d_out);
-  hipStream_t cs = P->s_compute;
+  hipStream_t cs = P->s_main;
   LOP_HIP(lop::launch_op(o, cs));  // warm-up
   LOP_HIP(hipEventRecord(P->ev_c0[0], cs));
   for (int i = 0; i < iters; ++i) LOP_HIP(lop::launch_op(o, cs));
@@ -474,7 +531,7 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
   if (!P || !d_in || !d_out || !layer_ms || iters < 1) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   const int nb = P->t.n_bands, nl = P->t.n_layers();
-  hipStream_t cs = P->s_compute;
+  hipStream_t cs = P->s_main;
   std::vector<hipEvent_t> ev((size_t)nb * nl * 2, nullptr);
   int rc = LOP_OK;
   auto run = [&]() -> int {

@@ -33,6 +33,11 @@ LOP_INPUT, LOP_NO_RESIDUAL = -1, -2
 LOP_MAX_BANDS = 64
 LOP_FLAG_NO_D2H, LOP_FLAG_PLAN_ONLY, LOP_FLAG_GRAPH = 1, 2, 4
 
+
+def LOP_FLAG_LANES(n: int) -> int:
+    return (n & 0xFF) << 8
+
+
 EXPORTS = [
     "lop_plan", "lop_plan_out_desc", "lop_plan_layer_desc", "lop_plan_n_bands",
     "lop_plan_n_layers", "lop_plan_band_out_rows", "lop_plan_band_in_rows",

@@ -31,9 +31,10 @@ def test_tiny_chain_fp32(oracle):
     assert not np.isnan(dev).any()
     np.testing.assert_array_equal(dev, host)          # every byte arrived on the host
     assert rel_err(dev, want) <= TOL["f32"]
-    # a kernel's per-element summation order does not depend on the band: B=1 is identical
+    # unbanded run of the same library: same result up to summation order (the split of
+    # the reduction axis may differ between the two launch shapes)
     one, _ = run_gpu(chain, t, n_bands=1)
-    np.testing.assert_array_equal(dev, one)
+    assert rel_err(dev, one) <= TOL["f32"]
 
 
 CONV_GRID = [
@@ -137,7 +138,9 @@ def test_scaled_chains(oracle, name, kw):
     np.testing.assert_array_equal(dev, host)
     assert rel_err(dev, want) <= TOL[chain.dtype]
     one, _ = run_gpu(chain, t, n_bands=1, use_host=False)
-    np.testing.assert_array_equal(dev, one)
+    assert rel_err(dev, one) <= TOL[chain.dtype]
+    serial, _ = run_gpu(chain, t, use_host=False, flags=lop.LOP_FLAG_LANES(1))
+    np.testing.assert_array_equal(dev, serial)      # lanes change scheduling, not values
 
 
 @pytest.mark.parametrize("name", ["resnet18", "vgg16", "detector720p"])
