@@ -28,6 +28,7 @@ def parse():
                     help="comma list of further workloads reported under 'also' (fewer steps)")
     ap.add_argument("--bands", type=int, default=None, help="override the workload's band count")
     ap.add_argument("--lanes", type=int, default=0, help="concurrent band streams (0 = library default)")
+    ap.add_argument("--graph", type=int, default=1, help="1: replay the chain as a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--profile-iters", type=int, default=10)
@@ -115,12 +116,12 @@ def roofline_of(k, dtype):
                 avg_us=k["avg_us"], launches_per_step=k["launches"])
 
 
-def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0):
+def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0, graph=1):
     chain = workloads.CONFIGS[name]()
     if bands:
         chain.n_bands = bands
     tensors = workloads.make_tensors(chain)
-    plan = lop.Plan(chain, tensors, flags=lop.LOP_FLAG_LANES(lanes))
+    plan = lop.Plan(chain, tensors, flags=lop.LOP_FLAG_LANES(lanes) | (lop.LOP_FLAG_GRAPH if graph else 0))
     d_in, d_out, h_out = device_tensors(torch, chain, tensors, plan)
     n_img = chain.in_shape[0]
     useful, executed, scratch = plan.stats()
@@ -196,12 +197,12 @@ def main():
     torch.cuda.set_device(0)
 
     chain, tensors, res, roof = run_workload(torch, lop, workloads, a.workload, a.steps, a.warmup,
-                                             a.bands, a.profile_iters, a.lanes)
+                                             a.bands, a.profile_iters, a.lanes, a.graph)
     also = []
     for name in [s for s in a.also.split(",") if s and s != a.workload]:
         heavy = name == "mbv2"
         _, _, r, rf = run_workload(torch, lop, workloads, name, 10 if heavy else max(a.steps // 4, 10),
-                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters, a.lanes)
+                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters, a.lanes, a.graph)
         r["roofline"] = rf
         also.append(r)
 
@@ -214,7 +215,8 @@ def main():
         "dtype": "f32" if chain.dtype == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload} {'x'.join(map(str, chain.in_shape))} "
                                f"{chain.dtype}, {res['n_bands']} row bands, {res['n_layers']} layers",
-                   "images_per_step": chain.in_shape[0], "independent_bands": True},
+                   "images_per_step": chain.in_shape[0], "independent_bands": True,
+                   "hip_graph": bool(a.graph), "lanes": a.lanes or "default"},
         "roofline": roof,
         "detail": res,
         "also": also,

@@ -91,8 +91,10 @@ typedef struct {
                                  compute streams ("lanes", each with its own scratch) that run
                                  concurrently; 0 = LOP_DEFAULT_LANES, capped at the number of
                                  non-empty bands                                          */
-#define LOP_FLAG_GRAPH 4u     /* lop_run_chain records its launches into a HIP graph on the
-                                 first call for a given set of pointers and replays it   */
+#define LOP_FLAG_GRAPH 4u     /* lop_run_chain (without timing) captures its launches and copies
+                                 into a HIP graph on the first call for a given (d_in, d_out,
+                                 h_out) and replays it afterwards; the graph joins the copies,
+                                 so compute_stream then also waits for them              */
 
 /* Build a plan: validate the chain, infer shapes, split the last layer's output rows
  * into n_bands intervals (first H mod B bands one row longer; trailing bands may be

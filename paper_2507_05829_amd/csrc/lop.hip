@@ -76,6 +76,12 @@ struct lop_plan_s {
   std::vector<char> copied_valid;
   std::vector<hipEvent_t> ev_c0, ev_c1, ev_d0, ev_d1;       // timing only (lazy)
   hipEvent_t ev_t0 = nullptr, ev_t1 = nullptr;
+  hipEvent_t ev_copy_tail = nullptr;
+  struct GraphEntry {
+    const void* d_in; void* d_out; void* h_out;
+    hipGraphExec_t exec;
+  };
+  std::vector<GraphEntry> graphs;  // LOP_FLAG_GRAPH: one instantiated graph per pointer set
 
   int n_lanes() const { return (int)lanes.size(); }
   Lane& lane_of(int band) { return lanes[band % lanes.size()]; }
@@ -279,6 +285,7 @@ int setup_device(lop_plan_t* P) {
   LOP_HIP(hipStreamCreateWithFlags(&P->s_main, hipStreamNonBlocking));
   LOP_HIP(hipStreamCreateWithFlags(&P->s_copy, hipStreamNonBlocking));
   LOP_HIP(hipEventCreateWithFlags(&P->ev_fork, hipEventDisableTiming));
+  LOP_HIP(hipEventCreateWithFlags(&P->ev_copy_tail, hipEventDisableTiming));
   P->ev_done.assign(nb, nullptr);
   P->ev_copied.assign(nb, nullptr);
   P->copied_valid.assign(nb, 0);
@@ -291,9 +298,10 @@ int setup_device(lop_plan_t* P) {
 // Kernels of one band on stream `cs`, then (optionally) its device-to-host copy on the
 // copy stream, gated by the band's "kernels finished" event.
 int enqueue_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h_out,
-                 hipStream_t cs, hipStream_t ds, bool timing) {
+                 hipStream_t cs, hipStream_t ds, bool timing, bool capturing = false) {
   // the band's rows of d_out may still be in flight to the host from an earlier call
-  if (P->copied_valid[band]) LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[band], 0));
+  if (P->copied_valid[band] && !capturing)
+    LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[band], 0));
   if (timing) LOP_HIP(hipEventRecord(P->ev_c0[band], cs));
   int rc = enqueue_band_kernels(P, band, d_in, d_out, cs);
   if (rc != LOP_OK) return rc;
@@ -305,9 +313,72 @@ int enqueue_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h
     rc = enqueue_band_copy(P, band, d_out, h_out, ds);
     if (rc != LOP_OK) return rc;
     if (timing) LOP_HIP(hipEventRecord(P->ev_d1[band], ds));
-    LOP_HIP(hipEventRecord(P->ev_copied[band], ds));
-    P->copied_valid[band] = 1;
+    if (!capturing) {
+      LOP_HIP(hipEventRecord(P->ev_copied[band], ds));
+      P->copied_valid[band] = 1;
+    }
   }
+  return LOP_OK;
+}
+
+// Fork the lanes from `ms`, enqueue every band, join the lanes back into `ms`.
+int enqueue_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms,
+                  bool timing, bool capturing) {
+  hipStream_t ds = P->s_copy;
+  LOP_HIP(hipEventRecord(P->ev_fork, ms));
+  for (Lane& L : P->lanes) LOP_HIP(hipStreamWaitEvent(L.stream, P->ev_fork, 0));
+  bool copied = false;
+  for (int b = 0; b < P->t.n_bands; ++b) {
+    if (band_empty(P, b)) continue;
+    int rc = enqueue_band(P, b, d_in, d_out, h_out, P->lane_of(b).stream, ds, timing, capturing);
+    if (rc != LOP_OK) return rc;
+    copied = copied || (h_out && !(P->flags & LOP_FLAG_NO_D2H));
+  }
+  // join: the main stream continues once every lane's kernels are done. Eagerly the
+  // copies are not joined, so the last copy can run under whatever is enqueued next; a
+  // captured graph has to join every stream it forked.
+  for (Lane& L : P->lanes) {
+    LOP_HIP(hipEventRecord(L.ev_join, L.stream));
+    LOP_HIP(hipStreamWaitEvent(ms, L.ev_join, 0));
+  }
+  if (capturing && copied) {
+    LOP_HIP(hipEventRecord(P->ev_copy_tail, ds));
+    LOP_HIP(hipStreamWaitEvent(ms, P->ev_copy_tail, 0));
+  }
+  return LOP_OK;
+}
+
+int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms) {
+  for (const auto& g : P->graphs)
+    if (g.d_in == d_in && g.d_out == d_out && g.h_out == h_out) {
+      LOP_HIP(hipGraphLaunch(g.exec, ms));
+      return LOP_OK;
+    }
+  // an eager run may still have copies in flight that later eager calls would wait for
+  for (int b = 0; b < P->t.n_bands; ++b)
+    if (P->copied_valid[b]) {
+      LOP_HIP(hipStreamWaitEvent(ms, P->ev_copied[b], 0));
+      P->copied_valid[b] = 0;
+    }
+  hipGraph_t graph = nullptr;
+  LOP_HIP(hipStreamBeginCapture(ms, hipStreamCaptureModeThreadLocal));
+  int rc = enqueue_chain(P, d_in, d_out, h_out, ms, false, true);
+  hipError_t e = hipStreamEndCapture(ms, &graph);
+  if (rc != LOP_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return rc;
+  }
+  if (e != hipSuccess) return hip_fail(e);
+  hipGraphExec_t exec = nullptr;
+  e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) return hip_fail(e);
+  if (P->graphs.size() >= 8) {  // bounded cache: drop the oldest
+    (void)hipGraphExecDestroy(P->graphs.front().exec);
+    P->graphs.erase(P->graphs.begin());
+  }
+  P->graphs.push_back({d_in, d_out, h_out, exec});
+  LOP_HIP(hipGraphLaunch(exec, ms));
   return LOP_OK;
 }
 
@@ -343,7 +414,8 @@ void lop_plan_destroy(lop_plan_t* P) {
   for (float* b : P->d_bias) if (b) (void)hipFree(b);
   for (auto* v : {&P->ev_done, &P->ev_copied, &P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
-  for (hipEvent_t e : {P->ev_fork, P->ev_t0, P->ev_t1}) if (e) (void)hipEventDestroy(e);
+  for (auto& g : P->graphs) (void)hipGraphExecDestroy(g.exec);
+  for (hipEvent_t e : {P->ev_fork, P->ev_t0, P->ev_t1, P->ev_copy_tail}) if (e) (void)hipEventDestroy(e);
   for (Lane& L : P->lanes) {
     if (L.arena) (void)hipFree(L.arena);
     if (L.conv_ws) (void)hipFree(L.conv_ws);
@@ -435,7 +507,6 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
   if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   hipStream_t ms = compute_stream ? (hipStream_t)compute_stream : P->s_main;
-  hipStream_t ds = P->s_copy;
   if (compute_stream) P->last_user_stream = ms;
   const int nb = P->t.n_bands;
   const bool copy = h_out && !(P->flags & LOP_FLAG_NO_D2H);
@@ -445,21 +516,12 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
     rc = lop_synchronize(P);
     if (rc != LOP_OK) return rc;
   }
+  if ((P->flags & LOP_FLAG_GRAPH) && !timing) return launch_graph(P, d_in, d_out, h_out, ms);
   const auto t0 = std::chrono::steady_clock::now();
   if (timing) LOP_HIP(hipEventRecord(P->ev_t0, ms));
-  // fork: every lane starts after what is already queued on the main stream
-  LOP_HIP(hipEventRecord(P->ev_fork, ms));
-  for (Lane& L : P->lanes) LOP_HIP(hipStreamWaitEvent(L.stream, P->ev_fork, 0));
-  for (int b = 0; b < nb; ++b) {
-    if (band_empty(P, b)) continue;
-    int rc = enqueue_band(P, b, d_in, d_out, h_out, P->lane_of(b).stream, ds, timing != nullptr);
+  {
+    int rc = enqueue_chain(P, d_in, d_out, h_out, ms, timing != nullptr, false);
     if (rc != LOP_OK) return rc;
-  }
-  // join: the main stream continues once every lane's kernels are done (copies are not
-  // joined so that the last copy can run under whatever the caller enqueues next)
-  for (Lane& L : P->lanes) {
-    LOP_HIP(hipEventRecord(L.ev_join, L.stream));
-    LOP_HIP(hipStreamWaitEvent(ms, L.ev_join, 0));
   }
   if (!timing) return LOP_OK;
   LOP_HIP(hipEventRecord(P->ev_t1, ms));

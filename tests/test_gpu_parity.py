@@ -231,3 +231,35 @@ def test_timing_struct_is_filled():
     ms = plan.time_layer(1, 0, d_in, d_out, iters=5)
     assert ms > 0
     plan.destroy()
+
+
+def test_graph_replays_match_eager(oracle):
+    """Captured chain replayed several times, with eager work and synchronisation between
+    the replays and fresh inputs each time; every replay equals the eager result."""
+    chain = workloads.resnet18_chain(h=64, w=48)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    eager = lop.Plan(chain, t)
+    graph = lop.Plan(chain, t, flags=lop.LOP_FLAG_GRAPH)
+    d_in = to_device_nhwc(t.x, chain.dtype)
+    outs = [(empty_out(eager.out_shape(), chain.dtype), empty_out(eager.out_shape(), chain.dtype, pinned=True))
+            for _ in range(2)]
+    rng = np.random.default_rng(0)
+    for rep in range(5):
+        x = rng.random(chain.in_shape, dtype=np.float32)
+        d_in.copy_(torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1))))
+        torch.cuda.synchronize()
+        d_ref, h_ref = outs[0]
+        eager.run_chain(d_in, d_ref, h_ref)
+        eager.synchronize()
+        d_g, h_g = outs[1]
+        d_g.fill_(float("nan")); h_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.run_chain(d_in, d_g, h_g)
+        graph.synchronize()
+        np.testing.assert_array_equal(to_nchw(d_g), to_nchw(d_ref))
+        np.testing.assert_array_equal(to_nchw(h_g), to_nchw(h_ref))
+        if rep == 0:
+            tt = workloads.Tensors(x, t.weights, t.biases)
+            assert rel_err(to_nchw(h_g), oracle.run_chain(chain, tt)) <= TOL["f32"]
+        (d_ref * 2).sum().item()          # unrelated eager work between replays
+    eager.destroy(); graph.destroy()
