@@ -29,6 +29,7 @@ def parse():
     ap.add_argument("--bands", type=int, default=None, help="override the workload's band count")
     ap.add_argument("--lanes", type=int, default=0, help="concurrent band streams (0 = library default)")
     ap.add_argument("--graph", type=int, default=1, help="1: replay the chain as a HIP graph")
+    ap.add_argument("--dma-copy", type=int, default=0, help="1: band copies via hipMemcpyAsync")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--profile-iters", type=int, default=10)
@@ -116,12 +117,12 @@ def roofline_of(k, dtype):
                 avg_us=k["avg_us"], launches_per_step=k["launches"])
 
 
-def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0, graph=1):
+def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0, graph=1, dma=0):
     chain = workloads.CONFIGS[name]()
     if bands:
         chain.n_bands = bands
     tensors = workloads.make_tensors(chain)
-    plan = lop.Plan(chain, tensors, flags=lop.LOP_FLAG_LANES(lanes) | (lop.LOP_FLAG_GRAPH if graph else 0))
+    plan = lop.Plan(chain, tensors, flags=lop.LOP_FLAG_LANES(lanes) | (lop.LOP_FLAG_GRAPH if graph else 0) | (lop.LOP_FLAG_DMA_COPY if dma else 0))
     d_in, d_out, h_out = device_tensors(torch, chain, tensors, plan)
     n_img = chain.in_shape[0]
     useful, executed, scratch = plan.stats()
@@ -197,12 +198,12 @@ def main():
     torch.cuda.set_device(0)
 
     chain, tensors, res, roof = run_workload(torch, lop, workloads, a.workload, a.steps, a.warmup,
-                                             a.bands, a.profile_iters, a.lanes, a.graph)
+                                             a.bands, a.profile_iters, a.lanes, a.graph, a.dma_copy)
     also = []
     for name in [s for s in a.also.split(",") if s and s != a.workload]:
         heavy = name == "mbv2"
         _, _, r, rf = run_workload(torch, lop, workloads, name, 10 if heavy else max(a.steps // 4, 10),
-                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters, a.lanes, a.graph)
+                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters, a.lanes, a.graph, a.dma_copy)
         r["roofline"] = rf
         also.append(r)
 

@@ -86,6 +86,9 @@ typedef struct {
 #define LOP_FLAG_NO_D2H 1u    /* never copy to the host even if a host pointer is given  */
 #define LOP_FLAG_PLAN_ONLY 2u /* integer planning only: touches no GPU, needs no weights;
                                  lop_run_* return LOP_ERR_NOT_READY                      */
+#define LOP_FLAG_DMA_COPY 8u  /* always use hipMemcpyAsync for the band copies; by default a
+                                 mapped pinned host buffer is written by a copy kernel on
+                                 the copy stream                                         */
 #define LOP_DEFAULT_LANES 4
 #define LOP_FLAG_LANES(n) (((unsigned)(n) & 0xffu) << 8) /* bands are dealt round robin to n
                                  compute streams ("lanes", each with its own scratch) that run

@@ -6,6 +6,7 @@
 #include <chrono>
 #include <cstring>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "kernels.hpp"
@@ -15,6 +16,8 @@
 namespace lop {
 hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream);
 hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream);
+hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
+                            hipStream_t stream);
 
 const char* conv_igemm_name(const OpLaunch& L);
 const char* rowwise_name(const OpLaunch& L);
@@ -82,6 +85,7 @@ struct lop_plan_s {
     hipGraphExec_t exec;
   };
   std::vector<GraphEntry> graphs;  // LOP_FLAG_GRAPH: one instantiated graph per pointer set
+  std::vector<std::pair<void*, void*>> host_views;  // host buffer -> device-side address
 
   int n_lanes() const { return (int)lanes.size(); }
   Lane& lane_of(int band) { return lanes[band % lanes.size()]; }
@@ -218,6 +222,23 @@ int enqueue_band_kernels(lop_plan_t* P, int band, const void* d_in, void* d_out,
   return LOP_OK;
 }
 
+// Device-side address of a pinned, mapped host buffer, or nullptr if the buffer is not
+// such memory. Looked up once per pointer.
+void* device_view_of_host(lop_plan_t* P, void* h_out) {
+  for (const auto& e : P->host_views)
+    if (e.first == h_out) return e.second;
+  void* dev = nullptr;
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, h_out) == hipSuccess) {
+    if (attr.type == hipMemoryTypeHost && attr.devicePointer) dev = attr.devicePointer;
+  } else {
+    (void)hipGetLastError();  // pageable memory: clear the sticky error, use the DMA path
+  }
+  if (P->host_views.size() >= 16) P->host_views.erase(P->host_views.begin());
+  P->host_views.emplace_back(h_out, dev);
+  return dev;
+}
+
 // Copy the band's final rows of every image to the host buffer (same NHWC layout).
 int enqueue_band_copy(lop_plan_t* P, int band, const void* d_out, void* h_out, hipStream_t s) {
   const lop::Tables& t = P->t;
@@ -227,6 +248,15 @@ int enqueue_band_copy(lop_plan_t* P, int band, const void* d_out, void* h_out, h
   const size_t row_b = (size_t)t.row_elems(t.n_layers() - 1) * t.esz();
   const size_t img_b = row_b * L.h_out;
   const size_t off = row_b * r.lo, len = row_b * (r.hi - r.lo);
+  // Mapped pinned host memory is written by a small kernel on the copy stream (no DMA
+  // set-up cost per band, and it can be captured like any kernel); anything else, or a
+  // plan made with LOP_FLAG_DMA_COPY, goes through the runtime's copy engines.
+  void* mapped = (P->flags & LOP_FLAG_DMA_COPY) ? nullptr : device_view_of_host(P, h_out);
+  if (mapped) {
+    LOP_HIP(lop::launch_copy_rows((char*)mapped + off, (const char*)d_out + off, img_b, len,
+                                  t.in.n, s));
+    return LOP_OK;
+  }
   if (t.in.n == 1) {
     LOP_HIP(hipMemcpyAsync((char*)h_out + off, (const char*)d_out + off, len,
                            hipMemcpyDeviceToHost, s));
@@ -307,8 +337,10 @@ int enqueue_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h
   if (rc != LOP_OK) return rc;
   if (timing) LOP_HIP(hipEventRecord(P->ev_c1[band], cs));
   if (h_out && !(P->flags & LOP_FLAG_NO_D2H)) {
-    LOP_HIP(hipEventRecord(P->ev_done[band], cs));
-    LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[band], 0));
+    if (ds != cs) {  // stream order already gates a copy on the kernels' own stream
+      LOP_HIP(hipEventRecord(P->ev_done[band], cs));
+      LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[band], 0));
+    }
     if (timing) LOP_HIP(hipEventRecord(P->ev_d0[band], ds));
     rc = enqueue_band_copy(P, band, d_out, h_out, ds);
     if (rc != LOP_OK) return rc;
@@ -330,7 +362,12 @@ int enqueue_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hip
   bool copied = false;
   for (int b = 0; b < P->t.n_bands; ++b) {
     if (band_empty(P, b)) continue;
-    int rc = enqueue_band(P, b, d_in, d_out, h_out, P->lane_of(b).stream, ds, timing, capturing);
+    // With several lanes a band's copy follows its kernels on the lane's own stream and
+    // overlaps the other lanes' kernels; a single lane needs the separate copy stream to
+    // overlap band b's copy with band b+1's kernels.
+    hipStream_t cs = P->lane_of(b).stream;
+    int rc = enqueue_band(P, b, d_in, d_out, h_out, cs, P->n_lanes() > 1 ? cs : ds, timing,
+                          capturing);
     if (rc != LOP_OK) return rc;
     copied = copied || (h_out && !(P->flags & LOP_FLAG_NO_D2H));
   }
@@ -341,7 +378,7 @@ int enqueue_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hip
     LOP_HIP(hipEventRecord(L.ev_join, L.stream));
     LOP_HIP(hipStreamWaitEvent(ms, L.ev_join, 0));
   }
-  if (capturing && copied) {
+  if (capturing && copied && P->n_lanes() == 1) {
     LOP_HIP(hipEventRecord(P->ev_copy_tail, ds));
     LOP_HIP(hipStreamWaitEvent(ms, P->ev_copy_tail, 0));
   }
@@ -360,6 +397,7 @@ int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipS
       LOP_HIP(hipStreamWaitEvent(ms, P->ev_copied[b], 0));
       P->copied_valid[b] = 0;
     }
+  if (h_out) (void)device_view_of_host(P, h_out);  // query before capture starts
   hipGraph_t graph = nullptr;
   LOP_HIP(hipStreamBeginCapture(ms, hipStreamCaptureModeThreadLocal));
   int rc = enqueue_chain(P, d_in, d_out, h_out, ms, false, true);

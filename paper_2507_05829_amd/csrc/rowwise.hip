@@ -5,6 +5,8 @@
 // store of a wavefront is one contiguous run of channels. fp32 math, one rounding.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "kernels.hpp"
 #include "lop.h"
 
@@ -171,6 +173,36 @@ hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream) {
                         : launch_rowwise<__bf16, 1>(p, L.op, stream);
   return p.C % 4 == 0 ? launch_rowwise<float, 4>(p, L.op, stream)
                       : launch_rowwise<float, 1>(p, L.op, stream);
+}
+
+namespace {
+// Copies `n` segments of `len` bytes (segment i at offset i*pitch in both buffers), 16 bytes
+// per thread and step. Used to push a band's finished rows into mapped pinned host memory
+// from a stream of its own: the stores travel over PCIe while other streams compute.
+__global__ __launch_bounds__(256) void copy_rows_kernel(char* __restrict__ dst,
+                                                        const char* __restrict__ src,
+                                                        size_t pitch, size_t len, int n) {
+  const size_t vec = len / 16;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (int i = 0; i < n; ++i) {
+    const uint4* s = (const uint4*)(src + i * pitch);
+    uint4* d = (uint4*)(dst + i * pitch);
+    for (size_t j = (size_t)blockIdx.x * 256 + threadIdx.x; j < vec; j += stride) d[j] = s[j];
+    // tail bytes (len is a multiple of the element size, not necessarily of 16)
+    for (size_t j = vec * 16 + (size_t)blockIdx.x * 256 + threadIdx.x; j < len; j += stride)
+      dst[i * pitch + j] = src[i * pitch + j];
+  }
+}
+}  // namespace
+
+hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
+                            hipStream_t stream) {
+  if (len == 0 || n <= 0) return hipSuccess;
+  const size_t vec = (len + 15) / 16;
+  const unsigned grid = (unsigned)std::min<size_t>((vec + 255) / 256, 64);
+  hipLaunchKernelGGL(copy_rows_kernel, dim3(grid), dim3(256), 0, stream, (char*)dst,
+                     (const char*)src, pitch, len, n);
+  return hipGetLastError();
 }
 
 const char* rowwise_name(const OpLaunch& L) {

@@ -31,7 +31,7 @@ LOP_ACT_NONE, LOP_ACT_RELU, LOP_ACT_RELU6 = 0, 1, 2
 LOP_F32, LOP_BF16 = 0, 1
 LOP_INPUT, LOP_NO_RESIDUAL = -1, -2
 LOP_MAX_BANDS = 64
-LOP_FLAG_NO_D2H, LOP_FLAG_PLAN_ONLY, LOP_FLAG_GRAPH = 1, 2, 4
+LOP_FLAG_NO_D2H, LOP_FLAG_PLAN_ONLY, LOP_FLAG_GRAPH, LOP_FLAG_DMA_COPY = 1, 2, 4, 8
 
 
 def LOP_FLAG_LANES(n: int) -> int:
