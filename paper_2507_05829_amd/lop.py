@@ -310,10 +310,14 @@ class Plan:
 
     def destroy(self) -> None:
         if getattr(self, "handle", None):
-            lop_plan_destroy(self.handle)
+            _lib.lop_plan_destroy(self.handle)
             self.handle = None
 
-    __del__ = destroy
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:      # interpreter shutdown: the library may already be gone
+            pass
 
     def out_shape(self) -> Tuple[int, int, int, int]:
         d = lop_plan_out_desc(self.handle)
