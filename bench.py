@@ -30,6 +30,11 @@ def parse():
     ap.add_argument("--lanes", type=int, default=0, help="concurrent band streams (0 = library default)")
     ap.add_argument("--graph", type=int, default=1, help="1: replay the chain as a HIP graph")
     ap.add_argument("--dma-copy", type=int, default=0, help="1: band copies via hipMemcpyAsync")
+    ap.add_argument("--replicas", type=int, default=1,
+                    help="plans (each with its own lanes and scratch) the steady-state steps rotate over")
+    ap.add_argument("--mode", default="independent", choices=["independent", "reuse"],
+                    help="independent: every band recomputes its halos; reuse: bands run in "
+                         "order and reuse rows earlier bands produced")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--profile-iters", type=int, default=10)
@@ -48,16 +53,20 @@ def device_tensors(torch, chain, tensors, plan, n_buf=2):
     return d_in, d_out, h_out
 
 
-def timed_steps(torch, plan, d_in, d_out, h_out, steps, warmup, copy=True):
-    """Steady state: `steps` chains back to back, double-buffered outputs."""
+def timed_steps(torch, plans, d_in, d_out, h_out, steps, warmup, copy=True):
+    """Steady state: `steps` chains back to back; step i uses plan i % R and its own output
+    buffers, so with R > 1 consecutive images overlap on the GPU."""
+    R = len(plans)
     for i in range(warmup):
-        plan.run_chain(d_in, d_out[i % 2], h_out[i % 2] if copy else None)
-    plan.synchronize()
+        plans[i % R].run_chain(d_in, d_out[i % len(d_out)], h_out[i % len(d_out)] if copy else None)
+    for p in plans:
+        p.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        plan.run_chain(d_in, d_out[i % 2], h_out[i % 2] if copy else None)
-    plan.synchronize()
+        plans[i % R].run_chain(d_in, d_out[i % len(d_out)], h_out[i % len(d_out)] if copy else None)
+    for p in plans:
+        p.synchronize()
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
@@ -117,18 +126,22 @@ def roofline_of(k, dtype):
                 avg_us=k["avg_us"], launches_per_step=k["launches"])
 
 
-def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0, graph=1, dma=0):
+def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0, graph=1, dma=0, replicas=1, mode="independent"):
     chain = workloads.CONFIGS[name]()
     if bands:
         chain.n_bands = bands
     tensors = workloads.make_tensors(chain)
-    plan = lop.Plan(chain, tensors, flags=lop.LOP_FLAG_LANES(lanes) | (lop.LOP_FLAG_GRAPH if graph else 0) | (lop.LOP_FLAG_DMA_COPY if dma else 0))
-    d_in, d_out, h_out = device_tensors(torch, chain, tensors, plan)
+    flags = (lop.LOP_FLAG_LANES(lanes) | (lop.LOP_FLAG_GRAPH if graph else 0)
+             | (lop.LOP_FLAG_DMA_COPY if dma else 0)
+             | (lop.LOP_FLAG_REUSE if mode == "reuse" else 0))
+    plans = [lop.Plan(chain, tensors, flags=flags) for _ in range(max(1, replicas))]
+    plan = plans[0]
+    d_in, d_out, h_out = device_tensors(torch, chain, tensors, plan, n_buf=max(2, len(plans), 8 if mode == "reuse" else 2))
     n_img = chain.in_shape[0]
     useful, executed, scratch = plan.stats()
 
-    t_c = timed_steps(torch, plan, d_in, d_out, h_out, steps, warmup, copy=True)
-    t_a = timed_steps(torch, plan, d_in, d_out, h_out, steps, min(warmup, 5), copy=False)
+    t_c = timed_steps(torch, plans, d_in, d_out, h_out, steps, warmup, copy=True)
+    t_a = timed_steps(torch, plans, d_in, d_out, h_out, steps, min(warmup, 5), copy=False)
     t_b = timed_copies(torch, plan, d_out, h_out, steps, min(warmup, 5))
     hidden_steady = 1.0 - max(0.0, t_c - t_a) / t_b
 
@@ -146,7 +159,7 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
 
     kernels = kernel_table(plan, d_in, d_out[0], profile_iters)
     res = dict(
-        workload=name, dtype=chain.dtype, n_bands=plan.n_bands, n_layers=plan.n_layers,
+        workload=name, mode=mode, dtype=chain.dtype, n_bands=plan.n_bands, n_layers=plan.n_layers,
         images_per_s=n_img * steps / t_c, ms_per_step=t_c / steps * 1e3,
         ms_per_step_no_d2h=t_a / steps * 1e3, ms_copies_only=t_b / steps * 1e3,
         d2h_hidden_steady=round(hidden_steady, 4), d2h_hidden_single=round(hidden_single, 4),
@@ -159,7 +172,8 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
         kernels=[{k: v for k, v in kk.items() if not k.endswith("_per_launch")} for kk in kernels],
     )
     roof = roofline_of(kernels[0], chain.dtype)
-    plan.destroy()
+    for p in plans:
+        p.destroy()
     return chain, tensors, res, roof
 
 
@@ -198,12 +212,12 @@ def main():
     torch.cuda.set_device(0)
 
     chain, tensors, res, roof = run_workload(torch, lop, workloads, a.workload, a.steps, a.warmup,
-                                             a.bands, a.profile_iters, a.lanes, a.graph, a.dma_copy)
+                                             a.bands, a.profile_iters, a.lanes, a.graph, a.dma_copy, a.replicas, a.mode)
     also = []
     for name in [s for s in a.also.split(",") if s and s != a.workload]:
         heavy = name == "mbv2"
         _, _, r, rf = run_workload(torch, lop, workloads, name, 10 if heavy else max(a.steps // 4, 10),
-                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters, a.lanes, a.graph, a.dma_copy)
+                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters, a.lanes, a.graph, a.dma_copy, a.replicas, a.mode)
         r["roofline"] = rf
         also.append(r)
 
@@ -216,8 +230,9 @@ def main():
         "dtype": "f32" if chain.dtype == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload} {'x'.join(map(str, chain.in_shape))} "
                                f"{chain.dtype}, {res['n_bands']} row bands, {res['n_layers']} layers",
-                   "images_per_step": chain.in_shape[0], "independent_bands": True,
-                   "hip_graph": bool(a.graph), "lanes": a.lanes or "default"},
+                   "images_per_step": chain.in_shape[0], "independent_bands": a.mode == "independent",
+                   "hip_graph": bool(a.graph), "lanes": a.lanes or "default",
+                   "replicas": a.replicas},
         "roofline": roof,
         "detail": res,
         "also": also,

@@ -89,6 +89,13 @@ typedef struct {
 #define LOP_FLAG_DMA_COPY 8u  /* always use hipMemcpyAsync for the band copies; by default a
                                  mapped pinned host buffer is written by a copy kernel on
                                  the copy stream                                         */
+#define LOP_FLAG_REUSE 16u    /* bands run in order and share per-layer buffers: a band computes,
+                                 of every layer, only the rows no earlier band has produced
+                                 (no halo recompute; data already on the device is reused,
+                                 Sec. IV-B). A whole chain then runs on one lane and the
+                                 chains of consecutive lop_run_chain calls rotate over the
+                                 lanes. lop_run_band must be called for bands 0,1,2,... in
+                                 order.                                                   */
 #define LOP_DEFAULT_LANES 4
 #define LOP_FLAG_LANES(n) (((unsigned)(n) & 0xffu) << 8) /* bands are dealt round robin to n
                                  compute streams ("lanes", each with its own scratch) that run
@@ -122,6 +129,9 @@ LOP_API int lop_plan_n_layers(const lop_plan_t* plan);
 LOP_API int lop_plan_band_out_rows(const lop_plan_t* plan, int band, lop_rows_t* rows);
 LOP_API int lop_plan_band_in_rows(const lop_plan_t* plan, int band, lop_rows_t* rows);
 LOP_API int lop_plan_band_layer_rows(const lop_plan_t* plan, int band, int layer, lop_rows_t* rows);
+/* Rows of `layer`'s output that the band's launch produces: all the rows it needs
+ * (independent bands), or those of them no earlier band has produced (LOP_FLAG_REUSE). */
+LOP_API int lop_plan_band_compute_rows(const lop_plan_t* plan, int band, int layer, lop_rows_t* rows);
 
 /* Work counts: operations of the whole layers (useful) and summed over the bands'
  * intervals (executed; > useful where halos are recomputed); bytes of device scratch. */

@@ -135,6 +135,45 @@ def plan(chain, n_bands: Optional[int] = None) -> List[Dict[int, Interval]]:
     return [plan_closed_form(chain, br) for br in bands]
 
 
+def plan_reuse(chain, n_bands: Optional[int] = None) -> List[Dict[int, Interval]]:
+    """Rows each band computes when bands run in order and share per-layer buffers, so
+    that data already on the device is reused instead of recomputed (Sec. IV-B: execution
+    is placed where the required input already is). Set arithmetic only: of the rows
+    band b needs of a layer (brute-force marking), those that no earlier band has
+    computed. The result per layer must be one interval (Sec. IV-C contiguity)."""
+    shapes = infer_shapes(chain)
+    nl = len(chain.layers)
+    bands = split_rows(shapes[-1][2], chain.n_bands if n_bands is None else n_bands)
+    have: Dict[int, set] = {t: set() for t in range(nl)}
+    out = []
+    for br in bands:
+        need = plan_brute_force(chain, br)
+        fresh: Dict[int, Interval] = {}
+        for t in range(nl):
+            rows = set() if need[t] is None else set(range(need[t][0], need[t][1]))
+            new = rows - have[t]
+            if new:
+                lo, hi = min(new), max(new) + 1
+                assert new == set(range(lo, hi)), "fresh rows must be one interval"
+                fresh[t] = (lo, hi)
+            else:
+                fresh[t] = None
+            have[t] |= new
+        out.append(fresh)
+    return out
+
+
+def flop_counts_reuse(chain, n_bands: Optional[int] = None) -> Tuple[float, float]:
+    shapes = infer_shapes(chain)
+    useful = sum(conv_flop(chain, shapes, i, shapes[i][2]) for i in range(len(chain.layers)))
+    executed = 0.0
+    for fresh in plan_reuse(chain, n_bands):
+        for i, iv in fresh.items():
+            if iv is not None:
+                executed += conv_flop(chain, shapes, i, iv[1] - iv[0])
+    return useful, executed
+
+
 def receptive_field_rows(chain_layers) -> int:
     """RF = 1 + sum_l (k_l-1)*d_l*prod_{i<l} s_i along a straight chain of layers."""
     rf, jump = 1, 1

@@ -158,3 +158,25 @@ def run_chain_banded(chain, t, n_bands: Optional[int] = None) -> np.ndarray:
         covered[s.row0:s.row0 + s.rows] += 1
     assert np.all(covered == 1), "bands must tile the final rows exactly once"
     return out
+
+
+def run_chain_reuse(chain, t, n_bands: Optional[int] = None) -> np.ndarray:
+    """Bands in order on shared full-height buffers; each band computes only the rows the
+    planner oracle marks as not yet computed. Buffers start as NaN, so a row that is read
+    before any band produced it poisons the result."""
+    shapes = planner.infer_shapes(chain)
+    nl = len(chain.layers)
+    bufs: Dict[int, Slab] = {-1: Slab(t.x, 0, chain.in_shape[2])}
+    for i, (n, c, h, w) in enumerate(shapes):
+        bufs[i] = Slab(np.full((n, c, h, w), np.nan, np.float32), 0, h)
+    for fresh in planner.plan_reuse(chain, n_bands):
+        for i, L in enumerate(chain.layers):
+            if fresh[i] is None:
+                continue
+            lo, hi = fresh[i]
+            res = bufs[L.residual_from] if L.residual_from != -2 else None
+            _, _, h, w = shapes[i]
+            part = run_layer(L, bufs[L.input_from], t.weights[i], t.biases[i], res,
+                             chain.dtype, lo, hi - lo, h, w)
+            bufs[i].data[:, :, lo:hi, :] = part.data
+    return bufs[nl - 1].data

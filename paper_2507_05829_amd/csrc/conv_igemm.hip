@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "kernels.hpp"
 #include "lop.h"
@@ -129,7 +130,7 @@ __device__ __forceinline__ void finish4(const ConvParams& p, const PixelAddr& a,
 // axis per row and step; VEC_A: c_in is a multiple of the 16-byte vector so one vector
 // never straddles two taps. blockIdx.z selects a slice of the reduction (split-K): the
 // slices' fp32 partial tiles go to p.ws and splitk_finish_kernel adds them in slice order.
-template <typename T, int BM, int BN, int WM, int WN, int BKB, bool VEC_A>
+template <typename T, int BM, int BN, int WM, int WN, int BKB, int NS, bool VEC_A>
 __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
   constexpr int CH = BKB / 16;             // vectors per row and step
@@ -181,9 +182,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
     kwi = tap - khi * p.kw;
   }
 
-  uint4 ra[A_IT], rb[B_IT];
+  uint4 ra_s[NS][A_IT], rb_s[NS][B_IT];  // NS steps of global loads in flight
 
-  auto gather = [&](int kc) {
+  auto gather = [&](int kc, uint4 (&ra)[A_IT], uint4 (&rb)[B_IT]) {
     if (VEC_A) {
 #pragma unroll
       for (int i = 0; i < A_IT; ++i) {
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
         rb[i] = *(const uint4*)(wg + (size_t)(co0 + row) * p.k_pad + kc * BKE + chunk * KE);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](int buf, const uint4 (&ra)[A_IT], const uint4 (&rb)[B_IT]) {
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const int row = lrow + RPP * i;
@@ -247,35 +248,105 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  if (kc0 < kc1) {
-    gather(kc0);
-    stash(0);
-  }
-  __syncthreads();
-  for (int kc = kc0; kc < kc1; ++kc) {
-    const int buf = (kc - kc0) & 1;
-    if (kc + 1 < kc1) gather(kc + 1);
+  // Software pipeline: the global loads of NS steps are in flight in registers; each
+  // step moves the oldest one into the LDS buffer the previous step is not reading,
+  // refills its registers with the step NS ahead and multiplies. One barrier per step.
 #pragma unroll
-    for (int ks = 0; ks < BKB / 32; ++ks) {
-      uint4 px[TM], wt[TN];
-      const int koff = ks * 32 + (lane >> 5) * 16;
+  for (int st = 0; st < NS; ++st)
+    if (kc0 + st < kc1) gather(kc0 + st, ra_s[st], rb_s[st]);
+  for (int kc = kc0; kc < kc1; kc += NS) {
 #pragma unroll
-      for (int tm = 0; tm < TM; ++tm)
-        px[tm] = *(const uint4*)(As + (buf * BM + (wm * TM + tm) * 32 + (lane & 31)) * ROWB + koff);
+    for (int st = 0; st < NS; ++st) {
+      if (kc + st < kc1) {
+        const int buf = (NS % 2 == 0) ? (st & 1) : ((kc - kc0 + st) & 1);
+        stash(buf, ra_s[st], rb_s[st]);
+        __syncthreads();
+        if (kc + st + NS < kc1) gather(kc + st + NS, ra_s[st], rb_s[st]);
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-        wt[tn] = *(const uint4*)(Bs + (buf * BN + (wn * TN + tn) * 32 + (lane & 31)) * ROWB + koff);
+        for (int ks = 0; ks < BKB / 32; ++ks) {
+          uint4 px[TM], wt[TN];
+          const int koff = ks * 32 + (lane >> 5) * 16;
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
+          for (int tm = 0; tm < TM; ++tm)
+            px[tm] = *(const uint4*)(As + (buf * BM + (wm * TM + tm) * 32 + (lane & 31)) * ROWB + koff);
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
+          for (int tn = 0; tn < TN; ++tn)
+            wt[tn] = *(const uint4*)(Bs + (buf * BN + (wn * TN + tn) * 32 + (lane & 31)) * ROWB + koff);
+#pragma unroll
+          for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
+        }
+      }
     }
-    if (kc + 1 < kc1) stash(buf ^ 1);
-    __syncthreads();
   }
 
-  // ---- epilogue: lane holds, per 32x32 tile, pixel (lane & 31) and output channels
-  // g*8 + (lane >> 5)*4 + {0,1,2,3} for g = 0..3.
+  // ---- epilogue. In the accumulator a lane holds, per 32x32 tile, pixel (lane & 31) and
+  // channels g*8 + (lane >> 5)*4 + {0..3}, g = 0..3. The tile goes through LDS once so that
+  // consecutive lanes then own consecutive 16-byte pieces of a pixel's channels: bias,
+  // residual, activation and the one rounding are applied on whole vectors and every
+  // store (and residual load) of a wavefront covers contiguous runs of memory.
+  constexpr int VE = 16 / (int)sizeof(T);  // output elements per 16-byte store
+  if (p.C_out % VE == 0) {
+    constexpr int CP = BN + 4;  // fp32 pitch of the staged tile: conflict-free float4 rows
+    static_assert(BM * CP * 4 <= 2 * (BM + BN) * ROWB, "staged tile must fit the K-loop LDS");
+    float* const Cs = (float*)smem;
+    __syncthreads();  // every wavefront is done reading the operand tiles
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int row = (wm * TM + tm) * 32 + (lane & 31);
+          const int col = (wn * TN + tn) * 32 + g * 8 + (lane >> 5) * 4;
+          *(float4*)(Cs + row * CP + col) =
+              make_float4(acc[tn][tm][g * 4], acc[tn][tm][g * 4 + 1], acc[tn][tm][g * 4 + 2],
+                          acc[tn][tm][g * 4 + 3]);
+        }
+    __syncthreads();
+    constexpr int CPR = BN / VE;  // 16-byte pieces per pixel of the tile
+    T* __restrict__ yg = (T*)p.y;
+    const T* __restrict__ rg = (const T*)p.res;
+    for (int slot = tid; slot < BM * CPR; slot += 256) {
+      const int row = slot / CPR, c = (slot % CPR) * VE;
+      const int m = m0 + row, co = co0 + c;
+      if (m >= p.M || co >= p.C_out) continue;
+      float v[VE];
+#pragma unroll
+      for (int j = 0; j < VE; j += 4) {
+        const float4 t = *(const float4*)(Cs + row * CP + c + j);
+        v[j] = t.x; v[j + 1] = t.y; v[j + 2] = t.z; v[j + 3] = t.w;
+      }
+      if (p.ws) {
+        float* dst = p.ws + ((size_t)blockIdx.z * p.M + m) * p.C_out + co;
+#pragma unroll
+        for (int j = 0; j < VE; j += 4)
+          *(float4*)(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+        continue;
+      }
+      const PixelAddr pa = pixel_addr(p, m);
+      if (p.bias) {
+#pragma unroll
+        for (int j = 0; j < VE; j += 4) {
+          const float4 b4 = *(const float4*)(p.bias + co + j);
+          v[j] += b4.x; v[j + 1] += b4.y; v[j + 2] += b4.z; v[j + 3] += b4.w;
+        }
+      }
+      if (rg) {
+        alignas(16) T rr[VE];
+        *(uint4*)rr = *(const uint4*)(rg + pa.r + co);
+#pragma unroll
+        for (int j = 0; j < VE; ++j) v[j] += to_f32(rr[j]);
+      }
+      alignas(16) T o[VE];
+#pragma unroll
+      for (int j = 0; j < VE; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
+      *(uint4*)(yg + pa.y + co) = *(const uint4*)o;
+    }
+    return;
+  }
+  // channel counts that are not a multiple of the vector: straight from the registers
 #pragma unroll
   for (int tm = 0; tm < TM; ++tm) {
     const int m = m0 + (wm * TM + tm) * 32 + (lane & 31);
@@ -352,6 +423,7 @@ struct Choice {
 };
 
 constexpr int kBKB = 128;       // bytes of the reduction axis per row and step
+constexpr int kStages = 3;      // steps of global loads kept in flight
 constexpr int kComputeUnits = 256;
 
 // Largest tile that still gives every compute unit a workgroup; layers too small for
@@ -370,9 +442,11 @@ Choice choose(const ConvParams& p, int dtype) {
   const int nk = p.k_pad / bke;
   const long b = blocks(c.bm, c.bn);
   int splits = 1;
+  static const int target = getenv("LOP_SPLIT_TARGET") ? atoi(getenv("LOP_SPLIT_TARGET")) : 2 * kComputeUnits;
+  static const int minsteps = getenv("LOP_SPLIT_MINSTEPS") ? atoi(getenv("LOP_SPLIT_MINSTEPS")) : 4;
   if (b < kComputeUnits) {
-    splits = (int)((2 * kComputeUnits + b - 1) / b);
-    splits = std::min(splits, std::max(nk / 4, 1));
+    splits = (int)((target + b - 1) / b);
+    splits = std::min(splits, std::max(nk / minsteps, 1));
     splits = std::min(splits, 64);
   }
   c.kc_per_split = (nk + splits - 1) / splits;
@@ -384,9 +458,9 @@ template <typename T, int BM, int BN, int WM, int WN>
 hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
   if (vec_a)
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, true>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>), grid, dim3(256), 0, s, p);
   else
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, false>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>), grid, dim3(256), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !p.ws) return e;
   const long work = (long)p.M * ((p.C_out + 3) / 4);

@@ -54,6 +54,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // robin and the lanes run concurrently (bands are independent of one another).
 struct Lane {
   hipStream_t stream = nullptr;
+  hipStream_t copy = nullptr;  // reuse mode: this lane's copies overlap its next band
   void* arena = nullptr;    // scratch slabs of one band at a time
   void* conv_ws = nullptr;  // split-K partial sums of one launch at a time
   hipEvent_t ev_join = nullptr;
@@ -82,14 +83,23 @@ struct lop_plan_s {
   hipEvent_t ev_copy_tail = nullptr;
   struct GraphEntry {
     const void* d_in; void* d_out; void* h_out;
+    int lane;
     hipGraphExec_t exec;
   };
   std::vector<GraphEntry> graphs;  // LOP_FLAG_GRAPH: one instantiated graph per pointer set
   std::vector<std::pair<void*, void*>> host_views;  // host buffer -> device-side address
 
+  int cur_lane = 0;   // reuse mode: the lane the chain being enqueued runs on
+  int next_lane = 0;  // reuse mode: rotates with every lop_run_chain
+
   int n_lanes() const { return (int)lanes.size(); }
-  Lane& lane_of(int band) { return lanes[band % lanes.size()]; }
-  const Lane& lane_of(int band) const { return lanes[band % lanes.size()]; }
+  // Independent bands are dealt to the lanes round robin; in reuse mode a whole chain (all
+  // bands, in order) runs on one lane and consecutive chains rotate over the lanes.
+  int lane_index(int band) const { return t.reuse ? cur_lane : band % (int)lanes.size(); }
+  Lane& lane_of(int band) { return lanes[lane_index(band)]; }
+  const Lane& lane_of(int band) const { return lanes[lane_index(band)]; }
+  void* arena_of(int band) const { return lanes.empty() ? nullptr : lane_of(band).arena; }
+  void* ws_of(int band) const { return lanes.empty() ? nullptr : lane_of(band).conv_ws; }
 };
 
 namespace {
@@ -154,15 +164,25 @@ void size_scratch(lop_plan_t* P) {
   const int nl = t.n_layers();
   P->slab_off.assign(t.n_bands, std::vector<size_t>(nl, 0));
   size_t worst = 0;
-  for (int b = 0; b < t.n_bands; ++b) {
+  if (t.reuse) {
+    // bands share one full-height buffer per layer (rows at their absolute position)
     size_t off = 0;
-    for (int l = 0; l + 1 < nl; ++l) {  // the last layer writes the caller's output
-      const lop_rows_t r = t.bands[b].need[l + 1];
-      P->slab_off[b][l] = off;
-      if (r.hi > r.lo)
-        off += align_up((size_t)t.in.n * (r.hi - r.lo) * t.row_elems(l) * t.esz(), 256);
+    for (int l = 0; l + 1 < nl; ++l) {
+      for (int b = 0; b < t.n_bands; ++b) P->slab_off[b][l] = off;
+      off += align_up((size_t)t.in.n * t.layers[l].h_out * t.row_elems(l) * t.esz(), 256);
     }
-    worst = off > worst ? off : worst;
+    worst = off;
+  } else {
+    for (int b = 0; b < t.n_bands; ++b) {
+      size_t off = 0;
+      for (int l = 0; l + 1 < nl; ++l) {  // the last layer writes the caller's output
+        const lop_rows_t r = t.bands[b].need[l + 1];
+        P->slab_off[b][l] = off;
+        if (r.hi > r.lo)
+          off += align_up((size_t)t.in.n * (r.hi - r.lo) * t.row_elems(l) * t.esz(), 256);
+      }
+      worst = off > worst ? off : worst;
+    }
   }
   P->arena_bytes = worst;
 }
@@ -182,9 +202,13 @@ lop::Slab slab_of(const lop_plan_t* P, int band, int tensor, const void* d_in, v
     if (tensor == nl - 1) {
       s.ptr = d_out; s.row0 = 0; s.rows = s.h;
     } else {
-      const lop_rows_t r = t.bands[band].need[tensor + 1];
-      s.ptr = (char*)P->lane_of(band).arena + P->slab_off[band][tensor];
-      s.row0 = r.lo; s.rows = r.hi - r.lo;
+      s.ptr = (char*)P->arena_of(band) + P->slab_off[band][tensor];
+      if (t.reuse) {
+        s.row0 = 0; s.rows = s.h;
+      } else {
+        const lop_rows_t r = t.bands[band].need[tensor + 1];
+        s.row0 = r.lo; s.rows = r.hi - r.lo;
+      }
     }
   }
   return s;
@@ -204,17 +228,17 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
   o.ph = L.d.ph; o.pw = L.d.pw; o.dh = L.d.dh; o.dw = L.d.dw;
   o.act = L.d.act;
-  o.out_lo = t.bands[band].need[l + 1].lo;
-  o.out_hi = t.bands[band].need[l + 1].hi;
+  o.out_lo = t.bands[band].compute[l].lo;
+  o.out_hi = t.bands[band].compute[l].hi;
   o.k_pad = P->k_pad[l];
-  o.ws = P->lane_of(band).conv_ws;
+  o.ws = P->ws_of(band);
   return o;
 }
 
 int enqueue_band_kernels(lop_plan_t* P, int band, const void* d_in, void* d_out, hipStream_t cs) {
   const int nl = P->t.n_layers();
   for (int l = 0; l < nl; ++l) {
-    const lop_rows_t r = P->t.bands[band].need[l + 1];
+    const lop_rows_t r = P->t.bands[band].compute[l];
     if (r.hi <= r.lo) continue;
     const lop::OpLaunch o = make_launch(P, band, l, d_in, d_out);
     LOP_HIP(lop::launch_op(o, cs));
@@ -293,13 +317,13 @@ int setup_device(lop_plan_t* P) {
   for (int b = 0; b < nb; ++b) live += band_empty(P, b) ? 0 : 1;
   int want = (int)((P->flags >> 8) & 0xff);
   if (want == 0) want = LOP_DEFAULT_LANES;
-  const int n_lanes = std::max(1, std::min(want, live));
+  const int n_lanes = P->t.reuse ? std::max(1, want) : std::max(1, std::min(want, live));
   P->lanes.assign(n_lanes, Lane{});
   // the launch descriptors below only need sizes, not the scratch addresses
   for (int b = 0; b < nb; ++b)
     for (int l = 0; l < P->t.n_layers(); ++l) {
       if (P->t.layers[l].d.op != LOP_CONV2D) continue;
-      const lop_rows_t rr = P->t.bands[b].need[l + 1];
+      const lop_rows_t rr = P->t.bands[b].compute[l];
       if (rr.hi <= rr.lo) continue;
       const size_t need = lop::conv_workspace_bytes(make_launch(P, b, l, nullptr, nullptr));
       P->conv_ws_bytes = std::max(need, P->conv_ws_bytes);
@@ -310,6 +334,7 @@ int setup_device(lop_plan_t* P) {
       LOP_HIP(hipMalloc(&L.conv_ws, P->conv_ws_bytes));
     }
     LOP_HIP(hipStreamCreateWithFlags(&L.stream, hipStreamNonBlocking));
+    LOP_HIP(hipStreamCreateWithFlags(&L.copy, hipStreamNonBlocking));
     LOP_HIP(hipEventCreateWithFlags(&L.ev_join, hipEventDisableTiming));
   }
   LOP_HIP(hipStreamCreateWithFlags(&P->s_main, hipStreamNonBlocking));
@@ -385,9 +410,29 @@ int enqueue_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hip
   return LOP_OK;
 }
 
+// Bands of a reuse-mode chain, in order, on one lane; band b's copy runs on the lane's copy
+// stream under band b+1's kernels.
+int enqueue_chain_reuse(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, bool timing,
+                        bool capturing) {
+  Lane& L = P->lanes[P->cur_lane];
+  bool copied = false;
+  for (int b = 0; b < P->t.n_bands; ++b) {
+    if (band_empty(P, b)) continue;
+    int rc = enqueue_band(P, b, d_in, d_out, h_out, L.stream, L.copy, timing, capturing);
+    if (rc != LOP_OK) return rc;
+    copied = copied || (h_out && !(P->flags & LOP_FLAG_NO_D2H));
+  }
+  if (capturing && copied) {  // a captured graph has to join the stream it forked
+    LOP_HIP(hipEventRecord(P->ev_copy_tail, L.copy));
+    LOP_HIP(hipStreamWaitEvent(L.stream, P->ev_copy_tail, 0));
+  }
+  return LOP_OK;
+}
+
 int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms) {
+  const int lane = P->t.reuse ? P->cur_lane : -1;
   for (const auto& g : P->graphs)
-    if (g.d_in == d_in && g.d_out == d_out && g.h_out == h_out) {
+    if (g.d_in == d_in && g.d_out == d_out && g.h_out == h_out && g.lane == lane) {
       LOP_HIP(hipGraphLaunch(g.exec, ms));
       return LOP_OK;
     }
@@ -400,7 +445,8 @@ int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipS
   if (h_out) (void)device_view_of_host(P, h_out);  // query before capture starts
   hipGraph_t graph = nullptr;
   LOP_HIP(hipStreamBeginCapture(ms, hipStreamCaptureModeThreadLocal));
-  int rc = enqueue_chain(P, d_in, d_out, h_out, ms, false, true);
+  int rc = P->t.reuse ? enqueue_chain_reuse(P, d_in, d_out, h_out, false, true)
+                      : enqueue_chain(P, d_in, d_out, h_out, ms, false, true);
   hipError_t e = hipStreamEndCapture(ms, &graph);
   if (rc != LOP_OK) {
     if (graph) (void)hipGraphDestroy(graph);
@@ -411,11 +457,11 @@ int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipS
   e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
   (void)hipGraphDestroy(graph);
   if (e != hipSuccess) return hip_fail(e);
-  if (P->graphs.size() >= 8) {  // bounded cache: drop the oldest
+  if (P->graphs.size() >= 32) {  // bounded cache: drop the oldest
     (void)hipGraphExecDestroy(P->graphs.front().exec);
     P->graphs.erase(P->graphs.begin());
   }
-  P->graphs.push_back({d_in, d_out, h_out, exec});
+  P->graphs.push_back({d_in, d_out, h_out, lane, exec});
   LOP_HIP(hipGraphLaunch(exec, ms));
   return LOP_OK;
 }
@@ -430,7 +476,7 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
   *out_plan = nullptr;
   lop_plan_t* P = new (std::nothrow) lop_plan_t;
   if (!P) return LOP_ERR_OOM;
-  int rc = lop::build_tables(layers, n_layers, in, n_bands, P->t);
+  int rc = lop::build_tables(layers, n_layers, in, n_bands, (flags & LOP_FLAG_REUSE) != 0, P->t);
   if (rc != LOP_OK) { delete P; return rc; }
   P->flags = flags;
   size_scratch(P);
@@ -445,7 +491,10 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
 
 void lop_plan_destroy(lop_plan_t* P) {
   if (!P) return;
-  for (Lane& L : P->lanes) if (L.stream) (void)hipStreamSynchronize(L.stream);
+  for (Lane& L : P->lanes) {
+    if (L.stream) (void)hipStreamSynchronize(L.stream);
+    if (L.copy) (void)hipStreamSynchronize(L.copy);
+  }
   if (P->s_main) (void)hipStreamSynchronize(P->s_main);
   if (P->s_copy) (void)hipStreamSynchronize(P->s_copy);
   for (void* w : P->d_w) if (w) (void)hipFree(w);
@@ -459,6 +508,7 @@ void lop_plan_destroy(lop_plan_t* P) {
     if (L.conv_ws) (void)hipFree(L.conv_ws);
     if (L.ev_join) (void)hipEventDestroy(L.ev_join);
     if (L.stream) (void)hipStreamDestroy(L.stream);
+    if (L.copy) (void)hipStreamDestroy(L.copy);
   }
   if (P->s_main) (void)hipStreamDestroy(P->s_main);
   if (P->s_copy) (void)hipStreamDestroy(P->s_copy);
@@ -498,6 +548,16 @@ int lop_plan_band_out_rows(const lop_plan_t* P, int band, lop_rows_t* rows) {
   return LOP_OK;
 }
 
+int lop_plan_band_compute_rows(const lop_plan_t* P, int band, int layer, lop_rows_t* rows) {
+  if (!P || !rows) return LOP_ERR_INVALID_ARG;
+  if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
+    return LOP_ERR_BAND_RANGE;
+  lop_rows_t r = P->t.bands[band].compute[layer];
+  if (r.hi <= r.lo) r = {0, 0};
+  *rows = r;
+  return LOP_OK;
+}
+
 int lop_plan_band_in_rows(const lop_plan_t* P, int band, lop_rows_t* rows) {
   return lop_plan_band_layer_rows(P, band, -1, rows);
 }
@@ -508,7 +568,7 @@ int lop_plan_stats(const lop_plan_t* P, double* useful, double* executed, size_t
   for (int l = 0; l < P->t.n_layers(); ++l) {
     u += P->t.layer_flop(l, P->t.layers[l].h_out);
     for (int b = 0; b < P->t.n_bands; ++b) {
-      const lop_rows_t r = P->t.bands[b].need[l + 1];
+      const lop_rows_t r = P->t.bands[b].compute[l];
       if (r.hi > r.lo) e += P->t.layer_flop(l, r.hi - r.lo);
     }
   }
@@ -522,7 +582,7 @@ int lop_plan_layer_work(const lop_plan_t* P, int band, int layer, double* flop, 
   if (!P) return LOP_ERR_INVALID_ARG;
   if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
     return LOP_ERR_BAND_RANGE;
-  const lop_rows_t r = P->t.bands[band].need[layer + 1];
+  const lop_rows_t r = P->t.bands[band].compute[layer];
   if (flop) *flop = r.hi > r.lo ? P->t.layer_flop(layer, r.hi - r.lo) : 0.0;
   if (bytes) *bytes = P->t.layer_bytes(band, layer);
   return LOP_OK;
@@ -554,15 +614,35 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
     rc = lop_synchronize(P);
     if (rc != LOP_OK) return rc;
   }
-  if ((P->flags & LOP_FLAG_GRAPH) && !timing) return launch_graph(P, d_in, d_out, h_out, ms);
   const auto t0 = std::chrono::steady_clock::now();
-  if (timing) LOP_HIP(hipEventRecord(P->ev_t0, ms));
-  {
+  if (P->t.reuse) {
+    // the whole chain runs on one lane; chains of consecutive calls rotate over the lanes
+    // and overlap unless the caller's stream orders them
+    P->cur_lane = P->next_lane;
+    P->next_lane = (P->next_lane + 1) % P->n_lanes();
+    Lane& L = P->lanes[P->cur_lane];
+    if (compute_stream) {
+      LOP_HIP(hipEventRecord(P->ev_fork, ms));
+      LOP_HIP(hipStreamWaitEvent(L.stream, P->ev_fork, 0));
+    }
+    if (timing) LOP_HIP(hipEventRecord(P->ev_t0, L.stream));
+    int rc = ((P->flags & LOP_FLAG_GRAPH) && !timing)
+                 ? launch_graph(P, d_in, d_out, h_out, L.stream)
+                 : enqueue_chain_reuse(P, d_in, d_out, h_out, timing != nullptr, false);
+    if (rc != LOP_OK) return rc;
+    if (timing) LOP_HIP(hipEventRecord(P->ev_t1, L.stream));
+    if (compute_stream) {
+      LOP_HIP(hipEventRecord(L.ev_join, L.stream));
+      LOP_HIP(hipStreamWaitEvent(ms, L.ev_join, 0));
+    }
+  } else {
+    if ((P->flags & LOP_FLAG_GRAPH) && !timing) return launch_graph(P, d_in, d_out, h_out, ms);
+    if (timing) LOP_HIP(hipEventRecord(P->ev_t0, ms));
     int rc = enqueue_chain(P, d_in, d_out, h_out, ms, timing != nullptr, false);
     if (rc != LOP_OK) return rc;
+    if (timing) LOP_HIP(hipEventRecord(P->ev_t1, ms));
   }
   if (!timing) return LOP_OK;
-  LOP_HIP(hipEventRecord(P->ev_t1, ms));
   int rc = lop_synchronize(P);
   if (rc != LOP_OK) return rc;
   const auto t1 = std::chrono::steady_clock::now();
@@ -585,7 +665,10 @@ int lop_synchronize(lop_plan_t* P) {
   if (!P) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   if (P->last_user_stream) LOP_HIP(hipStreamSynchronize(P->last_user_stream));
-  for (Lane& L : P->lanes) LOP_HIP(hipStreamSynchronize(L.stream));
+  for (Lane& L : P->lanes) {
+    LOP_HIP(hipStreamSynchronize(L.stream));
+    LOP_HIP(hipStreamSynchronize(L.copy));
+  }
   LOP_HIP(hipStreamSynchronize(P->s_main));
   LOP_HIP(hipStreamSynchronize(P->s_copy));
   return LOP_OK;
@@ -598,7 +681,7 @@ int lop_time_layer(lop_plan_t* P, int band, int layer, const void* d_in, void* d
     return LOP_ERR_BAND_RANGE;
   if (!P->ready) return LOP_ERR_NOT_READY;
   *ms_per_launch = 0.f;
-  const lop_rows_t r = P->t.bands[band].need[layer + 1];
+  const lop_rows_t r = P->t.bands[band].compute[layer];
   if (r.hi <= r.lo) return LOP_OK;
   int rc = ensure_timing_events(P);
   if (rc != LOP_OK) return rc;
@@ -619,7 +702,7 @@ int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, 
   if (!P || !name || size == 0) return LOP_ERR_INVALID_ARG;
   if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
     return LOP_ERR_BAND_RANGE;
-  const lop_rows_t r = P->t.bands[band].need[layer + 1];
+  const lop_rows_t r = P->t.bands[band].compute[layer];
   const char* n = "";
   if (r.hi > r.lo) n = lop::kernel_name(make_launch(P, band, layer, nullptr, nullptr));
   std::strncpy(name, n, size - 1);
@@ -640,7 +723,7 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
     for (int it = 0; it < iters; ++it) {
       for (int b = 0; b < nb; ++b)
         for (int l = 0; l < nl; ++l) {
-          const lop_rows_t r = P->t.bands[b].need[l + 1];
+          const lop_rows_t r = P->t.bands[b].compute[l];
           if (r.hi <= r.lo) continue;
           const lop::OpLaunch o = make_launch(P, b, l, d_in, d_out);
           const size_t i = ((size_t)b * nl + l) * 2;
@@ -651,7 +734,7 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
       LOP_HIP(hipStreamSynchronize(cs));
       for (int b = 0; b < nb; ++b)
         for (int l = 0; l < nl; ++l) {
-          const lop_rows_t r = P->t.bands[b].need[l + 1];
+          const lop_rows_t r = P->t.bands[b].compute[l];
           if (r.hi <= r.lo) continue;
           const size_t i = ((size_t)b * nl + l) * 2;
           float ms = 0.f;

@@ -57,7 +57,7 @@ double Tables::layer_flop(int l, int rows) const {
 double Tables::layer_bytes(int band, int l) const {
   const LayerInfo& L = layers[l];
   const BandRows& B = bands[band];
-  const lop_rows_t out = B.need[l + 1];
+  const lop_rows_t out = B.compute[l];
   if (empty(out)) return 0.0;
   const lop_rows_t rd = B.reads[l];
   const double e = (double)esz();
@@ -70,14 +70,24 @@ double Tables::layer_bytes(int band, int l) const {
   return bytes;
 }
 
+static lop_rows_t reads_of(const LayerInfo& L, lop_rows_t o) {
+  lop_rows_t src{0, 0};
+  if (empty(o)) return src;
+  src.lo = std::max(o.lo * L.d.sh - L.d.ph, 0);
+  src.hi = std::min((o.hi - 1) * L.d.sh - L.d.ph + L.d.dh * (L.d.kh - 1) + 1, L.h_in);
+  if (src.hi < src.lo) src.hi = src.lo;
+  return src;
+}
+
 int build_tables(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* in,
-                 int n_bands, Tables& t) {
+                 int n_bands, bool reuse, Tables& t) {
   if (!layers || !in || n_layers < 1) return LOP_ERR_INVALID_ARG;
   if (n_bands < 1 || n_bands > LOP_MAX_BANDS) return LOP_ERR_INVALID_ARG;
   if (in->n < 1 || in->c < 1 || in->h < 1 || in->w < 1) return LOP_ERR_INVALID_ARG;
   if (in->dtype != LOP_F32 && in->dtype != LOP_BF16) return LOP_ERR_UNSUPPORTED;
   t.in = *in;
   t.n_bands = n_bands;
+  t.reuse = reuse;
   t.layers.assign(n_layers, LayerInfo{});
 
   // ---- forward: shapes
@@ -139,13 +149,28 @@ int build_tables(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_
       const LayerInfo& L = t.layers[i];
       const lop_rows_t o = B.need[i + 1];
       if (empty(o)) continue;
-      lop_rows_t src;
-      src.lo = std::max(o.lo * L.d.sh - L.d.ph, 0);
-      src.hi = std::min((o.hi - 1) * L.d.sh - L.d.ph + L.d.dh * (L.d.kh - 1) + 1, L.h_in);
-      if (src.hi < src.lo) src.hi = src.lo;
-      B.reads[i] = src;
+      const lop_rows_t src = reads_of(L, o);
       hull_into(B.need[L.d.input_from + 1], src);
       if (L.d.residual_from != LOP_NO_RESIDUAL) hull_into(B.need[L.d.residual_from + 1], o);
+    }
+  }
+  // ---- what each band's launches produce. The needed intervals move monotonically down
+  // the image with the band index, so "rows some earlier band produced" is everything
+  // below the highest `hi` seen so far; rows of need[] below that mark are already there.
+  std::vector<int> done_hi(n_layers, 0);
+  for (int b = 0; b < n_bands; ++b) {
+    BandRows& B = t.bands[b];
+    B.compute.assign(n_layers, lop_rows_t{0, 0});
+    for (int i = 0; i < n_layers; ++i) {
+      lop_rows_t c = B.need[i + 1];
+      if (empty(c)) continue;
+      if (reuse) {
+        c.lo = std::max(c.lo, done_hi[i]);
+        if (c.hi <= c.lo) { c = {0, 0}; }
+        done_hi[i] = std::max(done_hi[i], B.need[i + 1].hi);
+      }
+      B.compute[i] = c;
+      B.reads[i] = reads_of(t.layers[i], c);
     }
   }
   return LOP_OK;

@@ -20,14 +20,18 @@ struct LayerInfo {
 // Row intervals of one band. need[0] is the chain input, need[l + 1] is layer l's output.
 struct BandRows {
   std::vector<lop_rows_t> need;
-  // reads[l]: rows of layer l's *input* tensor that layer l itself touches for this band
-  // (the producer's slab may be larger because of other consumers).
+  // compute[l]: rows of layer l's output this band's launch produces. Independent bands:
+  // all of need[l + 1]. Reuse mode: only the rows no earlier band has produced.
+  std::vector<lop_rows_t> compute;
+  // reads[l]: rows of layer l's *input* tensor that the launch touches (the producer's
+  // slab may be larger because of other consumers).
   std::vector<lop_rows_t> reads;
 };
 
 struct Tables {
   lop_tensor_desc_t in{};
   int n_bands = 0;
+  bool reuse = false;
   std::vector<LayerInfo> layers;
   std::vector<BandRows> bands;
 
@@ -49,7 +53,9 @@ int out_size(int in, int k, int s, int p, int d);
 void split_rows(int h, int n, std::vector<lop_rows_t>& out);
 
 // Validate the chain and fill shapes and per-band row intervals. Returns a lop_status_t.
+// reuse: bands run in order and share per-layer buffers, so a band only computes the rows
+// of each layer that bands before it have not produced (no halo recompute).
 int build_tables(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* in,
-                 int n_bands, Tables& t);
+                 int n_bands, bool reuse, Tables& t);
 
 }  // namespace lop

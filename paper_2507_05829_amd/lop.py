@@ -32,6 +32,7 @@ LOP_F32, LOP_BF16 = 0, 1
 LOP_INPUT, LOP_NO_RESIDUAL = -1, -2
 LOP_MAX_BANDS = 64
 LOP_FLAG_NO_D2H, LOP_FLAG_PLAN_ONLY, LOP_FLAG_GRAPH, LOP_FLAG_DMA_COPY = 1, 2, 4, 8
+LOP_FLAG_REUSE = 16
 
 
 def LOP_FLAG_LANES(n: int) -> int:
@@ -44,6 +45,7 @@ EXPORTS = [
     "lop_plan_band_layer_rows", "lop_plan_stats", "lop_plan_layer_work", "lop_run_band",
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
     "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
+    "lop_plan_band_compute_rows",
 ]
 
 
@@ -86,6 +88,7 @@ def _load() -> ctypes.CDLL:
         "lop_plan_band_out_rows": (c_int, [P, c_int, POINTER(lop_rows_t)]),
         "lop_plan_band_in_rows": (c_int, [P, c_int, POINTER(lop_rows_t)]),
         "lop_plan_band_layer_rows": (c_int, [P, c_int, c_int, POINTER(lop_rows_t)]),
+        "lop_plan_band_compute_rows": (c_int, [P, c_int, c_int, POINTER(lop_rows_t)]),
         "lop_plan_stats": (c_int, [P, POINTER(c_double), POINTER(c_double), POINTER(c_size_t)]),
         "lop_plan_layer_work": (c_int, [P, c_int, c_int, POINTER(c_double), POINTER(c_double)]),
         "lop_run_band": (c_int, [P, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -191,6 +194,10 @@ def lop_plan_band_in_rows(plan, band: int) -> Tuple[int, int]:
 
 def lop_plan_band_layer_rows(plan, band: int, layer: int) -> Tuple[int, int]:
     return _rows(_lib.lop_plan_band_layer_rows, "lop_plan_band_layer_rows", plan, band, layer)
+
+
+def lop_plan_band_compute_rows(plan, band: int, layer: int) -> Tuple[int, int]:
+    return _rows(_lib.lop_plan_band_compute_rows, "lop_plan_band_compute_rows", plan, band, layer)
 
 
 def lop_plan_stats(plan) -> Tuple[float, float, int]:
@@ -330,6 +337,7 @@ class Plan:
     def band_out_rows(self, b): return lop_plan_band_out_rows(self.handle, b)
     def band_in_rows(self, b): return lop_plan_band_in_rows(self.handle, b)
     def band_layer_rows(self, b, l): return lop_plan_band_layer_rows(self.handle, b, l)
+    def band_compute_rows(self, b, l): return lop_plan_band_compute_rows(self.handle, b, l)
     def stats(self): return lop_plan_stats(self.handle)
     def layer_work(self, b, l): return lop_plan_layer_work(self.handle, b, l)
 

@@ -136,3 +136,47 @@ def test_band_range_and_not_ready():
     finally:
         lop.lop_plan_destroy(h)
     lop.lop_plan_destroy(None)                   # destroying NULL is a no-op
+
+
+@pytest.mark.parametrize("name", list(workloads.CONFIGS))
+def test_reuse_planner_matches_oracle_bit_exact(name):
+    chain = workloads.CONFIGS[name]()
+    plan = lop.Plan(chain, flags=lop.LOP_FLAG_REUSE)
+    want = oplan.plan_reuse(chain)
+    need = oplan.plan(chain)
+    for b in range(chain.n_bands):
+        for l in range(len(chain.layers)):
+            exp = want[b][l]
+            assert plan.band_compute_rows(b, l) == ((0, 0) if exp is None else exp), (name, b, l)
+            n = need[b][l]
+            assert plan.band_layer_rows(b, l) == ((0, 0) if n is None else n)
+    u, e, _ = plan.stats()
+    ou, oe = oplan.flop_counts_reuse(chain)
+    assert u == ou and e == oe
+    # independent plans compute exactly what they need
+    ind = lop.Plan(chain)
+    for b in range(chain.n_bands):
+        for l in range(len(chain.layers)):
+            assert ind.band_compute_rows(b, l) == ind.band_layer_rows(b, l)
+
+
+def test_reuse_planner_random_chains():
+    from test_oracle_planner import _random_chain
+    rng = np.random.default_rng(9)
+    done = 0
+    while done < 100:
+        chain = _random_chain(rng)
+        if chain is None or any(L.op == "maxpool" and L.p[0] >= L.k[0] for L in chain.layers):
+            continue
+        if any(L.d[0] > 1 and L.k[0] > 1 for L in chain.layers):
+            continue        # with dilation the closed form is a superset (see the planner pins)
+        done += 1
+        plan = lop.Plan(chain, flags=lop.LOP_FLAG_REUSE)
+        try:
+            want = oplan.plan_reuse(chain)
+        except AssertionError:
+            continue        # a chain whose fresh rows are not one interval is not plannable
+        for b in range(chain.n_bands):
+            for l in range(len(chain.layers)):
+                exp = want[b][l]
+                assert plan.band_compute_rows(b, l) == ((0, 0) if exp is None else exp), (chain, b, l)

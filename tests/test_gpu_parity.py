@@ -263,3 +263,71 @@ def test_graph_replays_match_eager(oracle):
             assert rel_err(to_nchw(h_g), oracle.run_chain(chain, tt)) <= TOL["f32"]
         (d_ref * 2).sum().item()          # unrelated eager work between replays
     eager.destroy(); graph.destroy()
+
+
+@pytest.mark.parametrize("name,kw", SCALED + [("tiny", dict())])
+@pytest.mark.parametrize("graph", [0, 1])
+def test_reuse_mode_scaled_chains(oracle, name, kw, graph):
+    """LOP_FLAG_REUSE: no halo recompute, bands in order on shared buffers. Same oracle."""
+    chain = workloads.CONFIGS[name](**kw)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    flags = lop.LOP_FLAG_REUSE | (lop.LOP_FLAG_GRAPH if graph else 0)
+    plan = lop.Plan(chain, t, flags=flags)
+    d_in = to_device_nhwc(t.x, chain.dtype)
+    # more calls than lanes: every lane (own buffers, own graph) is used at least twice
+    for rep in range(9):
+        d_out = empty_out(plan.out_shape(), chain.dtype)
+        h_out = empty_out(plan.out_shape(), chain.dtype, pinned=True)
+        plan.run_chain(d_in, d_out, h_out)
+        plan.synchronize()
+        got = to_nchw(d_out)
+        assert rel_err(got, want) <= TOL[chain.dtype], rep
+        np.testing.assert_array_equal(to_nchw(h_out), got)
+    u, e, _ = plan.stats()
+    assert e <= u * (1 + 1e-9)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("name", ["resnet18", "vgg16", "detector720p"])
+def test_reuse_mode_full_size(oracle, name):
+    chain = workloads.CONFIGS[name]()
+    t = workloads.make_tensors(chain)
+    want = oracle.run_chain(chain, t)
+    dev, host = run_gpu(chain, t, flags=lop.LOP_FLAG_REUSE)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL[chain.dtype]
+
+
+def test_reuse_mode_small_integers_bit_exact(oracle):
+    chain = workloads.Chain("ints", (2, 8, 40, 24), "f32", 5)
+    chain.add(workloads.CONV, 8, 8, 3, 1, 1, act="relu")
+    chain.add(workloads.MAXPOOL, 8, 8, 2, 2, 0)
+    chain.add(workloads.CONV, 8, 16, 3, 2, 1, act="none")
+    chain.add(workloads.DWCONV, 16, 16, 3, 1, 1, act="relu6")
+    chain.add(workloads.CONV, 16, 16, 1, 1, 0, act="none", residual_from=2)
+    t = workloads.small_int_tensors(chain, seed=21)
+    for i, w_ in enumerate(t.weights):
+        if w_ is not None:
+            t.weights[i] = np.sign(w_) * (np.abs(w_) > 1)     # keep sums small and exact
+    want = oracle.run_chain(chain, t)
+    dev, host = run_gpu(chain, t, flags=lop.LOP_FLAG_REUSE)
+    np.testing.assert_array_equal(dev, want)
+    np.testing.assert_array_equal(host, want)
+
+
+def test_reuse_mode_run_band_in_order(oracle):
+    chain = workloads.tiny_chain()
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    plan = lop.Plan(chain, t, flags=lop.LOP_FLAG_REUSE)
+    d_in = to_device_nhwc(t.x, chain.dtype)
+    d_out = empty_out(plan.out_shape(), chain.dtype)
+    h_out = empty_out(plan.out_shape(), chain.dtype, pinned=True)
+    for b in range(plan.n_bands):
+        plan.run_band(b, d_in, d_out, h_out)
+        plan.synchronize()
+        lo, hi = plan.band_out_rows(b)
+        assert rel_err(to_nchw(h_out)[:, :, :hi], want[:, :, :hi]) <= TOL["f32"]
+        assert np.isnan(to_nchw(h_out)[:, :, hi:]).all()
+    plan.destroy()

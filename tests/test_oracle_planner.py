@@ -174,3 +174,31 @@ def test_config_shapes_and_replication_ratios():
         assert need[-1] == (0, 224)
     # vgg16 with 8 bands over 7 rows: the last band is empty
     assert planner.plan(workloads.vgg16_chain())[7][17] is None
+
+
+@pytest.mark.parametrize("name", list(workloads.CONFIGS))
+def test_reuse_plan_invariants(name):
+    """Reuse mode: the rows the bands compute of a layer are disjoint, their union is the
+    union of the bands' needs, and in total nothing is computed twice: executed work equals
+    the work of the rows that are needed at all (for these chains: every row)."""
+    chain = workloads.CONFIGS[name]()
+    shapes = planner.infer_shapes(chain)
+    fresh = planner.plan_reuse(chain)
+    need = [planner.plan_brute_force(chain, br)
+            for br in planner.split_rows(shapes[-1][2], chain.n_bands)]
+    for t in range(len(chain.layers)):
+        seen = set()
+        for b in range(chain.n_bands):
+            if fresh[b][t] is not None:
+                rows = set(range(*fresh[b][t]))
+                assert not (rows & seen)
+                seen |= rows
+        needed = set()
+        for b in range(chain.n_bands):
+            if need[b][t] is not None:
+                needed |= set(range(*need[b][t]))
+        assert seen == needed
+    u, e = planner.flop_counts_reuse(chain)
+    assert e <= u * (1 + 1e-12)
+    if name in ("tiny", "vgg16", "detector720p", "mbv2"):
+        assert e == pytest.approx(u)        # every row of every layer is needed by some band
