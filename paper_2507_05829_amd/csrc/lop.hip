@@ -410,20 +410,24 @@ int enqueue_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hip
   return LOP_OK;
 }
 
-// Bands of a reuse-mode chain, in order, on one lane; band b's copy runs on the lane's copy
-// stream under band b+1's kernels.
+// Bands of a reuse-mode chain, in order, on one lane.
 int enqueue_chain_reuse(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, bool timing,
                         bool capturing) {
   Lane& L = P->lanes[P->cur_lane];
+  // With several lanes a band's copy follows its kernels on the lane and overlaps the
+  // other lanes' chains (cross-stream edges inside a captured graph were measured to
+  // serialise the lanes); a single lane uses its copy stream so that band b's copy
+  // overlaps band b+1's kernels.
+  hipStream_t ds = P->n_lanes() > 1 ? L.stream : L.copy;
   bool copied = false;
   for (int b = 0; b < P->t.n_bands; ++b) {
     if (band_empty(P, b)) continue;
-    int rc = enqueue_band(P, b, d_in, d_out, h_out, L.stream, L.copy, timing, capturing);
+    int rc = enqueue_band(P, b, d_in, d_out, h_out, L.stream, ds, timing, capturing);
     if (rc != LOP_OK) return rc;
     copied = copied || (h_out && !(P->flags & LOP_FLAG_NO_D2H));
   }
-  if (capturing && copied) {  // a captured graph has to join the stream it forked
-    LOP_HIP(hipEventRecord(P->ev_copy_tail, L.copy));
+  if (capturing && copied && ds != L.stream) {  // a captured graph joins the stream it forked
+    LOP_HIP(hipEventRecord(P->ev_copy_tail, ds));
     LOP_HIP(hipStreamWaitEvent(L.stream, P->ev_copy_tail, 0));
   }
   return LOP_OK;
