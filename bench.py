@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--mode", default="independent", choices=["independent", "reuse"],
                     help="independent: every band recomputes its halos; reuse: bands run in "
                          "order and reuse rows earlier bands produced")
+    ap.add_argument("--pmc-calibrate", action="store_true",
+                    help="also run a plain 256 MiB device-to-device copy (torch) a few times so "
+                         "that a counter run can be scaled by a kernel of known traffic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--profile-iters", type=int, default=10)
@@ -82,28 +85,38 @@ def timed_copies(torch, plan, d_out, h_out, steps, warmup):
     return time.perf_counter() - t0
 
 
-def kernel_table(plan, d_in, d_out, iters):
-    """Per kernel variant: launches per step, mean duration, algorithmic work."""
-    ms = plan.profile_chain(d_in, d_out, iters)
+def kernel_table(plan, d_in, d_out, iters, dtype):
+    """Per kernel instance (named as rocprofv3 prints it): launches per chain, mean duration
+    from HIP events around every launch on its stream, algorithmic work. The finish kernel
+    of a split-K convolution is listed on its own; the layer's algorithmic FLOP and bytes
+    are booked on the convolution kernel."""
+    ms, fin = plan.profile_chain(d_in, d_out, iters)
     groups = {}
+
+    def add(name, t, flop, byts):
+        g = groups.setdefault(name, dict(name=name, launches=0, ms=0.0, flop=0.0, bytes=0.0))
+        g["launches"] += 1
+        g["ms"] += t
+        g["flop"] += flop
+        g["bytes"] += byts
+
     for b in range(plan.n_bands):
         for l in range(plan.n_layers):
-            name = plan.layer_kernel(b, l)
+            name, slices = plan.layer_kernel(b, l)
             if not name:
                 continue
             flop, byts = plan.layer_work(b, l)
-            g = groups.setdefault(name, dict(name=name, launches=0, ms=0.0, flop=0.0, bytes=0.0))
-            g["launches"] += 1
-            g["ms"] += float(ms[b, l])
-            g["flop"] += flop
-            g["bytes"] += byts
+            add(name, float(ms[b, l]), flop, byts)
+            if slices > 1:
+                add("splitk_finish_kernel<%s>" % ("__bf16" if dtype == "bf16" else "float"),
+                    float(fin[b, l]), 0.0, 0.0)
     out = []
     for g in sorted(groups.values(), key=lambda g: -g["ms"]):
         t = g["ms"] * 1e-3
         out.append(dict(name=g["name"], launches=g["launches"], total_ms=round(g["ms"], 4),
                         avg_us=round(g["ms"] * 1e3 / g["launches"], 3),
-                        tflops=round(g["flop"] / t / 1e12, 3) if t > 0 else None,
-                        gbs=round(g["bytes"] / t / 1e9, 1) if t > 0 else None,
+                        tflops=round(g["flop"] / t / 1e12, 3) if t > 0 and g["flop"] else None,
+                        gbs=round(g["bytes"] / t / 1e9, 1) if t > 0 and g["bytes"] else None,
                         flop_per_launch=g["flop"] / g["launches"],
                         bytes_per_launch=g["bytes"] / g["launches"]))
     return out
@@ -115,7 +128,7 @@ def roofline_of(k, dtype):
     mf_peak = PEAK["mfma_bf16"] if dtype == "bf16" else PEAK["mfma_f32"]
     ai = k["flop_per_launch"] / max(k["bytes_per_launch"], 1.0)
     ridge = mf_peak * 1e12 / (PEAK["hbm"] * 1e9)
-    if k["name"].startswith("conv_igemm") and ai >= ridge:
+    if k["name"].startswith("conv_igemm") and ai >= ridge:  # a dense contraction above the ridge
         a = k["tflops"]
         return dict(bound="mfma", achieved=a, peak=mf_peak, unit="TFLOP/s",
                     frac=round(a / mf_peak, 4), traffic=None, kernel=k["name"],
@@ -157,7 +170,7 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
     med = lambda v: v[len(v) // 2]
     hidden_single = 1.0 - max(0.0, med(lat) - med(lat_nc)) / max(med(cp), 1e-9)
 
-    kernels = kernel_table(plan, d_in, d_out[0], profile_iters)
+    kernels = kernel_table(plan, d_in, d_out[0], profile_iters, chain.dtype)
     res = dict(
         workload=name, mode=mode, dtype=chain.dtype, n_bands=plan.n_bands, n_layers=plan.n_layers,
         images_per_s=n_img * steps / t_c, ms_per_step=t_c / steps * 1e3,
@@ -171,7 +184,7 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
         scratch_mb=round(scratch / 2 ** 20, 2),
         kernels=[{k: v for k, v in kk.items() if not k.endswith("_per_launch")} for kk in kernels],
     )
-    roof = roofline_of(kernels[0], chain.dtype)
+    roof = roofline_of(next(k for k in kernels if k["flop_per_launch"] > 0), chain.dtype)
     for p in plans:
         p.destroy()
     return chain, tensors, res, roof
@@ -211,6 +224,13 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
 
+    if a.pmc_calibrate:
+        src = torch.zeros(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     chain, tensors, res, roof = run_workload(torch, lop, workloads, a.workload, a.steps, a.warmup,
                                              a.bands, a.profile_iters, a.lanes, a.graph, a.dma_copy, a.replicas, a.mode)
     also = []

@@ -171,15 +171,21 @@ LOP_API int lop_synchronize(lop_plan_t* plan);
 LOP_API int lop_time_layer(lop_plan_t* plan, int band, int layer, const void* d_in, void* d_out,
                    int iters, float* ms_per_launch);
 
-/* Name of the kernel variant that runs `layer` for `band` (empty string for an empty
- * interval), copied into name[size]. Measurement aid: lets a profile be grouped by kernel. */
-LOP_API int lop_plan_layer_kernel(const lop_plan_t* plan, int band, int layer, char* name, size_t size);
+/* Name of the kernel instance that runs `layer` for `band`, as a profiler prints it without
+ * namespace and argument list (empty string when the band computes no row of the layer),
+ * copied into name[size]; *k_slices (optional) receives the number of slices its reduction
+ * axis is cut into: 1 = one kernel, > 1 = that kernel followed by splitk_finish_kernel,
+ * 0 = nothing to run. Measurement aid: lets a profile be grouped by kernel. */
+LOP_API int lop_plan_layer_kernel(const lop_plan_t* plan, int band, int layer, char* name, size_t size,
+                                  int* k_slices);
 
-/* Run the whole chain `iters` times on the plan's compute stream with an event before and
- * after every kernel and write the mean milliseconds of each (band, layer) launch to
- * layer_ms[band * n_layers + layer] (host, n_bands * n_layers floats). No host copies.
- * Synchronous. Measurement aid. */
-LOP_API int lop_profile_chain(lop_plan_t* plan, const void* d_in, void* d_out, int iters, float* layer_ms);
+/* Run the whole chain `iters` times, bands in order on one stream, with an event before and
+ * after every kernel, and write the mean milliseconds of each (band, layer) main kernel to
+ * layer_ms[band * n_layers + layer] and of its splitk_finish_kernel (0 if none) to
+ * finish_ms[...] (host, n_bands * n_layers floats each; finish_ms may be NULL, the finish
+ * time is then not reported). No host copies. Synchronous. Measurement aid. */
+LOP_API int lop_profile_chain(lop_plan_t* plan, const void* d_in, void* d_out, int iters, float* layer_ms,
+                              float* finish_ms);
 
 /* Enqueue only the bands' device-to-host copies, back to back on the plan's copy stream
  * (the transmission leg alone, to measure how much of it the pipelined run hides). */

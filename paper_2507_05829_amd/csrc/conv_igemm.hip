@@ -17,7 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <cstdlib>
+#include <cstdio>
 
 #include "kernels.hpp"
 #include "lop.h"
@@ -124,6 +124,30 @@ __device__ __forceinline__ void finish4(const ConvParams& p, const PixelAddr& a,
       yg[a.y + co + j] = from_f32<T>(apply_act(u, p.act));
     }
   }
+}
+
+// bias + residual + activation + the one rounding for VE consecutive channels (one
+// 16-byte vector of the storage type) of output pixel m.
+template <typename T, int VE>
+__device__ __forceinline__ void finish_vec(const ConvParams& p, int m, int co, float* v) {
+  const PixelAddr pa = pixel_addr(p, m);
+  if (p.bias) {
+#pragma unroll
+    for (int j = 0; j < VE; j += 4) {
+      const float4 b4 = *(const float4*)(p.bias + co + j);
+      v[j] += b4.x; v[j + 1] += b4.y; v[j + 2] += b4.z; v[j + 3] += b4.w;
+    }
+  }
+  if (p.res) {
+    alignas(16) T rr[VE];
+    *(uint4*)rr = *(const uint4*)((const T*)p.res + pa.r + co);
+#pragma unroll
+    for (int j = 0; j < VE; ++j) v[j] += to_f32(rr[j]);
+  }
+  alignas(16) T o[VE];
+#pragma unroll
+  for (int j = 0; j < VE; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
+  *(uint4*)((T*)p.y + pa.y + co) = *(const uint4*)o;
 }
 
 // BM pixels x BN channels per workgroup; WM x WN wavefronts; BKB bytes of the reduction
@@ -306,8 +330,6 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
         }
     __syncthreads();
     constexpr int CPR = BN / VE;  // 16-byte pieces per pixel of the tile
-    T* __restrict__ yg = (T*)p.y;
-    const T* __restrict__ rg = (const T*)p.res;
     for (int slot = tid; slot < BM * CPR; slot += 256) {
       const int row = slot / CPR, c = (slot % CPR) * VE;
       const int m = m0 + row, co = co0 + c;
@@ -325,24 +347,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
           *(float4*)(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
         continue;
       }
-      const PixelAddr pa = pixel_addr(p, m);
-      if (p.bias) {
-#pragma unroll
-        for (int j = 0; j < VE; j += 4) {
-          const float4 b4 = *(const float4*)(p.bias + co + j);
-          v[j] += b4.x; v[j + 1] += b4.y; v[j + 2] += b4.z; v[j + 3] += b4.w;
-        }
-      }
-      if (rg) {
-        alignas(16) T rr[VE];
-        *(uint4*)rr = *(const uint4*)(rg + pa.r + co);
-#pragma unroll
-        for (int j = 0; j < VE; ++j) v[j] += to_f32(rr[j]);
-      }
-      alignas(16) T o[VE];
-#pragma unroll
-      for (int j = 0; j < VE; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
-      *(uint4*)(yg + pa.y + co) = *(const uint4*)o;
+      finish_vec<T, VE>(p, m, co, v);
     }
     return;
   }
@@ -442,11 +447,9 @@ Choice choose(const ConvParams& p, int dtype) {
   const int nk = p.k_pad / bke;
   const long b = blocks(c.bm, c.bn);
   int splits = 1;
-  static const int target = getenv("LOP_SPLIT_TARGET") ? atoi(getenv("LOP_SPLIT_TARGET")) : 2 * kComputeUnits;
-  static const int minsteps = getenv("LOP_SPLIT_MINSTEPS") ? atoi(getenv("LOP_SPLIT_MINSTEPS")) : 4;
   if (b < kComputeUnits) {
-    splits = (int)((target + b - 1) / b);
-    splits = std::min(splits, std::max(nk / minsteps, 1));
+    splits = (int)((2 * kComputeUnits + b - 1) / b);
+    splits = std::min(splits, std::max(nk / 4, 1));
     splits = std::min(splits, 64);
   }
   c.kc_per_split = (nk + splits - 1) / splits;
@@ -455,7 +458,7 @@ Choice choose(const ConvParams& p, int dtype) {
 }
 
 template <typename T, int BM, int BN, int WM, int WN>
-hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s) {
+hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, hipEvent_t mid) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
   if (vec_a)
     hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>), grid, dim3(256), 0, s, p);
@@ -463,13 +466,14 @@ hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s) {
     hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>), grid, dim3(256), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !p.ws) return e;
+  if (mid && (e = hipEventRecord(mid, s)) != hipSuccess) return e;
   const long work = (long)p.M * ((p.C_out + 3) / 4);
   hipLaunchKernelGGL((splitk_finish_kernel<T>), dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s) {
+hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, hipEvent_t mid) {
   constexpr int KE = 16 / (int)sizeof(T);
   const bool vec_a = p.C_in % KE == 0;
   const Choice c = choose(p, dtype);
@@ -478,10 +482,10 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s) {
   if (c.splits > 1 && !ws) return hipErrorInvalidValue;
   p.ws = c.splits > 1 ? ws : nullptr;
   switch (c.shape) {
-    case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s);
-    case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s);
-    case S64x64: return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s);
-    default: return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s);
+    case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s, mid);
+    case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s, mid);
+    case S64x64: return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s, mid);
+    default: return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s, mid);
   }
 }
 
@@ -518,36 +522,24 @@ size_t conv_workspace_bytes(const OpLaunch& L) {
   return c.splits > 1 ? (size_t)c.splits * p.M * p.C_out * sizeof(float) : 0;
 }
 
-hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream) {
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, hipEvent_t mid) {
   ConvParams p = make_params(L);
   if (p.M <= 0) return hipSuccess;
-  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, L.dtype, (float*)L.ws, stream)
-                             : launch_typed<float>(p, L.dtype, (float*)L.ws, stream);
+  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, L.dtype, (float*)L.ws, stream, mid)
+                             : launch_typed<float>(p, L.dtype, (float*)L.ws, stream, mid);
 }
 
-const char* conv_igemm_name(const OpLaunch& L) {
+// Name of the kernel instance as a profiler prints it, and the number of K slices.
+int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const ConvParams p = make_params(L);
   const bool bf = L.dtype == LOP_BF16;
   const bool vec = p.C_in % (bf ? 8 : 4) == 0;
   const Choice c = choose(p, L.dtype);
-  static const char* names[2][2][2][4] = {
-      {{{"conv_igemm<f32,128x128,gather>", "conv_igemm<f32,128x64,gather>",
-         "conv_igemm<f32,64x64,gather>", "conv_igemm<f32,128x32,gather>"},
-        {"conv_igemm<f32,128x128,gather,splitk>", "conv_igemm<f32,128x64,gather,splitk>",
-         "conv_igemm<f32,64x64,gather,splitk>", "conv_igemm<f32,128x32,gather,splitk>"}},
-       {{"conv_igemm<f32,128x128>", "conv_igemm<f32,128x64>", "conv_igemm<f32,64x64>",
-         "conv_igemm<f32,128x32>"},
-        {"conv_igemm<f32,128x128,splitk>", "conv_igemm<f32,128x64,splitk>",
-         "conv_igemm<f32,64x64,splitk>", "conv_igemm<f32,128x32,splitk>"}}},
-      {{{"conv_igemm<bf16,128x128,gather>", "conv_igemm<bf16,128x64,gather>",
-         "conv_igemm<bf16,64x64,gather>", "conv_igemm<bf16,128x32,gather>"},
-        {"conv_igemm<bf16,128x128,gather,splitk>", "conv_igemm<bf16,128x64,gather,splitk>",
-         "conv_igemm<bf16,64x64,gather,splitk>", "conv_igemm<bf16,128x32,gather,splitk>"}},
-       {{"conv_igemm<bf16,128x128>", "conv_igemm<bf16,128x64>", "conv_igemm<bf16,64x64>",
-         "conv_igemm<bf16,128x32>"},
-        {"conv_igemm<bf16,128x128,splitk>", "conv_igemm<bf16,128x64,splitk>",
-         "conv_igemm<bf16,64x64,splitk>", "conv_igemm<bf16,128x32,splitk>"}}}};
-  return names[bf][vec][c.splits > 1][c.shape];
+  static const int wm[] = {2, 2, 2, 4}, wn[] = {2, 2, 2, 1};
+  if (name && size)
+    snprintf(name, size, "conv_igemm_kernel<%s, %d, %d, %d, %d, %d, %d, %s>", bf ? "__bf16" : "float",
+             c.bm, c.bn, wm[c.shape], wn[c.shape], kBKB, kStages, vec ? "true" : "false");
+  return c.splits;
 }
 
 }  // namespace lop

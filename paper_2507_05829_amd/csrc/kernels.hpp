@@ -38,9 +38,12 @@ inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvC
 // Bytes of split-K scratch the dense conv launch needs (0: none).
 size_t conv_workspace_bytes(const OpLaunch& L);
 
-// Enqueue the kernel for one operator on `stream`. Returns hipError_t.
-hipError_t launch_op(const OpLaunch& L, hipStream_t stream);
-// Short name of the kernel variant launch_op would pick (static storage).
-const char* kernel_name(const OpLaunch& L);
+// Enqueue the kernel(s) for one operator on `stream`. A dense conv whose reduction axis is
+// cut into slices is two kernels; `mid` (optional) is recorded between them.
+hipError_t launch_op(const OpLaunch& L, hipStream_t stream, hipEvent_t mid = nullptr);
+// Name of the kernel instance launch_op would pick, as a profiler prints it (without the
+// namespace and argument list), written to name[size]. Returns the number of K slices
+// (1: a single kernel; > 1: followed by splitk_finish_kernel).
+int describe_op(const OpLaunch& L, char* name, size_t size);
 
 }  // namespace lop

@@ -14,22 +14,22 @@
 #include "plan_tables.hpp"
 
 namespace lop {
-hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream);
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, hipEvent_t mid);
 hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream);
 hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
                             hipStream_t stream);
 
-const char* conv_igemm_name(const OpLaunch& L);
-const char* rowwise_name(const OpLaunch& L);
+int conv_igemm_describe(const OpLaunch& L, char* name, size_t size);
+int rowwise_describe(const OpLaunch& L, char* name, size_t size);
 
-hipError_t launch_op(const OpLaunch& L, hipStream_t stream) {
+hipError_t launch_op(const OpLaunch& L, hipStream_t stream, hipEvent_t mid) {
   if (L.out_hi <= L.out_lo) return hipSuccess;
-  if (L.op == LOP_CONV2D) return launch_conv_igemm(L, stream);
+  if (L.op == LOP_CONV2D) return launch_conv_igemm(L, stream, mid);
   return launch_rowwise_op(L, stream);
 }
 
-const char* kernel_name(const OpLaunch& L) {
-  return L.op == LOP_CONV2D ? conv_igemm_name(L) : rowwise_name(L);
+int describe_op(const OpLaunch& L, char* name, size_t size) {
+  return L.op == LOP_CONV2D ? conv_igemm_describe(L, name, size) : rowwise_describe(L, name, size);
 }
 }  // namespace lop
 
@@ -702,48 +702,62 @@ int lop_time_layer(lop_plan_t* P, int band, int layer, const void* d_in, void* d
   return LOP_OK;
 }
 
-int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, size_t size) {
+int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, size_t size,
+                          int* k_slices) {
   if (!P || !name || size == 0) return LOP_ERR_INVALID_ARG;
   if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
     return LOP_ERR_BAND_RANGE;
   const lop_rows_t r = P->t.bands[band].compute[layer];
-  const char* n = "";
-  if (r.hi > r.lo) n = lop::kernel_name(make_launch(P, band, layer, nullptr, nullptr));
-  std::strncpy(name, n, size - 1);
-  name[size - 1] = 0;
+  name[0] = 0;
+  int slices = 0;
+  if (r.hi > r.lo) slices = lop::describe_op(make_launch(P, band, layer, nullptr, nullptr), name, size);
+  if (k_slices) *k_slices = slices;
   return LOP_OK;
 }
 
-int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, float* layer_ms) {
+int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, float* layer_ms,
+                      float* finish_ms) {
   if (!P || !d_in || !d_out || !layer_ms || iters < 1) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   const int nb = P->t.n_bands, nl = P->t.n_layers();
+  int rc = lop_synchronize(P);
+  if (rc != LOP_OK) return rc;
   hipStream_t cs = P->s_main;
-  std::vector<hipEvent_t> ev((size_t)nb * nl * 2, nullptr);
-  int rc = LOP_OK;
+  std::vector<hipEvent_t> ev((size_t)nb * nl * 3, nullptr);
+  std::vector<int> slices((size_t)nb * nl, 0);
   auto run = [&]() -> int {
     for (auto& e : ev) LOP_HIP(hipEventCreate(&e));
-    for (int i = 0; i < nb * nl; ++i) layer_ms[i] = 0.f;
+    for (int i = 0; i < nb * nl; ++i) {
+      layer_ms[i] = 0.f;
+      if (finish_ms) finish_ms[i] = 0.f;
+    }
     for (int it = 0; it < iters; ++it) {
       for (int b = 0; b < nb; ++b)
         for (int l = 0; l < nl; ++l) {
           const lop_rows_t r = P->t.bands[b].compute[l];
           if (r.hi <= r.lo) continue;
           const lop::OpLaunch o = make_launch(P, b, l, d_in, d_out);
-          const size_t i = ((size_t)b * nl + l) * 2;
+          const size_t i = ((size_t)b * nl + l) * 3;
+          slices[b * nl + l] = lop::describe_op(o, nullptr, 0);
           LOP_HIP(hipEventRecord(ev[i], cs));
-          LOP_HIP(lop::launch_op(o, cs));
-          LOP_HIP(hipEventRecord(ev[i + 1], cs));
+          LOP_HIP(lop::launch_op(o, cs, ev[i + 1]));
+          LOP_HIP(hipEventRecord(ev[i + 2], cs));
         }
       LOP_HIP(hipStreamSynchronize(cs));
       for (int b = 0; b < nb; ++b)
         for (int l = 0; l < nl; ++l) {
           const lop_rows_t r = P->t.bands[b].compute[l];
           if (r.hi <= r.lo) continue;
-          const size_t i = ((size_t)b * nl + l) * 2;
-          float ms = 0.f;
-          LOP_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+          const size_t i = ((size_t)b * nl + l) * 3;
+          float ms = 0.f, fin = 0.f;
+          if (slices[b * nl + l] > 1) {
+            LOP_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+            LOP_HIP(hipEventElapsedTime(&fin, ev[i + 1], ev[i + 2]));
+          } else {
+            LOP_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 2]));
+          }
           layer_ms[b * nl + l] += ms / iters;
+          if (finish_ms) finish_ms[b * nl + l] += fin / iters;
         }
     }
     return LOP_OK;

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
 
 #include "kernels.hpp"
 #include "lop.h"
@@ -205,16 +206,13 @@ hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len
   return hipGetLastError();
 }
 
-const char* rowwise_name(const OpLaunch& L) {
+int rowwise_describe(const OpLaunch& L, char* name, size_t size) {
   const bool bf = L.dtype == LOP_BF16;
-  const bool vec = L.x.c % (bf ? 8 : 4) == 0;
+  const int vec = bf ? (L.x.c % 8 == 0 ? 8 : 1) : (L.x.c % 4 == 0 ? 4 : 1);
   const int o = L.op == LOP_DWCONV2D ? 0 : (L.op == LOP_MAXPOOL2D ? 1 : 2);
-  static const char* names[2][2][3] = {
-      {{"rowwise<f32,scalar,dwconv>", "rowwise<f32,scalar,maxpool>", "rowwise<f32,scalar,eltwise>"},
-       {"rowwise<f32,dwconv>", "rowwise<f32,maxpool>", "rowwise<f32,eltwise>"}},
-      {{"rowwise<bf16,scalar,dwconv>", "rowwise<bf16,scalar,maxpool>", "rowwise<bf16,scalar,eltwise>"},
-       {"rowwise<bf16,dwconv>", "rowwise<bf16,maxpool>", "rowwise<bf16,eltwise>"}}};
-  return names[bf][vec][o];
+  if (name && size)
+    snprintf(name, size, "rowwise_kernel<%s, %d, %d>", bf ? "__bf16" : "float", vec, o);
+  return 1;
 }
 
 }  // namespace lop

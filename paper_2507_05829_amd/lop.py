@@ -96,8 +96,8 @@ def _load() -> ctypes.CDLL:
         "lop_synchronize": (c_int, [P]),
         "lop_time_layer": (c_int, [P, c_int, c_int, c_void_p, c_void_p, c_int, POINTER(c_float)]),
         "lop_plan_destroy": (None, [P]),
-        "lop_plan_layer_kernel": (c_int, [P, c_int, c_int, ctypes.c_char_p, c_size_t]),
-        "lop_profile_chain": (c_int, [P, c_void_p, c_void_p, c_int, POINTER(c_float)]),
+        "lop_plan_layer_kernel": (c_int, [P, c_int, c_int, ctypes.c_char_p, c_size_t, POINTER(c_int)]),
+        "lop_profile_chain": (c_int, [P, c_void_p, c_void_p, c_int, POINTER(c_float), POINTER(c_float)]),
         "lop_copy_chain": (c_int, [P, c_void_p, c_void_p]),
         "lop_strerror": (c_char_p, [c_int]),
         "lop_last_hip_error": (c_int, []),
@@ -237,18 +237,23 @@ def lop_time_layer(plan, band: int, layer: int, d_in, d_out, iters: int = 20) ->
     return ms.value
 
 
-def lop_plan_layer_kernel(plan, band: int, layer: int) -> str:
-    buf = ctypes.create_string_buffer(96)
-    _check(_lib.lop_plan_layer_kernel(plan, band, layer, buf, 96), "lop_plan_layer_kernel")
-    return buf.value.decode()
+def lop_plan_layer_kernel(plan, band: int, layer: int) -> Tuple[str, int]:
+    """(kernel instance name, number of K slices) of a (band, layer) launch."""
+    buf = ctypes.create_string_buffer(128)
+    k = c_int(0)
+    _check(_lib.lop_plan_layer_kernel(plan, band, layer, buf, 128, byref(k)), "lop_plan_layer_kernel")
+    return buf.value.decode(), k.value
 
 
-def lop_profile_chain(plan, d_in, d_out, iters: int = 5) -> np.ndarray:
+def lop_profile_chain(plan, d_in, d_out, iters: int = 5) -> Tuple[np.ndarray, np.ndarray]:
+    """Mean ms of every (band, layer) main kernel and of its split-K finish kernel."""
     nb, nl = lop_plan_n_bands(plan), lop_plan_n_layers(plan)
     ms = np.zeros((nb, nl), np.float32)
+    fin = np.zeros((nb, nl), np.float32)
     _check(_lib.lop_profile_chain(plan, _ptr(d_in), _ptr(d_out), iters,
-                                  ms.ctypes.data_as(POINTER(c_float))), "lop_profile_chain")
-    return ms
+                                  ms.ctypes.data_as(POINTER(c_float)),
+                                  fin.ctypes.data_as(POINTER(c_float))), "lop_profile_chain")
+    return ms, fin
 
 
 def lop_copy_chain(plan, d_out, h_out) -> None:
