@@ -24,15 +24,16 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18")
-    ap.add_argument("--also", default="tiny,vgg16,detector720p,mbv2",
-                    help="comma list of further workloads reported under 'also' (fewer steps)")
+    ap.add_argument("--also", default="resnet18:independent,tiny,vgg16,detector720p,mbv2",
+                    help="comma list of further workload[:mode] entries reported under 'also' "
+                         "(fewer steps; mode defaults to --mode)")
     ap.add_argument("--bands", type=int, default=None, help="override the workload's band count")
     ap.add_argument("--lanes", type=int, default=0, help="concurrent band streams (0 = library default)")
     ap.add_argument("--graph", type=int, default=1, help="1: replay the chain as a HIP graph")
     ap.add_argument("--dma-copy", type=int, default=0, help="1: band copies via hipMemcpyAsync")
     ap.add_argument("--replicas", type=int, default=1,
                     help="plans (each with its own lanes and scratch) the steady-state steps rotate over")
-    ap.add_argument("--mode", default="independent", choices=["independent", "reuse"],
+    ap.add_argument("--mode", default="reuse", choices=["independent", "reuse"],
                     help="independent: every band recomputes its halos; reuse: bands run in "
                          "order and reuse rows earlier bands produced")
     ap.add_argument("--pmc-calibrate", action="store_true",
@@ -139,6 +140,22 @@ def roofline_of(k, dtype):
                 avg_us=k["avg_us"], launches_per_step=k["launches"])
 
 
+def measured_traffic(workload, kernel_name):
+    """HBM bytes per launch of a kernel from the committed counter summary, or None when
+    there is none for this workload or the kernel sources changed since it was taken."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    if not os.path.exists(path):
+        return None
+    from paper_2507_05829_amd import pmc_traffic
+    doc = json.load(open(path))
+    if doc.get("source_hash") != pmc_traffic.source_hash():
+        return None
+    k = doc["kernels"].get(kernel_name)
+    if not k or k["fetch_bytes_per_launch"] is None or k["write_bytes_per_launch"] is None:
+        return None
+    return round(k["fetch_bytes_per_launch"] + k["write_bytes_per_launch"])
+
+
 def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0, graph=1, dma=0, replicas=1, mode="independent"):
     chain = workloads.CONFIGS[name]()
     if bands:
@@ -185,6 +202,9 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
         kernels=[{k: v for k, v in kk.items() if not k.endswith("_per_launch")} for kk in kernels],
     )
     roof = roofline_of(next(k for k in kernels if k["flop_per_launch"] > 0), chain.dtype)
+    roof["traffic"] = measured_traffic(f"{name}_{mode}", roof["kernel"])
+    roof["algorithmic_bytes_per_launch"] = round(
+        next(k for k in kernels if k["name"] == roof["kernel"])["bytes_per_launch"])
     for p in plans:
         p.destroy()
     return chain, tensors, res, roof
@@ -234,10 +254,15 @@ def main():
     chain, tensors, res, roof = run_workload(torch, lop, workloads, a.workload, a.steps, a.warmup,
                                              a.bands, a.profile_iters, a.lanes, a.graph, a.dma_copy, a.replicas, a.mode)
     also = []
-    for name in [s for s in a.also.split(",") if s and s != a.workload]:
+    for entry in [e for e in a.also.split(",") if e]:
+        name, _, mode = entry.partition(":")
+        mode = mode or a.mode
+        if name == a.workload and mode == a.mode:
+            continue
         heavy = name == "mbv2"
         _, _, r, rf = run_workload(torch, lop, workloads, name, 10 if heavy else max(a.steps // 4, 10),
-                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters, a.lanes, a.graph, a.dma_copy, a.replicas, a.mode)
+                                   2 if heavy else 5, None, 3 if heavy else a.profile_iters,
+                                   a.lanes, a.graph, a.dma_copy, a.replicas, mode)
         r["roofline"] = rf
         also.append(r)
 
@@ -250,7 +275,11 @@ def main():
         "dtype": "f32" if chain.dtype == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload} {'x'.join(map(str, chain.in_shape))} "
                                f"{chain.dtype}, {res['n_bands']} row bands, {res['n_layers']} layers",
-                   "images_per_step": chain.in_shape[0], "independent_bands": a.mode == "independent",
+                   "images_per_step": chain.in_shape[0],
+                   "mode": ("reuse: bands in order, rows produced by earlier bands are reused"
+                            if a.mode == "reuse" else
+                            "independent: every band recomputes its halos"),
+                   "executed_over_useful_flop": res["executed_over_useful"],
                    "hip_graph": bool(a.graph), "lanes": a.lanes or "default",
                    "replicas": a.replicas},
         "roofline": roof,
