@@ -19,6 +19,7 @@
 #include <algorithm>
 #include <cstdio>
 
+#include "act.hpp"
 #include "kernels.hpp"
 #include "lop.h"
 
@@ -47,9 +48,7 @@ struct ConvParams {
 };
 
 __device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == LOP_ACT_RELU) return fmaxf(v, 0.f);
-  if (act == LOP_ACT_RELU6) return fminf(fmaxf(v, 0.f), 6.f);
-  return v;
+  return clamp_act(v, make_clamp(act));
 }
 
 __device__ __forceinline__ float to_f32(float v) { return v; }

@@ -19,17 +19,22 @@ hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream);
 hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
                             hipStream_t stream);
 
+hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream);
+bool pointwise_applies(const OpLaunch& L);
+int pointwise_describe(const OpLaunch& L, char* name, size_t size);
 int conv_igemm_describe(const OpLaunch& L, char* name, size_t size);
 int rowwise_describe(const OpLaunch& L, char* name, size_t size);
 
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream, hipEvent_t mid) {
   if (L.out_hi <= L.out_lo) return hipSuccess;
-  if (L.op == LOP_CONV2D) return launch_conv_igemm(L, stream, mid);
+  if (L.op == LOP_CONV2D)
+    return pointwise_applies(L) ? launch_pointwise(L, stream) : launch_conv_igemm(L, stream, mid);
   return launch_rowwise_op(L, stream);
 }
 
 int describe_op(const OpLaunch& L, char* name, size_t size) {
-  return L.op == LOP_CONV2D ? conv_igemm_describe(L, name, size) : rowwise_describe(L, name, size);
+  if (L.op != LOP_CONV2D) return rowwise_describe(L, name, size);
+  return pointwise_applies(L) ? pointwise_describe(L, name, size) : conv_igemm_describe(L, name, size);
 }
 }  // namespace lop
 
@@ -325,7 +330,8 @@ int setup_device(lop_plan_t* P) {
       if (P->t.layers[l].d.op != LOP_CONV2D) continue;
       const lop_rows_t rr = P->t.bands[b].compute[l];
       if (rr.hi <= rr.lo) continue;
-      const size_t need = lop::conv_workspace_bytes(make_launch(P, b, l, nullptr, nullptr));
+      const lop::OpLaunch o = make_launch(P, b, l, nullptr, nullptr);
+      const size_t need = lop::pointwise_applies(o) ? 0 : lop::conv_workspace_bytes(o);
       P->conv_ws_bytes = std::max(need, P->conv_ws_bytes);
     }
   for (Lane& L : P->lanes) {

@@ -7,7 +7,9 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 
+#include "act.hpp"
 #include "kernels.hpp"
 #include "lop.h"
 
@@ -27,12 +29,6 @@ struct RowParams {
   int act, out_lo, R, N;
   long total;  // N * R * W_out * (C / VEC)
 };
-
-__device__ __forceinline__ float act_f(float v, int act) {
-  if (act == LOP_ACT_RELU) return fmaxf(v, 0.f);
-  if (act == LOP_ACT_RELU6) return fminf(fmaxf(v, 0.f), 6.f);
-  return v;
-}
 
 template <typename T, int VEC> struct Vec;  // VEC elements of T <-> fp32 registers
 
@@ -63,6 +59,19 @@ template <> struct Vec<__bf16, 8> {
 #pragma unroll
     for (int i = 0; i < 8; ++i) o[i] = (__bf16)v[i];
     *(uint4*)p = *(const uint4*)o;
+  }
+};
+template <> struct Vec<__bf16, 4> {
+  static __device__ __forceinline__ void load(const __bf16* p, float* v) {
+    const uint2 t = *(const uint2*)p;
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void store(__bf16* p, const float* v) {
+    alignas(8) __bf16 o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (__bf16)v[i];
+    *(uint2*)p = *(const uint2*)o;
   }
 };
 template <> struct Vec<__bf16, 1> {
@@ -139,9 +148,202 @@ __global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
       for (int i = 0; i < VEC; ++i) acc[i] += rv[i];
     }
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[i] = act_f(acc[i], p.act);
+    for (int i = 0; i < VEC; ++i) acc[i] = clamp_act(acc[i], make_clamp(p.act));
   }
   Vec<T, VEC>::store((T*)p.y + ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C + c, acc);
+}
+
+
+// Depthwise 3x3 (dilation 1, pad 1, stride S in both directions) with a sliding window:
+// a thread owns VEC channels of one output column and walks down `rows_per_thread` output
+// rows, keeping the 3 x 3 input window and the 9 x VEC weights in registers, so every
+// output costs S new input rows (3 vector loads each) instead of 9 loads plus 9 weight
+// loads. Threads of a workgroup are (channel vector, column) with the channel vector
+// fastest: loads and stores of a wavefront stay contiguous and the left/right neighbours'
+// columns come out of the same CU's L1.
+struct Dw3Params {
+  RowParams r;
+  int rows_per_thread;  // output rows one thread walks
+  int cols_per_block;   // output columns per workgroup
+  int chunks;           // row chunks per image
+};
+
+// Raw 8- or 16-byte vector of the storage type and its expansion to fp32 values.
+template <int BYTES> struct RawVec;
+template <> struct RawVec<16> { typedef uint4 type; };
+template <> struct RawVec<8> { typedef uint2 type; };
+
+__device__ __forceinline__ void unpack_bf16(const uint4& t, float* v) {
+  const unsigned u[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(u[i] << 16);
+    v[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void unpack_bf16(const uint2& t, float* v) {
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+__device__ __forceinline__ void unpack_f32(const uint4& t, float* v) {
+  v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y);
+  v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
+}
+template <typename T, typename R>
+__device__ __forceinline__ void unpack(const R& t, float* v) {
+  if constexpr (sizeof(T) == 2) unpack_bf16(t, v);
+  else unpack_f32(t, v);
+}
+
+template <typename T, int VEC, int S>
+__global__ __launch_bounds__(256) void dwconv3x3_kernel(const Dw3Params q) {
+  static_assert(VEC * sizeof(T) == 16 || VEC * sizeof(T) == 8, "8- or 16-byte vectors");
+  typedef typename RawVec<VEC * sizeof(T)>::type Raw;
+  const RowParams& p = q.r;
+  const int cv = p.C / VEC;
+  const int cg = threadIdx.x % cv, col = threadIdx.x / cv;
+  const int ow = blockIdx.x * q.cols_per_block + col;
+  if (col >= q.cols_per_block || ow >= p.W_out) return;
+  const int chunk = blockIdx.y % q.chunks, n = blockIdx.y / q.chunks;
+  const int c = cg * VEC;
+  const int oh0 = p.out_lo + chunk * q.rows_per_thread;
+  const int oh1 = min(oh0 + q.rows_per_thread, p.out_lo + p.R);
+  const T* __restrict__ xg = (const T*)p.x;
+  T* __restrict__ yg = (T*)p.y;
+
+  float w[9][VEC];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) load_f32<VEC>(p.w + (size_t)t * p.C + c, w[t]);
+  float bias[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) bias[i] = 0.f;
+  if (p.bias) load_f32<VEC>(p.bias + c, bias);
+
+  const int iw0 = ow * S - 1;
+  const Clamp clamp = make_clamp(p.act);
+  // one input row (3 columns), raw; rows or columns outside the image are zero
+  auto load_row = [&](int ih, Raw (&raw)[3]) {
+    const bool row_ok = ih >= p.x_row0 && ih < p.x_row0 + p.x_rows;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+      const int iw = iw0 + b;
+      raw[b] = Raw{};
+      if (row_ok && iw >= 0 && iw < p.W)
+        raw[b] = *(const Raw*)(xg + ((size_t)(n * p.x_rows + ih - p.x_row0) * p.W + iw) * p.C + c);
+    }
+  };
+  // acc += row . w[a][0..2]
+  auto mac = [&](float* acc, const float (&row)[3][VEC], int a) {
+#pragma unroll
+    for (int b = 0; b < 3; ++b)
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(row[b][i], w[a * 3 + b][i], acc[i]);
+  };
+  auto emit = [&](float* acc, int oh) {
+    float v[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = acc[i] + bias[i];
+    if (p.res) {
+      float rv[VEC];
+      Vec<T, VEC>::load((const T*)p.res +
+                            ((size_t)(n * p.r_rows + oh - p.r_row0) * p.W_out + ow) * p.C + c, rv);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) v[i] += rv[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) v[i] = clamp_act(v[i], clamp);
+    Vec<T, VEC>::store(yg + ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C + c, v);
+  };
+
+  float row[3][VEC];
+  if (S == 1) {
+    // Input row ih feeds outputs ih+1 (tap row 0), ih (tap row 1), ih-1 (tap row 2): three
+    // running sums; the loads of the next two rows are in flight while one is multiplied.
+    float s0[VEC], s1[VEC], s2[VEC];  // outputs ih-1, ih, ih+1
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) s0[i] = s1[i] = s2[i] = 0.f;
+    Raw ra[3], rb[3];
+    load_row(oh0 - 1, ra);
+    load_row(oh0, rb);
+    auto step = [&](int ih, Raw (&raw)[3]) {
+#pragma unroll
+      for (int b = 0; b < 3; ++b) unpack<T>(raw[b], row[b]);
+      load_row(ih + 2, raw);             // refill: rows past oh1 are never multiplied
+      if (ih - 1 >= oh0) mac(s0, row, 2);
+      if (ih >= oh0 && ih < oh1) mac(s1, row, 1);
+      if (ih + 1 < oh1) mac(s2, row, 0);
+      if (ih - 1 >= oh0) emit(s0, ih - 1);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) { s0[i] = s1[i]; s1[i] = s2[i]; s2[i] = 0.f; }
+    };
+    for (int ih = oh0 - 1; ih <= oh1; ih += 2) {
+      step(ih, ra);
+      if (ih + 1 <= oh1) step(ih + 1, rb);
+    }
+  } else {
+    // Output oh reads rows 2oh-1, 2oh, 2oh+1; row 2oh+1 is also the first row of oh+1, whose
+    // sum is started right away so that no row is kept or read twice.
+    float cur[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) cur[i] = 0.f;
+    Raw r0[3], r1[3], r2[3];
+    load_row(2 * oh0 - 1, r0);
+    load_row(2 * oh0, r1);
+    load_row(2 * oh0 + 1, r2);
+#pragma unroll
+    for (int b = 0; b < 3; ++b) unpack<T>(r0[b], row[b]);
+    mac(cur, row, 0);
+    for (int oh = oh0; oh < oh1; ++oh) {
+#pragma unroll
+      for (int b = 0; b < 3; ++b) unpack<T>(r1[b], row[b]);
+      if (oh + 1 < oh1) load_row(2 * oh + 2, r1);
+      mac(cur, row, 1);
+#pragma unroll
+      for (int b = 0; b < 3; ++b) unpack<T>(r2[b], row[b]);
+      if (oh + 1 < oh1) load_row(2 * oh + 3, r2);
+      mac(cur, row, 2);
+      emit(cur, oh);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) cur[i] = 0.f;
+      mac(cur, row, 0);
+    }
+  }
+}
+
+// The sliding-window kernel covers the common depthwise case; everything else runs on
+// rowwise_kernel.
+inline bool dw3_applies(const RowParams& p, int op, int vec) {
+  return op == LOP_DWCONV2D && p.kh == 3 && p.kw == 3 && p.dh == 1 && p.dw == 1 && p.ph == 1 &&
+         p.pw == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && vec > 1 && p.C / vec <= 256;
+}
+
+template <typename T, int VEC>
+hipError_t launch_dw3(const RowParams& p, hipStream_t s) {
+  if (p.R <= 0) return hipSuccess;
+  Dw3Params q;
+  q.r = p;
+  const int cv = p.C / VEC;
+  q.cols_per_block = std::max(1, 256 / cv);
+  // enough wavefronts to keep ~16 per SIMD queued: shorter row walks for small launches
+  const long waves_per_chunk = std::max<long>(1, (long)cv * p.W_out * p.N / 64);
+  const long chunks_wanted = (16384 + waves_per_chunk - 1) / waves_per_chunk;
+  const int rpt = (int)((p.R + chunks_wanted - 1) / chunks_wanted);
+  q.rows_per_thread = std::min(std::max(rpt, 4), 32);
+  q.chunks = (p.R + q.rows_per_thread - 1) / q.rows_per_thread;
+  dim3 grid((p.W_out + q.cols_per_block - 1) / q.cols_per_block, q.chunks * p.N);
+  if (p.sh == 1)
+    hipLaunchKernelGGL((dwconv3x3_kernel<T, VEC, 1>), grid, dim3(256), 0, s, q);
+  else
+    hipLaunchKernelGGL((dwconv3x3_kernel<T, VEC, 2>), grid, dim3(256), 0, s, q);
+  return hipGetLastError();
+}
+
+// Channel vector per thread of the sliding-window kernel (0: it does not apply).
+inline int dw3_vec(const RowParams& p, int op, int dtype) {
+  static const int force = getenv("LOP_DW_VEC") ? atoi(getenv("LOP_DW_VEC")) : 0;
+  const int want = dtype == LOP_BF16 ? (force ? force : 4) : 4;
+  if (p.C % want != 0) return 0;
+  return dw3_applies(p, op, want) ? want : 0;
 }
 
 template <typename T, int VEC>
@@ -169,6 +371,10 @@ hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream) {
   p.kh = L.kh; p.kw = L.kw; p.sh = L.sh; p.sw = L.sw; p.ph = L.ph; p.pw = L.pw;
   p.dh = L.dh; p.dw = L.dw;
   p.act = L.act; p.out_lo = L.out_lo; p.R = L.out_hi - L.out_lo; p.N = L.x.n;
+  if (const int v = dw3_vec(p, L.op, L.dtype)) {
+    if (L.dtype != LOP_BF16) return launch_dw3<float, 4>(p, stream);
+    return v == 8 ? launch_dw3<__bf16, 8>(p, stream) : launch_dw3<__bf16, 4>(p, stream);
+  }
   if (L.dtype == LOP_BF16)
     return p.C % 8 == 0 ? launch_rowwise<__bf16, 8>(p, L.op, stream)
                         : launch_rowwise<__bf16, 1>(p, L.op, stream);
@@ -210,8 +416,15 @@ int rowwise_describe(const OpLaunch& L, char* name, size_t size) {
   const bool bf = L.dtype == LOP_BF16;
   const int vec = bf ? (L.x.c % 8 == 0 ? 8 : 1) : (L.x.c % 4 == 0 ? 4 : 1);
   const int o = L.op == LOP_DWCONV2D ? 0 : (L.op == LOP_MAXPOOL2D ? 1 : 2);
-  if (name && size)
-    snprintf(name, size, "rowwise_kernel<%s, %d, %d>", bf ? "__bf16" : "float", vec, o);
+  RowParams p;
+  p.kh = L.kh; p.kw = L.kw; p.sh = L.sh; p.sw = L.sw; p.ph = L.ph; p.pw = L.pw;
+  p.dh = L.dh; p.dw = L.dw; p.C = L.x.c;
+  if (name && size) {
+    if (const int v = dw3_vec(p, L.op, L.dtype))
+      snprintf(name, size, "dwconv3x3_kernel<%s, %d, %d>", bf ? "__bf16" : "float", v, L.sh);
+    else
+      snprintf(name, size, "rowwise_kernel<%s, %d, %d>", bf ? "__bf16" : "float", vec, o);
+  }
   return 1;
 }
 
