@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void pointwise_kernel(const PwParams p) {
     for (int s = 0; s < KS; ++s)
       wf[t][s] = *(const uint4*)(p.w + (size_t)(t * 32 + px) * p.k_pad + s * 16 + kg * 8);
 
-  constexpr int GPW = KS >= 8 ? 1 : (KS >= 4 ? 2 : 4);  // pixel groups per wavefront
+  constexpr int GPW = KS >= 8 ? 1 : 2;  // pixel groups per wavefront
   const int wid = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(wave);
 
   // A band of a 1x1 stride-1 layer is one contiguous run of pixels per image in the input,
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void pointwise_kernel(const PwParams p) {
 
 template <int NT, int KS>
 hipError_t launch_pw(PwParams& p, hipStream_t s) {
-  constexpr int GPW = KS >= 8 ? 1 : (KS >= 4 ? 2 : 4);  // must match the kernel
+  constexpr int GPW = KS >= 8 ? 1 : 2;  // must match the kernel
   const int waves = (p.groups + GPW - 1) / GPW;
   const int grid = std::max(1, (waves + 3) / 4);
   p.iters = GPW;

@@ -154,18 +154,18 @@ __global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
 }
 
 
-// Depthwise 3x3 (dilation 1, pad 1, stride S in both directions) with a sliding window:
-// a thread owns VEC channels of one output column and walks down `rows_per_thread` output
-// rows, keeping the 3 x 3 input window and the 9 x VEC weights in registers, so every
-// output costs S new input rows (3 vector loads each) instead of 9 loads plus 9 weight
-// loads. Threads of a workgroup are (channel vector, column) with the channel vector
-// fastest: loads and stores of a wavefront stay contiguous and the left/right neighbours'
-// columns come out of the same CU's L1.
+// Depthwise 3x3 (dilation 1, pad 1, stride S in both directions), register blocked: a
+// thread owns VEC channels of one output column and kDwRowsPerThread consecutive output
+// rows; it loads the (rows-1)*S + 3 input rows it needs (3 vectors each) and the 9 x VEC
+// weights once, so an output costs about S + 0.5 vector loads instead of 9 loads plus 9
+// weight loads. Threads of a workgroup are (channel vector, column) with the channel
+// vector fastest: loads and stores of a wavefront stay contiguous and the left/right
+// neighbours' columns come out of the same CU's L1. No residual (rowwise_kernel has it).
+constexpr int kDwRowsPerThread = 4;
 struct Dw3Params {
   RowParams r;
-  int rows_per_thread;  // output rows one thread walks
-  int cols_per_block;   // output columns per workgroup
-  int chunks;           // row chunks per image
+  int cols_per_block;  // output columns per workgroup
+  int chunks;          // row chunks (kDwRowsPerThread output rows each) per image
 };
 
 // Raw 8- or 16-byte vector of the storage type and its expansion to fp32 values.
@@ -199,6 +199,8 @@ template <typename T, int VEC, int S>
 __global__ __launch_bounds__(256) void dwconv3x3_kernel(const Dw3Params q) {
   static_assert(VEC * sizeof(T) == 16 || VEC * sizeof(T) == 8, "8- or 16-byte vectors");
   typedef typename RawVec<VEC * sizeof(T)>::type Raw;
+  constexpr int RPT = kDwRowsPerThread;    // output rows per thread
+  constexpr int NR = (RPT - 1) * S + 3;    // input rows they read
   const RowParams& p = q.r;
   const int cv = p.C / VEC;
   const int cg = threadIdx.x % cv, col = threadIdx.x / cv;
@@ -206,11 +208,29 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(const Dw3Params q) {
   if (col >= q.cols_per_block || ow >= p.W_out) return;
   const int chunk = blockIdx.y % q.chunks, n = blockIdx.y / q.chunks;
   const int c = cg * VEC;
-  const int oh0 = p.out_lo + chunk * q.rows_per_thread;
-  const int oh1 = min(oh0 + q.rows_per_thread, p.out_lo + p.R);
+  const int oh0 = p.out_lo + chunk * RPT;
+  const int oh1 = min(oh0 + RPT, p.out_lo + p.R);
   const T* __restrict__ xg = (const T*)p.x;
   T* __restrict__ yg = (T*)p.y;
+  const Clamp clamp = make_clamp(p.act);
 
+  // Every load first (input rows, weights, bias), all stores after: loads and stores share
+  // one in-order counter, so a load waited for after a store would wait for the store too.
+  Raw in[NR][3];
+  const int ih0 = oh0 * S - 1, iw0 = ow * S - 1;
+  const int rows_needed = (oh1 - oh0 - 1) * S + 3;
+#pragma unroll
+  for (int a = 0; a < NR; ++a) {
+    const int ih = ih0 + a;
+    const bool row_ok = a < rows_needed && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows;
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+      const int iw = iw0 + b;
+      in[a][b] = Raw{};
+      if (row_ok && iw >= 0 && iw < p.W)
+        in[a][b] = *(const Raw*)(xg + ((size_t)(n * p.x_rows + ih - p.x_row0) * p.W + iw) * p.C + c);
+    }
+  }
   float w[9][VEC];
 #pragma unroll
   for (int t = 0; t < 9; ++t) load_f32<VEC>(p.w + (size_t)t * p.C + c, w[t]);
@@ -219,94 +239,24 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(const Dw3Params q) {
   for (int i = 0; i < VEC; ++i) bias[i] = 0.f;
   if (p.bias) load_f32<VEC>(p.bias + c, bias);
 
-  const int iw0 = ow * S - 1;
-  const Clamp clamp = make_clamp(p.act);
-  // one input row (3 columns), raw; rows or columns outside the image are zero
-  auto load_row = [&](int ih, Raw (&raw)[3]) {
-    const bool row_ok = ih >= p.x_row0 && ih < p.x_row0 + p.x_rows;
 #pragma unroll
-    for (int b = 0; b < 3; ++b) {
-      const int iw = iw0 + b;
-      raw[b] = Raw{};
-      if (row_ok && iw >= 0 && iw < p.W)
-        raw[b] = *(const Raw*)(xg + ((size_t)(n * p.x_rows + ih - p.x_row0) * p.W + iw) * p.C + c);
-    }
-  };
-  // acc += row . w[a][0..2]
-  auto mac = [&](float* acc, const float (&row)[3][VEC], int a) {
+  for (int r = 0; r < RPT; ++r) {
+    if (oh0 + r >= oh1) break;
+    float acc[VEC];
 #pragma unroll
-    for (int b = 0; b < 3; ++b)
+    for (int i = 0; i < VEC; ++i) acc[i] = bias[i];
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[i] = fmaf(row[b][i], w[a * 3 + b][i], acc[i]);
-  };
-  auto emit = [&](float* acc, int oh) {
-    float v[VEC];
+    for (int a = 0; a < 3; ++a)
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) v[i] = acc[i] + bias[i];
-    if (p.res) {
-      float rv[VEC];
-      Vec<T, VEC>::load((const T*)p.res +
-                            ((size_t)(n * p.r_rows + oh - p.r_row0) * p.W_out + ow) * p.C + c, rv);
+      for (int b = 0; b < 3; ++b) {
+        float x[VEC];
+        unpack<T>(in[r * S + a][b], x);
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) v[i] += rv[i];
-    }
+        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(x[i], w[a * 3 + b][i], acc[i]);
+      }
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) v[i] = clamp_act(v[i], clamp);
-    Vec<T, VEC>::store(yg + ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C + c, v);
-  };
-
-  float row[3][VEC];
-  if (S == 1) {
-    // Input row ih feeds outputs ih+1 (tap row 0), ih (tap row 1), ih-1 (tap row 2): three
-    // running sums; the loads of the next two rows are in flight while one is multiplied.
-    float s0[VEC], s1[VEC], s2[VEC];  // outputs ih-1, ih, ih+1
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) s0[i] = s1[i] = s2[i] = 0.f;
-    Raw ra[3], rb[3];
-    load_row(oh0 - 1, ra);
-    load_row(oh0, rb);
-    auto step = [&](int ih, Raw (&raw)[3]) {
-#pragma unroll
-      for (int b = 0; b < 3; ++b) unpack<T>(raw[b], row[b]);
-      load_row(ih + 2, raw);             // refill: rows past oh1 are never multiplied
-      if (ih - 1 >= oh0) mac(s0, row, 2);
-      if (ih >= oh0 && ih < oh1) mac(s1, row, 1);
-      if (ih + 1 < oh1) mac(s2, row, 0);
-      if (ih - 1 >= oh0) emit(s0, ih - 1);
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) { s0[i] = s1[i]; s1[i] = s2[i]; s2[i] = 0.f; }
-    };
-    for (int ih = oh0 - 1; ih <= oh1; ih += 2) {
-      step(ih, ra);
-      if (ih + 1 <= oh1) step(ih + 1, rb);
-    }
-  } else {
-    // Output oh reads rows 2oh-1, 2oh, 2oh+1; row 2oh+1 is also the first row of oh+1, whose
-    // sum is started right away so that no row is kept or read twice.
-    float cur[VEC];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) cur[i] = 0.f;
-    Raw r0[3], r1[3], r2[3];
-    load_row(2 * oh0 - 1, r0);
-    load_row(2 * oh0, r1);
-    load_row(2 * oh0 + 1, r2);
-#pragma unroll
-    for (int b = 0; b < 3; ++b) unpack<T>(r0[b], row[b]);
-    mac(cur, row, 0);
-    for (int oh = oh0; oh < oh1; ++oh) {
-#pragma unroll
-      for (int b = 0; b < 3; ++b) unpack<T>(r1[b], row[b]);
-      if (oh + 1 < oh1) load_row(2 * oh + 2, r1);
-      mac(cur, row, 1);
-#pragma unroll
-      for (int b = 0; b < 3; ++b) unpack<T>(r2[b], row[b]);
-      if (oh + 1 < oh1) load_row(2 * oh + 3, r2);
-      mac(cur, row, 2);
-      emit(cur, oh);
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) cur[i] = 0.f;
-      mac(cur, row, 0);
-    }
+    for (int i = 0; i < VEC; ++i) acc[i] = clamp_act(acc[i], clamp);
+    Vec<T, VEC>::store(yg + ((size_t)(n * p.y_rows + oh0 + r - p.y_row0) * p.W_out + ow) * p.C + c, acc);
   }
 }
 
@@ -314,7 +264,8 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(const Dw3Params q) {
 // rowwise_kernel.
 inline bool dw3_applies(const RowParams& p, int op, int vec) {
   return op == LOP_DWCONV2D && p.kh == 3 && p.kw == 3 && p.dh == 1 && p.dw == 1 && p.ph == 1 &&
-         p.pw == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && vec > 1 && p.C / vec <= 256;
+         p.pw == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) && vec > 1 && p.C / vec <= 256 &&
+         p.res == nullptr;
 }
 
 template <typename T, int VEC>
@@ -324,12 +275,7 @@ hipError_t launch_dw3(const RowParams& p, hipStream_t s) {
   q.r = p;
   const int cv = p.C / VEC;
   q.cols_per_block = std::max(1, 256 / cv);
-  // enough wavefronts to keep ~16 per SIMD queued: shorter row walks for small launches
-  const long waves_per_chunk = std::max<long>(1, (long)cv * p.W_out * p.N / 64);
-  const long chunks_wanted = (16384 + waves_per_chunk - 1) / waves_per_chunk;
-  const int rpt = (int)((p.R + chunks_wanted - 1) / chunks_wanted);
-  q.rows_per_thread = std::min(std::max(rpt, 4), 32);
-  q.chunks = (p.R + q.rows_per_thread - 1) / q.rows_per_thread;
+  q.chunks = (p.R + kDwRowsPerThread - 1) / kDwRowsPerThread;
   dim3 grid((p.W_out + q.cols_per_block - 1) / q.cols_per_block, q.chunks * p.N);
   if (p.sh == 1)
     hipLaunchKernelGGL((dwconv3x3_kernel<T, VEC, 1>), grid, dim3(256), 0, s, q);
@@ -418,7 +364,7 @@ int rowwise_describe(const OpLaunch& L, char* name, size_t size) {
   const int o = L.op == LOP_DWCONV2D ? 0 : (L.op == LOP_MAXPOOL2D ? 1 : 2);
   RowParams p;
   p.kh = L.kh; p.kw = L.kw; p.sh = L.sh; p.sw = L.sw; p.ph = L.ph; p.pw = L.pw;
-  p.dh = L.dh; p.dw = L.dw; p.C = L.x.c;
+  p.dh = L.dh; p.dw = L.dw; p.C = L.x.c; p.res = L.res.ptr;
   if (name && size) {
     if (const int v = dw3_vec(p, L.op, L.dtype))
       snprintf(name, size, "dwconv3x3_kernel<%s, %d, %d>", bf ? "__bf16" : "float", v, L.sh);
