@@ -34,7 +34,8 @@ struct ConvParams {
   const void* x;
   void* y;
   const void* res;
-  const void* w;
+  const void* w;   // [c_out_pad][k_pad]
+  const void* wd;  // the same weights in MFMA operand order (conv_direct_kernel), or nullptr
   const float* bias;
   float* ws;  // split-K partial sums [split][M][C_out], or nullptr
   int x_row0, x_rows, H, W, C_in;
@@ -395,20 +396,28 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const ConvParams p) 
   const float* src = p.ws + (size_t)m * p.C_out + co;
   const size_t slice = (size_t)p.M * p.C_out;
   if ((p.C_out & 3) == 0) {
+    constexpr int D = 8;  // loads in flight, added in slice order
     int s = 0;
-    for (; s + 4 <= p.splits; s += 4) {  // four loads in flight, added in slice order
-      const float4 t0 = *(const float4*)(src + (s + 0) * slice);
-      const float4 t1 = *(const float4*)(src + (s + 1) * slice);
-      const float4 t2 = *(const float4*)(src + (s + 2) * slice);
-      const float4 t3 = *(const float4*)(src + (s + 3) * slice);
-      v[0] = (((v[0] + t0.x) + t1.x) + t2.x) + t3.x;
-      v[1] = (((v[1] + t0.y) + t1.y) + t2.y) + t3.y;
-      v[2] = (((v[2] + t0.z) + t1.z) + t2.z) + t3.z;
-      v[3] = (((v[3] + t0.w) + t1.w) + t2.w) + t3.w;
+    for (; s + D <= p.splits; s += D) {
+      float4 t[D];
+#pragma unroll
+      for (int i = 0; i < D; ++i) t[i] = *(const float4*)(src + (s + i) * slice);
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        v[0] += t[i].x; v[1] += t[i].y; v[2] += t[i].z; v[3] += t[i].w;
+      }
     }
-    for (; s < p.splits; ++s) {
-      const float4 t = *(const float4*)(src + s * slice);
-      v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+    if (s < p.splits) {  // the last, partial group: slices past the end read as zero
+      float4 t[D];
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        t[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (s + i < p.splits) t[i] = *(const float4*)(src + (s + i) * slice);
+      }
+#pragma unroll
+      for (int i = 0; i < D; ++i) {
+        v[0] += t[i].x; v[1] += t[i].y; v[2] += t[i].z; v[3] += t[i].w;
+      }
     }
   } else {
     for (int s = 0; s < p.splits; ++s)
@@ -417,6 +426,245 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const ConvParams p) 
         if (co + j < p.C_out) v[j] += src[s * slice + j];
   }
   finish4<T>(p, pixel_addr(p, m), co, v);
+}
+
+// Small layers (few output pixels x channels, long reduction): one workgroup owns a
+// 32-pixel x (32*NT)-channel tile and its WK wavefronts split the reduction axis among
+// themselves, each taking one contiguous slice. Nothing is shared between the wavefronts
+// during the reduction, so operands go straight from global memory into MFMA operand
+// registers with no LDS staging and no barrier: per step a lane loads one 16-byte vector of
+// activations and one of weights per channel tile, U steps in flight. The weights come from
+// a second packing in operand order (p.wd: [channel tile of 32][step][lane] 16 bytes, lane =
+// half*32 + channel, holding k = step*MK + half*KE ... + KE), so a wavefront's weight load
+// is one contiguous KiB. What the epilogue needs (bias, residual, addresses) is loaded
+// before the reduction starts, so the kernel has one round of memory latency per U steps
+// plus one, not one more per epilogue operand. LDS is used once at the end to add the WK
+// partial tiles in wavefront order and to hand each thread a contiguous 16-byte piece.
+// With p.splits == 1 this replaces a split-K launch plus its finish kernel by one launch.
+// Layers whose weights are too large for one workgroup per tile to stream (a compute unit
+// sustains a small share of the HBM rate) also cut the reduction across blockIdx.z: every
+// slice writes its fp32 partial tile to p.ws and splitk_finish_kernel adds the slices.
+template <typename T, int WK, int NT>
+__global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p) {
+  constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
+  constexpr int MK = 2 * KE;               // reduction elements per step (two lane halves)
+  constexpr int U = 8;                     // steps of loads in flight
+  constexpr int BM = 32, BN = 32 * NT;
+  constexpr int CP = BN + 4;               // fp32 pitch of a staged partial tile
+  constexpr int RW = WK < 8 ? WK : 8;      // partial tiles staged per round
+  constexpr int VE = KE;
+  constexpr int CPR = BN / VE;             // 16-byte pieces per pixel of the tile
+  constexpr int SLOTS = BM * CPR;
+  constexpr int SPT = (SLOTS + 64 * WK - 1) / (64 * WK);  // pieces per thread
+  __shared__ __attribute__((aligned(16))) float part[RW][BM * CP];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int px = lane & 31, kg = lane >> 5;
+  const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+  const T* __restrict__ xg = (const T*)p.x;
+  const uint4* __restrict__ wg = (const uint4*)p.wd;
+  const bool partial = p.ws != nullptr;
+
+  // ---- epilogue operands of this thread's pieces, in flight during the reduction
+  bool e_ok[SPT];
+  size_t e_y[SPT];
+  int e_row[SPT], e_c[SPT];
+  float e_bias[SPT][VE];
+  uint4 e_res[SPT];
+#pragma unroll
+  for (int s = 0; s < SPT; ++s) {
+    const int slot = tid + s * 64 * WK;
+    e_row[s] = slot / CPR;
+    e_c[s] = (slot % CPR) * VE;
+    const int mo = m0 + e_row[s], co = co0 + e_c[s];
+    e_ok[s] = slot < SLOTS && mo < p.M && co < p.C_out;
+    e_res[s] = make_uint4(0, 0, 0, 0);
+    e_y[s] = 0;
+#pragma unroll
+    for (int j = 0; j < VE; ++j) e_bias[s][j] = 0.f;
+    if (e_ok[s] && partial) e_y[s] = ((size_t)blockIdx.z * p.M + mo) * p.C_out + co;
+    if (e_ok[s] && !partial) {
+      const PixelAddr pa = pixel_addr(p, mo);
+      e_y[s] = pa.y + co;
+      if (p.bias) {
+#pragma unroll
+        for (int j = 0; j < VE; j += 4) {
+          const float4 b4 = *(const float4*)(p.bias + co + j);
+          e_bias[s][j] = b4.x; e_bias[s][j + 1] = b4.y; e_bias[s][j + 2] = b4.z; e_bias[s][j + 3] = b4.w;
+        }
+      }
+      if (p.res) e_res[s] = *(const uint4*)((const T*)p.res + pa.r + co);
+    }
+  }
+
+  // ---- this lane's pixel
+  const int m = m0 + px;
+  const bool m_ok = m < p.M;
+  int ih0, iw0, nrow;
+  {
+    const int mm = m_ok ? m : 0;
+    const int ow = mm % p.W_out;
+    const int q = mm / p.W_out;
+    const int r = q % p.R, n = q / p.R;
+    ih0 = (p.out_lo + r) * p.sh - p.ph;
+    iw0 = ow * p.sw - p.pw;
+    nrow = n * p.x_rows - p.x_row0;
+  }
+  // this workgroup's slice of the reduction axis, then this wavefront's share of it, in
+  // steps of MK elements
+  const int steps_pad = p.k_pad / MK;         // pitch of the packed weights
+  const int steps_all = (p.K + MK - 1) / MK;  // steps that hold anything
+  const int z0 = blockIdx.z * p.kc_per_split, z1 = min(steps_all, z0 + p.kc_per_split);
+  const int per_wave = (z1 - z0 + WK - 1) / WK;
+  const int s0 = z0 + wave * per_wave, s1 = min(z1, s0 + per_wave);
+  // position of this lane's vector on the reduction axis: k = (khi*kw + kwi)*C_in + ci
+  int ci, kwi, khi;
+  {
+    const int k = s0 * MK + kg * KE;
+    const int tap = k / p.C_in;
+    ci = k - tap * p.C_in;
+    khi = tap / p.kw;
+    kwi = tap - khi * p.kw;
+  }
+  const uint4* wtile[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+    wtile[t] = wg + (size_t)(blockIdx.y * NT + t) * steps_pad * 64 + lane;
+
+  f32x16 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+
+  for (int sb = s0; sb < s1; sb += U) {
+    uint4 a[U], w[U][NT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool live = sb + u < s1;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        w[u][t] = make_uint4(0, 0, 0, 0);
+        if (live) w[u][t] = wtile[t][(size_t)(sb + u) * 64];
+      }
+      const int ih = ih0 + khi * p.dh, iw = iw0 + kwi * p.dw;
+      const bool ok = live && m_ok && khi < p.kh && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
+                      iw >= 0 && iw < p.W;
+      a[u] = make_uint4(0, 0, 0, 0);
+      if (ok) a[u] = *(const uint4*)(xg + ((size_t)(nrow + ih) * p.W + iw) * p.C_in + ci);
+      ci += MK;
+      while (ci >= p.C_in) {
+        ci -= p.C_in;
+        if (++kwi == p.kw) { kwi = 0; ++khi; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) mma<T>(w[u][t], a[u], acc[t]);
+  }
+
+  // ---- add the WK partial tiles in wavefront order, RW of them per round through LDS
+  float v[SPT][VE];
+#pragma unroll
+  for (int s = 0; s < SPT; ++s)
+#pragma unroll
+    for (int j = 0; j < VE; ++j) v[s][j] = 0.f;
+#pragma unroll
+  for (int round = 0; round < WK / RW; ++round) {
+    if (round) __syncthreads();  // the previous round's tiles have been read
+    if (wave / RW == round) {
+      float* const mine = part[wave % RW];
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *(float4*)(mine + px * CP + t * 32 + g * 8 + kg * 4) =
+              make_float4(acc[t][g * 4], acc[t][g * 4 + 1], acc[t][g * 4 + 2], acc[t][g * 4 + 3]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < SPT; ++s) {
+      if (!e_ok[s]) continue;
+#pragma unroll
+      for (int w = 0; w < RW; ++w)
+#pragma unroll
+        for (int j = 0; j < VE; j += 4) {
+          const float4 q = *(const float4*)(&part[w][e_row[s] * CP + e_c[s] + j]);
+          v[s][j] += q.x; v[s][j + 1] += q.y; v[s][j + 2] += q.z; v[s][j + 3] += q.w;
+        }
+    }
+  }
+  if (partial) {
+#pragma unroll
+    for (int s = 0; s < SPT; ++s) {
+      if (!e_ok[s]) continue;
+#pragma unroll
+      for (int j = 0; j < VE; j += 4)
+        *(float4*)(p.ws + e_y[s] + j) = make_float4(v[s][j], v[s][j + 1], v[s][j + 2], v[s][j + 3]);
+    }
+    return;
+  }
+  // ---- bias + residual + activation + the one rounding, one 16-byte store per piece
+  const Clamp cl = make_clamp(p.act);
+#pragma unroll
+  for (int s = 0; s < SPT; ++s) {
+    if (!e_ok[s]) continue;
+    alignas(16) T rr[VE];
+    *(uint4*)rr = e_res[s];
+    alignas(16) T o[VE];
+#pragma unroll
+    for (int j = 0; j < VE; ++j)
+      o[j] = from_f32<T>(clamp_act(v[s][j] + e_bias[s][j] + to_f32(rr[j]), cl));
+    *(uint4*)((T*)p.y + e_y[s]) = *(const uint4*)o;
+  }
+}
+
+// Whether (and how) the direct kernel takes a launch: only layers that the tiled kernel
+// would cut along the reduction axis, with vectorisable channel counts.
+struct DirectChoice {
+  int wk, nt;      // wk == 0: not applicable
+  int z, per_z;    // slices of the reduction across workgroups, steps per slice
+};
+DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
+  const int ke = dtype == LOP_BF16 ? 8 : 4;
+  if (!p.wd || splits <= 1 || p.C_in % ke != 0 || p.C_out % ke != 0) return {0, 0, 0, 0};
+  const int steps = (p.K + 2 * ke - 1) / (2 * ke);
+  const long mt32 = (p.M + 31) / 32, nt32 = (p.C_out + 31) / 32;
+  // one workgroup per tile streams steps KiB of weights and as much of activations, and
+  // fp32 MFMA runs at 1/16 of the bf16 rate: beyond these lengths the reduction is cut
+  const int single_max = dtype == LOP_BF16 ? 256 : 128;
+  DirectChoice d{4, 1, 1, steps};
+  if (steps <= single_max) {
+    if (p.C_out > 32 && mt32 * nt32 >= 512) d.nt = 2;  // plenty of workgroups anyway
+    while (d.wk < 16 && (steps + d.wk - 1) / d.wk > 8) d.wk *= 2;
+    return d;
+  }
+  // a slice is one round of loads per wavefront (4 wavefronts x 8 steps)
+  d.z = std::min(64, (steps + 31) / 32);
+  d.per_z = (steps + d.z - 1) / d.z;
+  d.z = (steps + d.per_z - 1) / d.per_z;
+  return d;
+}
+
+template <typename T, int WK, int NT>
+hipError_t launch_direct(const ConvParams& p, hipStream_t s) {
+  dim3 grid((p.M + 31) / 32, (p.C_out + 32 * NT - 1) / (32 * NT), p.splits);
+  hipLaunchKernelGGL((conv_direct_kernel<T, WK, NT>), grid, dim3(64 * WK), 0, s, p);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_direct_any(const ConvParams& p, const DirectChoice& d, hipStream_t s) {
+  if (d.nt == 2) {
+    if (d.wk == 4) return launch_direct<T, 4, 2>(p, s);
+    if (d.wk == 8) return launch_direct<T, 8, 2>(p, s);
+    return launch_direct<T, 16, 2>(p, s);
+  }
+  if (d.wk == 4) return launch_direct<T, 4, 1>(p, s);
+  if (d.wk == 8) return launch_direct<T, 8, 1>(p, s);
+  return launch_direct<T, 16, 1>(p, s);
 }
 
 enum Shape { S128x128, S128x64, S64x64, S128x32 };
@@ -456,6 +704,13 @@ Choice choose(const ConvParams& p, int dtype) {
   return c;
 }
 
+template <typename T>
+hipError_t launch_finish(const ConvParams& p, hipStream_t s) {
+  const long work = (long)p.M * ((p.C_out + 3) / 4);
+  hipLaunchKernelGGL((splitk_finish_kernel<T>), dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
 template <typename T, int BM, int BN, int WM, int WN>
 hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, hipEvent_t mid) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
@@ -466,9 +721,7 @@ hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, hipEvent
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || !p.ws) return e;
   if (mid && (e = hipEventRecord(mid, s)) != hipSuccess) return e;
-  const long work = (long)p.M * ((p.C_out + 3) / 4);
-  hipLaunchKernelGGL((splitk_finish_kernel<T>), dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, p);
-  return hipGetLastError();
+  return launch_finish<T>(p, s);
 }
 
 template <typename T>
@@ -476,6 +729,17 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, hipE
   constexpr int KE = 16 / (int)sizeof(T);
   const bool vec_a = p.C_in % KE == 0;
   const Choice c = choose(p, dtype);
+  const DirectChoice d = choose_direct(p, dtype, c.splits);
+  if (d.wk) {
+    if (d.z > 1 && !ws) return hipErrorInvalidValue;
+    p.splits = d.z;
+    p.kc_per_split = d.per_z;
+    p.ws = d.z > 1 ? ws : nullptr;
+    hipError_t e = launch_direct_any<T>(p, d, s);
+    if (e != hipSuccess || !p.ws) return e;
+    if (mid && (e = hipEventRecord(mid, s)) != hipSuccess) return e;
+    return launch_finish<T>(p, s);
+  }
   p.splits = c.splits;
   p.kc_per_split = c.kc_per_split;
   if (c.splits > 1 && !ws) return hipErrorInvalidValue;
@@ -490,7 +754,7 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, hipE
 
 ConvParams make_params(const OpLaunch& L) {
   ConvParams p;
-  p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = L.w; p.bias = L.bias;
+  p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = L.w; p.wd = L.wd; p.bias = L.bias;
   p.ws = nullptr;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.H = L.x.h; p.W = L.x.w; p.C_in = L.x.c;
   p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w; p.C_out = L.y.c;
@@ -518,6 +782,8 @@ size_t conv_workspace_bytes(const OpLaunch& L) {
   const ConvParams p = make_params(L);
   if (p.M <= 0) return 0;
   const Choice c = choose(p, L.dtype);
+  const DirectChoice d = choose_direct(p, L.dtype, c.splits);
+  if (d.wk) return d.z > 1 ? (size_t)d.z * p.M * p.C_out * sizeof(float) : 0;
   return c.splits > 1 ? (size_t)c.splits * p.M * p.C_out * sizeof(float) : 0;
 }
 
@@ -535,6 +801,12 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const bool vec = p.C_in % (bf ? 8 : 4) == 0;
   const Choice c = choose(p, L.dtype);
   static const int wm[] = {2, 2, 2, 4}, wn[] = {2, 2, 2, 1};
+  const DirectChoice d = choose_direct(p, L.dtype, c.splits);
+  if (d.wk) {
+    if (name && size)
+      snprintf(name, size, "conv_direct_kernel<%s, %d, %d>", bf ? "__bf16" : "float", d.wk, d.nt);
+    return d.z;
+  }
   if (name && size)
     snprintf(name, size, "conv_igemm_kernel<%s, %d, %d, %d, %d, %d, %d, %s>", bf ? "__bf16" : "float",
              c.bm, c.bn, wm[c.shape], wn[c.shape], kBKB, kStages, vec ? "true" : "false");

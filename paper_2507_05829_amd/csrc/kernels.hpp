@@ -20,6 +20,7 @@ struct OpLaunch {
   int dtype = 0;  // lop_dtype_t
   Slab x, y, res; // res.ptr == nullptr: no residual
   const void* w = nullptr;      // device, kernel layout (see pack_* below)
+  const void* wd = nullptr;     // dense conv: the weights in operand order, or nullptr
   const float* bias = nullptr;  // device or nullptr
   int kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0, dh = 1, dw = 1;
   int act = 0;
@@ -31,6 +32,10 @@ struct OpLaunch {
 
 // Dense conv weights are packed as [c_out_pad][k_pad], k = (a*kw + b)*c_in + ci, zero
 // padded so the kernel never guards weight loads.
+// Layers whose c_in and c_out are multiples of the 16-byte vector get a second packing in
+// MFMA operand order for the small-layer kernel: [c_out_pad / 32][k_pad / MK][64 lanes] x 16
+// bytes, MK = 2 vectors of elements; lane = half*32 + (co % 32) holds
+// w[co][step*MK + half*KE ... + KE) of the first packing.
 constexpr int kConvCoutPad = 128;
 int conv_k_pad(int c_in, int kh, int kw, int dtype);
 inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvCoutPad * kConvCoutPad; }

@@ -71,6 +71,7 @@ struct lop_plan_s {
   bool ready = false;
   int device = -1;
   std::vector<void*> d_w;      // per layer packed weights (device) or nullptr
+  std::vector<void*> d_wd;     // dense conv weights in MFMA operand order, or nullptr
   std::vector<float*> d_bias;  // per layer bias (device) or nullptr
   std::vector<int> k_pad;
   size_t conv_ws_bytes = 0;
@@ -114,6 +115,7 @@ int upload_weights(lop_plan_t* P) {
   const int nl = t.n_layers();
   const bool bf = t.in.dtype == LOP_BF16;
   P->d_w.assign(nl, nullptr);
+  P->d_wd.assign(nl, nullptr);
   P->d_bias.assign(nl, nullptr);
   P->k_pad.assign(nl, 0);
   for (int l = 0; l < nl; ++l) {
@@ -137,6 +139,21 @@ int upload_weights(lop_plan_t* P) {
             }
       LOP_HIP(hipMalloc(&P->d_w[l], host.size()));
       LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size(), hipMemcpyHostToDevice));
+      const int ke = 16 / (int)esz;
+      if (d.c_in % ke == 0 && d.c_out % ke == 0) {
+        // the same values in MFMA operand order: [co / 32][step][half*32 + co % 32] x 16 B
+        std::vector<unsigned char> ord(host.size());
+        const size_t steps = (size_t)kp / (2 * ke);
+        for (int co = 0; co < cp; ++co)
+          for (size_t st = 0; st < steps; ++st)
+            for (int half = 0; half < 2; ++half) {
+              const size_t src = (size_t)co * kp + st * 2 * ke + (size_t)half * ke;
+              const size_t dst = (((size_t)(co / 32) * steps + st) * 64 + half * 32 + co % 32) * ke;
+              std::memcpy(&ord[dst * esz], &host[src * esz], 16);
+            }
+        LOP_HIP(hipMalloc(&P->d_wd[l], ord.size()));
+        LOP_HIP(hipMemcpy(P->d_wd[l], ord.data(), ord.size(), hipMemcpyHostToDevice));
+      }
     } else if (d.op == LOP_DWCONV2D) {
       if (!d.weight) return LOP_ERR_INVALID_ARG;
       // C x 1 x kh x kw (storage type) -> [tap][C] fp32
@@ -229,6 +246,7 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
   o.y = slab_of(P, band, l, d_in, d_out);
   if (L.d.residual_from != LOP_NO_RESIDUAL) o.res = slab_of(P, band, L.d.residual_from, d_in, d_out);
   o.w = P->d_w[l];
+  o.wd = P->d_wd[l];
   o.bias = P->d_bias[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
   o.ph = L.d.ph; o.pw = L.d.pw; o.dh = L.d.dh; o.dw = L.d.dw;
@@ -508,6 +526,7 @@ void lop_plan_destroy(lop_plan_t* P) {
   if (P->s_main) (void)hipStreamSynchronize(P->s_main);
   if (P->s_copy) (void)hipStreamSynchronize(P->s_copy);
   for (void* w : P->d_w) if (w) (void)hipFree(w);
+  for (void* w : P->d_wd) if (w) (void)hipFree(w);
   for (float* b : P->d_bias) if (b) (void)hipFree(b);
   for (auto* v : {&P->ev_done, &P->ev_copied, &P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);

@@ -286,8 +286,8 @@ hipError_t launch_dw3(const RowParams& p, hipStream_t s) {
 
 // Channel vector per thread of the sliding-window kernel (0: it does not apply).
 inline int dw3_vec(const RowParams& p, int op, int dtype) {
-  static const int force = getenv("LOP_DW_VEC") ? atoi(getenv("LOP_DW_VEC")) : 0;
-  const int want = dtype == LOP_BF16 ? (force ? force : 4) : 4;
+  (void)dtype;
+  const int want = 4;
   if (p.C % want != 0) return 0;
   return dw3_applies(p, op, want) ? want : 0;
 }

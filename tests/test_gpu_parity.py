@@ -50,6 +50,12 @@ CONV_GRID = [
     (16, 6, 3, 1, 1, 1, (1, 8, 8)),        # c_out not a multiple of 4 (scalar stores)
     (5, 7, 2, 1, 0, 1, (1, 9, 9)),         # even kernel, odd channels
     (128, 256, 3, 1, 1, 1, (1, 10, 30)),   # several N tiles
+    # few pixels, long reductions: the kernel whose wavefronts split the reduction axis
+    (64, 64, 3, 1, 1, 1, (1, 14, 12)),     # with the residual variant below
+    (64, 72, 3, 1, 1, 1, (2, 9, 7)),       # c_out not a multiple of the 32-channel tile
+    (256, 64, 3, 1, 1, 1, (1, 6, 9)),      # fp32: reduction also cut across workgroups
+    (512, 40, 3, 2, 1, 1, (1, 9, 8)),      # bf16: reduction also cut across workgroups
+    (40, 24, 5, 1, 4, 2, (1, 12, 9)),      # dilated 5x5, K = 1000: half-filled last step
 ]
 
 
@@ -84,6 +90,25 @@ def test_conv_random_within_tolerance(oracle, cfg, dtype):
     want = oracle.run_chain(chain, t)
     dev, _ = run_gpu(chain, t)
     assert rel_err(dev, want) <= TOL[dtype]
+
+
+def test_small_layer_kernel_is_selected():
+    """The grid above reaches every variant of the small-layer kernel: one launch, and a
+    launch cut across workgroups followed by the finish kernel."""
+    seen = set()
+    for dtype in ("f32", "bf16"):
+        for cfg in CONV_GRID:
+            c_in, c_out, k, s, p, d, shape = cfg
+            chain = _single(workloads.CONV, c_in, c_out, k, s, p, d, "relu", dtype, shape)
+            plan = lop.Plan(chain, workloads.make_tensors(chain, seed=1))
+            try:
+                for b in range(plan.n_bands):
+                    name, slices = plan.layer_kernel(b, 0)
+                    if name.startswith("conv_direct_kernel"):
+                        seen.add((dtype, slices > 1))
+            finally:
+                plan.destroy()
+    assert seen == {("f32", False), ("f32", True), ("bf16", False), ("bf16", True)}
 
 
 ROW_GRID = [
