@@ -18,6 +18,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <type_traits>
 
 #include "act.hpp"
 #include "kernels.hpp"
@@ -29,6 +30,10 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// 16 bytes in registers: a native vector, so that copies of it are loads and stores the
+// optimiser can keep in registers (copies of HIP's uint4 struct are memcpy calls, and an
+// array of them that is filled from memory stays in private memory)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct ConvParams {
   const void* x;
@@ -59,17 +64,25 @@ template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float v) { return (__bf16)v; }
 
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
 template <typename T>
-__device__ __forceinline__ void mma(const uint4& wa, const uint4& px, f32x16& acc);
+__device__ __forceinline__ void mma(const u32x4& wa, const u32x4& px, f32x16& acc);
 
 template <>
-__device__ __forceinline__ void mma<__bf16>(const uint4& wa, const uint4& px, f32x16& acc) {
+__device__ __forceinline__ void mma<__bf16>(const u32x4& wa, const u32x4& px, f32x16& acc) {
   acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wa),
                                                 __builtin_bit_cast(bf16x8, px), acc, 0, 0, 0);
 }
 
 template <>
-__device__ __forceinline__ void mma<float>(const uint4& wa, const uint4& px, f32x16& acc) {
+__device__ __forceinline__ void mma<float>(const u32x4& wa, const u32x4& px, f32x16& acc) {
   const f32x4 a = __builtin_bit_cast(f32x4, wa), b = __builtin_bit_cast(f32x4, px);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc, 0, 0, 0);
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc, 0, 0, 0);
@@ -105,7 +118,7 @@ __device__ __forceinline__ void finish4(const ConvParams& p, const PixelAddr& a,
     if (rg) {
       alignas(16) T rr[4];
       if (sizeof(T) == 2) *(uint2*)rr = *(const uint2*)(rg + a.r + co);
-      else *(uint4*)rr = *(const uint4*)(rg + a.r + co);
+      else *(u32x4*)rr = *(const u32x4*)(rg + a.r + co);
 #pragma unroll
       for (int j = 0; j < 4; ++j) v[j] += to_f32(rr[j]);
     }
@@ -113,7 +126,7 @@ __device__ __forceinline__ void finish4(const ConvParams& p, const PixelAddr& a,
 #pragma unroll
     for (int j = 0; j < 4; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
     if (sizeof(T) == 2) *(uint2*)(yg + a.y + co) = *(const uint2*)o;
-    else *(uint4*)(yg + a.y + co) = *(const uint4*)o;
+    else *(u32x4*)(yg + a.y + co) = *(const u32x4*)o;
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -140,14 +153,14 @@ __device__ __forceinline__ void finish_vec(const ConvParams& p, int m, int co, f
   }
   if (p.res) {
     alignas(16) T rr[VE];
-    *(uint4*)rr = *(const uint4*)((const T*)p.res + pa.r + co);
+    *(u32x4*)rr = *(const u32x4*)((const T*)p.res + pa.r + co);
 #pragma unroll
     for (int j = 0; j < VE; ++j) v[j] += to_f32(rr[j]);
   }
   alignas(16) T o[VE];
 #pragma unroll
   for (int j = 0; j < VE; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
-  *(uint4*)((T*)p.y + pa.y + co) = *(const uint4*)o;
+  *(u32x4*)((T*)p.y + pa.y + co) = *(const u32x4*)o;
 }
 
 // BM pixels x BN channels per workgroup; WM x WN wavefronts; BKB bytes of the reduction
@@ -206,19 +219,20 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
     kwi = tap - khi * p.kw;
   }
 
-  uint4 ra_s[NS][A_IT], rb_s[NS][B_IT];  // NS steps of global loads in flight
+  // NS steps of global loads in flight
+  u32x4 ra0[A_IT], ra1[A_IT], ra2[A_IT], rb0[B_IT], rb1[B_IT], rb2[B_IT];
 
-  auto gather = [&](int kc, uint4 (&ra)[A_IT], uint4 (&rb)[B_IT]) {
+  auto gather = [&](int kc, u32x4 (&ra)[A_IT], u32x4 (&rb)[B_IT]) __attribute__((always_inline)) {
     if (VEC_A) {
 #pragma unroll
       for (int i = 0; i < A_IT; ++i) {
         const int ih = a_ih0[i] + khi * p.dh, iw = a_iw0[i] + kwi * p.dw;
         const bool ok = a_ok[i] && khi < p.kh && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
                         iw >= 0 && iw < p.W;
-        uint4 v = make_uint4(0, 0, 0, 0);
+        u32x4 v = u32x4{0u, 0u, 0u, 0u};
         if (ok) {
           const size_t off = ((size_t)(a_nrow[i] + ih) * p.W + iw) * p.C_in + ci;
-          v = *(const uint4*)(xg + off);
+          v = *(const u32x4*)(xg + off);
         }
         ra[i] = v;
       }
@@ -241,26 +255,26 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
                           iw >= 0 && iw < p.W;
           e[j] = ok ? xg[((size_t)(a_nrow[i] + ih) * p.W + iw) * p.C_in + c] : from_f32<T>(0.f);
         }
-        ra[i] = *(const uint4*)e;
+        ra[i] = *(const u32x4*)e;
       }
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
       const int row = lrow + RPP * i;
       if (BN % RPP == 0 || row < BN)
-        rb[i] = *(const uint4*)(wg + (size_t)(co0 + row) * p.k_pad + kc * BKE + chunk * KE);
+        rb[i] = *(const u32x4*)(wg + (size_t)(co0 + row) * p.k_pad + kc * BKE + chunk * KE);
     }
   };
-  auto stash = [&](int buf, const uint4 (&ra)[A_IT], const uint4 (&rb)[B_IT]) {
+  auto stash = [&](int buf, const u32x4 (&ra)[A_IT], const u32x4 (&rb)[B_IT]) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const int row = lrow + RPP * i;
-      if (BM % RPP == 0 || row < BM) *(uint4*)(As + (buf * BM + row) * ROWB + chunk * 16) = ra[i];
+      if (BM % RPP == 0 || row < BM) *(u32x4*)(As + (buf * BM + row) * ROWB + chunk * 16) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
       const int row = lrow + RPP * i;
-      if (BN % RPP == 0 || row < BN) *(uint4*)(Bs + (buf * BN + row) * ROWB + chunk * 16) = rb[i];
+      if (BN % RPP == 0 || row < BN) *(u32x4*)(Bs + (buf * BN + row) * ROWB + chunk * 16) = rb[i];
     }
   };
 
@@ -275,35 +289,43 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   // Software pipeline: the global loads of NS steps are in flight in registers; each
   // step moves the oldest one into the LDS buffer the previous step is not reading,
   // refills its registers with the step NS ahead and multiplies. One barrier per step.
+  // (every stage is a variable of its own and the step body is written out once per
+  // stage: indexed through an array of stages they end up in private memory)
+  static_assert(NS == 3, "the pipeline below is written out for three stages");
+  if (kc0 + 0 < kc1) gather(kc0 + 0, ra0, rb0);
+  if (kc0 + 1 < kc1) gather(kc0 + 1, ra1, rb1);
+  if (kc0 + 2 < kc1) gather(kc0 + 2, ra2, rb2);
+  auto multiply = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-  for (int st = 0; st < NS; ++st)
-    if (kc0 + st < kc1) gather(kc0 + st, ra_s[st], rb_s[st]);
-  for (int kc = kc0; kc < kc1; kc += NS) {
+    for (int ks = 0; ks < BKB / 32; ++ks) {
+      u32x4 px[TM], wt[TN];
+      const int koff = ks * 32 + (lane >> 5) * 16;
 #pragma unroll
-    for (int st = 0; st < NS; ++st) {
-      if (kc + st < kc1) {
-        const int buf = (NS % 2 == 0) ? (st & 1) : ((kc - kc0 + st) & 1);
-        stash(buf, ra_s[st], rb_s[st]);
-        __syncthreads();
-        if (kc + st + NS < kc1) gather(kc + st + NS, ra_s[st], rb_s[st]);
+      for (int tm = 0; tm < TM; ++tm)
+        px[tm] = *(const u32x4*)(As + (buf * BM + (wm * TM + tm) * 32 + (lane & 31)) * ROWB + koff);
 #pragma unroll
-        for (int ks = 0; ks < BKB / 32; ++ks) {
-          uint4 px[TM], wt[TN];
-          const int koff = ks * 32 + (lane >> 5) * 16;
+      for (int tn = 0; tn < TN; ++tn)
+        wt[tn] = *(const u32x4*)(Bs + (buf * BN + (wn * TN + tn) * 32 + (lane & 31)) * ROWB + koff);
 #pragma unroll
-          for (int tm = 0; tm < TM; ++tm)
-            px[tm] = *(const uint4*)(As + (buf * BM + (wm * TM + tm) * 32 + (lane & 31)) * ROWB + koff);
+      for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-          for (int tn = 0; tn < TN; ++tn)
-            wt[tn] = *(const uint4*)(Bs + (buf * BN + (wn * TN + tn) * 32 + (lane & 31)) * ROWB + koff);
-#pragma unroll
-          for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
-        }
-      }
+        for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
     }
+  };
+#define LOP_CONV_STEP(ST, RA, RB)                                   \
+  if (kc + ST < kc1) {                                              \
+    const int buf = (kc - kc0 + ST) & 1;                            \
+    stash(buf, RA, RB);                                             \
+    __syncthreads();                                                \
+    if (kc + ST + NS < kc1) gather(kc + ST + NS, RA, RB);           \
+    multiply(buf);                                                  \
   }
+  for (int kc = kc0; kc < kc1; kc += NS) {
+    LOP_CONV_STEP(0, ra0, rb0)
+    LOP_CONV_STEP(1, ra1, rb1)
+    LOP_CONV_STEP(2, ra2, rb2)
+  }
+#undef LOP_CONV_STEP
 
   // ---- epilogue. In the accumulator a lane holds, per 32x32 tile, pixel (lane & 31) and
   // channels g*8 + (lane >> 5)*4 + {0..3}, g = 0..3. The tile goes through LDS once so that
@@ -448,7 +470,7 @@ template <typename T, int WK, int NT>
 __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p) {
   constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
   constexpr int MK = 2 * KE;               // reduction elements per step (two lane halves)
-  constexpr int U = 8;                     // steps of loads in flight
+  constexpr int U = (WK == 16 && NT == 2) ? 4 : 8;  // steps of loads in flight (register budget)
   constexpr int BM = 32, BN = 32 * NT;
   constexpr int CP = BN + 4;               // fp32 pitch of a staged partial tile
   constexpr int RW = WK < 8 ? WK : 8;      // partial tiles staged per round
@@ -463,7 +485,7 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
   const int px = lane & 31, kg = lane >> 5;
   const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
   const T* __restrict__ xg = (const T*)p.x;
-  const uint4* __restrict__ wg = (const uint4*)p.wd;
+  const u32x4* __restrict__ wg = (const u32x4*)p.wd;
   const bool partial = p.ws != nullptr;
 
   // ---- epilogue operands of this thread's pieces, in flight during the reduction
@@ -471,7 +493,7 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
   size_t e_y[SPT];
   int e_row[SPT], e_c[SPT];
   float e_bias[SPT][VE];
-  uint4 e_res[SPT];
+  u32x4 e_res[SPT];
 #pragma unroll
   for (int s = 0; s < SPT; ++s) {
     const int slot = tid + s * 64 * WK;
@@ -479,7 +501,7 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
     e_c[s] = (slot % CPR) * VE;
     const int mo = m0 + e_row[s], co = co0 + e_c[s];
     e_ok[s] = slot < SLOTS && mo < p.M && co < p.C_out;
-    e_res[s] = make_uint4(0, 0, 0, 0);
+    e_res[s] = u32x4{0u, 0u, 0u, 0u};
     e_y[s] = 0;
 #pragma unroll
     for (int j = 0; j < VE; ++j) e_bias[s][j] = 0.f;
@@ -494,7 +516,7 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
           e_bias[s][j] = b4.x; e_bias[s][j + 1] = b4.y; e_bias[s][j + 2] = b4.z; e_bias[s][j + 3] = b4.w;
         }
       }
-      if (p.res) e_res[s] = *(const uint4*)((const T*)p.res + pa.r + co);
+      if (p.res) e_res[s] = *(const u32x4*)((const T*)p.res + pa.r + co);
     }
   }
 
@@ -527,7 +549,7 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
     khi = tap / p.kw;
     kwi = tap - khi * p.kw;
   }
-  const uint4* wtile[NT];
+  const u32x4* wtile[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
     wtile[t] = wg + (size_t)(blockIdx.y * NT + t) * steps_pad * 64 + lane;
@@ -539,20 +561,20 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
     for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
   for (int sb = s0; sb < s1; sb += U) {
-    uint4 a[U], w[U][NT];
+    u32x4 a[U], w[U][NT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool live = sb + u < s1;
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        w[u][t] = make_uint4(0, 0, 0, 0);
+        w[u][t] = u32x4{0u, 0u, 0u, 0u};
         if (live) w[u][t] = wtile[t][(size_t)(sb + u) * 64];
       }
       const int ih = ih0 + khi * p.dh, iw = iw0 + kwi * p.dw;
       const bool ok = live && m_ok && khi < p.kh && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
                       iw >= 0 && iw < p.W;
-      a[u] = make_uint4(0, 0, 0, 0);
-      if (ok) a[u] = *(const uint4*)(xg + ((size_t)(nrow + ih) * p.W + iw) * p.C_in + ci);
+      a[u] = u32x4{0u, 0u, 0u, 0u};
+      if (ok) a[u] = *(const u32x4*)(xg + ((size_t)(nrow + ih) * p.W + iw) * p.C_in + ci);
       ci += MK;
       while (ci >= p.C_in) {
         ci -= p.C_in;
@@ -612,12 +634,12 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
   for (int s = 0; s < SPT; ++s) {
     if (!e_ok[s]) continue;
     alignas(16) T rr[VE];
-    *(uint4*)rr = e_res[s];
+    *(u32x4*)rr = e_res[s];
     alignas(16) T o[VE];
 #pragma unroll
     for (int j = 0; j < VE; ++j)
       o[j] = from_f32<T>(clamp_act(v[s][j] + e_bias[s][j] + to_f32(rr[j]), cl));
-    *(uint4*)((T*)p.y + e_y[s]) = *(const uint4*)o;
+    *(u32x4*)((T*)p.y + e_y[s]) = *(const u32x4*)o;
   }
 }
 
