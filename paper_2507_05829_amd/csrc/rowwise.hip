@@ -352,7 +352,10 @@ hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len
                             hipStream_t stream) {
   if (len == 0 || n <= 0) return hipSuccess;
   const size_t vec = (len + 15) / 16;
-  const unsigned grid = (unsigned)std::min<size_t>((vec + 255) / 256, 64);
+  // Few workgroups on purpose: the stores are paced by PCIe, and many of them in flight
+  // hold up the HBM writes of the kernels running beside the copy (4 workgroups still move
+  // about 30 GB/s; with 64 the copy was 1.7x faster and the other streams lost more than that).
+  const unsigned grid = (unsigned)std::min<size_t>((vec + 255) / 256, 4);
   hipLaunchKernelGGL(copy_rows_kernel, dim3(grid), dim3(256), 0, stream, (char*)dst,
                      (const char*)src, pitch, len, n);
   return hipGetLastError();
