@@ -88,7 +88,8 @@ def timed_copies(torch, plan, d_out, h_out, steps, warmup):
 
 def kernel_table(plan, d_in, d_out, iters, dtype):
     """Per kernel instance (named as rocprofv3 prints it): launches per chain, mean duration
-    from HIP events around every launch on its stream, algorithmic work. The finish kernel
+    from a start and a stop HIP event attached to every dispatch on its stream (the kernel's
+    own duration, as a profiler's kernel trace reports it), algorithmic work. The finish kernel
     of a split-K convolution is listed on its own; the layer's algorithmic FLOP and bytes
     are booked on the convolution kernel."""
     ms, fin = plan.profile_chain(d_in, d_out, iters)

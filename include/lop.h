@@ -179,8 +179,9 @@ LOP_API int lop_time_layer(lop_plan_t* plan, int band, int layer, const void* d_
 LOP_API int lop_plan_layer_kernel(const lop_plan_t* plan, int band, int layer, char* name, size_t size,
                                   int* k_slices);
 
-/* Run the whole chain `iters` times, bands in order on one stream, with an event before and
- * after every kernel, and write the mean milliseconds of each (band, layer) main kernel to
+/* Run the whole chain `iters` times, bands in order on one stream, with a start and a stop
+ * event attached to every kernel dispatch (the kernel's own duration, as a profiler's kernel
+ * trace reports it), and write the mean milliseconds of each (band, layer) main kernel to
  * layer_ms[band * n_layers + layer] and of its splitk_finish_kernel (0 if none) to
  * finish_ms[...] (host, n_bands * n_layers floats each; finish_ms may be NULL, the finish
  * time is then not reported). No host copies. Synchronous. Measurement aid. */

@@ -22,6 +22,7 @@
 
 #include "act.hpp"
 #include "kernels.hpp"
+#include "launch.hpp"
 #include "lop.h"
 
 namespace lop {
@@ -671,22 +672,22 @@ DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
 }
 
 template <typename T, int WK, int NT>
-hipError_t launch_direct(const ConvParams& p, hipStream_t s) {
+hipError_t launch_direct(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
   dim3 grid((p.M + 31) / 32, (p.C_out + 32 * NT - 1) / (32 * NT), p.splits);
-  hipLaunchKernelGGL((conv_direct_kernel<T, WK, NT>), grid, dim3(64 * WK), 0, s, p);
-  return hipGetLastError();
+  return launch_kernel(conv_direct_kernel<T, WK, NT>, grid, dim3(64 * WK), s, ev, p);
 }
 
 template <typename T>
-hipError_t launch_direct_any(const ConvParams& p, const DirectChoice& d, hipStream_t s) {
+hipError_t launch_direct_any(const ConvParams& p, const DirectChoice& d, hipStream_t s,
+                             KernelEvents* ev) {
   if (d.nt == 2) {
-    if (d.wk == 4) return launch_direct<T, 4, 2>(p, s);
-    if (d.wk == 8) return launch_direct<T, 8, 2>(p, s);
-    return launch_direct<T, 16, 2>(p, s);
+    if (d.wk == 4) return launch_direct<T, 4, 2>(p, s, ev);
+    if (d.wk == 8) return launch_direct<T, 8, 2>(p, s, ev);
+    return launch_direct<T, 16, 2>(p, s, ev);
   }
-  if (d.wk == 4) return launch_direct<T, 4, 1>(p, s);
-  if (d.wk == 8) return launch_direct<T, 8, 1>(p, s);
-  return launch_direct<T, 16, 1>(p, s);
+  if (d.wk == 4) return launch_direct<T, 4, 1>(p, s, ev);
+  if (d.wk == 8) return launch_direct<T, 8, 1>(p, s, ev);
+  return launch_direct<T, 16, 1>(p, s, ev);
 }
 
 enum Shape { S128x128, S128x64, S64x64, S128x32 };
@@ -727,27 +728,23 @@ Choice choose(const ConvParams& p, int dtype) {
 }
 
 template <typename T>
-hipError_t launch_finish(const ConvParams& p, hipStream_t s) {
+hipError_t launch_finish(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
   const long work = (long)p.M * ((p.C_out + 3) / 4);
-  hipLaunchKernelGGL((splitk_finish_kernel<T>), dim3((unsigned)((work + 255) / 256)), dim3(256), 0, s, p);
-  return hipGetLastError();
+  return launch_kernel(splitk_finish_kernel<T>, dim3((unsigned)((work + 255) / 256)), dim3(256), s, ev, p);
 }
 
 template <typename T, int BM, int BN, int WM, int WN>
-hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, hipEvent_t mid) {
+hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, KernelEvents* ev) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
-  if (vec_a)
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>), grid, dim3(256), 0, s, p);
-  else
-    hipLaunchKernelGGL((conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>), grid, dim3(256), 0, s, p);
-  hipError_t e = hipGetLastError();
+  const hipError_t e =
+      vec_a ? launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>, grid, dim3(256), s, ev, p)
+            : launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>, grid, dim3(256), s, ev, p);
   if (e != hipSuccess || !p.ws) return e;
-  if (mid && (e = hipEventRecord(mid, s)) != hipSuccess) return e;
-  return launch_finish<T>(p, s);
+  return launch_finish<T>(p, s, ev);
 }
 
 template <typename T>
-hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, hipEvent_t mid) {
+hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, KernelEvents* ev) {
   constexpr int KE = 16 / (int)sizeof(T);
   const bool vec_a = p.C_in % KE == 0;
   const Choice c = choose(p, dtype);
@@ -757,20 +754,19 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, hipE
     p.splits = d.z;
     p.kc_per_split = d.per_z;
     p.ws = d.z > 1 ? ws : nullptr;
-    hipError_t e = launch_direct_any<T>(p, d, s);
+    const hipError_t e = launch_direct_any<T>(p, d, s, ev);
     if (e != hipSuccess || !p.ws) return e;
-    if (mid && (e = hipEventRecord(mid, s)) != hipSuccess) return e;
-    return launch_finish<T>(p, s);
+    return launch_finish<T>(p, s, ev);
   }
   p.splits = c.splits;
   p.kc_per_split = c.kc_per_split;
   if (c.splits > 1 && !ws) return hipErrorInvalidValue;
   p.ws = c.splits > 1 ? ws : nullptr;
   switch (c.shape) {
-    case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s, mid);
-    case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s, mid);
-    case S64x64: return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s, mid);
-    default: return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s, mid);
+    case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s, ev);
+    case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s, ev);
+    case S64x64: return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s, ev);
+    default: return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s, ev);
   }
 }
 
@@ -809,11 +805,11 @@ size_t conv_workspace_bytes(const OpLaunch& L) {
   return c.splits > 1 ? (size_t)c.splits * p.M * p.C_out * sizeof(float) : 0;
 }
 
-hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, hipEvent_t mid) {
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   ConvParams p = make_params(L);
   if (p.M <= 0) return hipSuccess;
-  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, L.dtype, (float*)L.ws, stream, mid)
-                             : launch_typed<float>(p, L.dtype, (float*)L.ws, stream, mid);
+  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, L.dtype, (float*)L.ws, stream, ev)
+                             : launch_typed<float>(p, L.dtype, (float*)L.ws, stream, ev);
 }
 
 // Name of the kernel instance as a profiler prints it, and the number of K slices.

@@ -43,9 +43,17 @@ inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvC
 // Bytes of split-K scratch the dense conv launch needs (0: none).
 size_t conv_workspace_bytes(const OpLaunch& L);
 
-// Enqueue the kernel(s) for one operator on `stream`. A dense conv whose reduction axis is
-// cut into slices is two kernels; `mid` (optional) is recorded between them.
-hipError_t launch_op(const OpLaunch& L, hipStream_t stream, hipEvent_t mid = nullptr);
+// Events that time the kernels of one operator: pair 0 the operator's kernel, pair 1 the
+// finish kernel of a dense conv whose reduction axis is cut into slices. `n` counts the
+// pairs a launch has used.
+struct KernelEvents {
+  static constexpr int kMax = 2;
+  hipEvent_t start[kMax] = {nullptr, nullptr}, stop[kMax] = {nullptr, nullptr};
+  int n = 0;
+};
+
+// Enqueue the kernel(s) for one operator on `stream`; `ev` (optional) times them.
+hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev = nullptr);
 // Name of the kernel instance launch_op would pick, as a profiler prints it (without the
 // namespace and argument list), written to name[size]. Returns the number of K slices
 // (1: a single kernel; > 1: followed by splitk_finish_kernel).

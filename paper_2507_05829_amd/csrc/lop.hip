@@ -14,22 +14,22 @@
 #include "plan_tables.hpp"
 
 namespace lop {
-hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, hipEvent_t mid);
-hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream);
+hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
+hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
 hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
                             hipStream_t stream);
 
-hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream);
+hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
 bool pointwise_applies(const OpLaunch& L);
 int pointwise_describe(const OpLaunch& L, char* name, size_t size);
 int conv_igemm_describe(const OpLaunch& L, char* name, size_t size);
 int rowwise_describe(const OpLaunch& L, char* name, size_t size);
 
-hipError_t launch_op(const OpLaunch& L, hipStream_t stream, hipEvent_t mid) {
+hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   if (L.out_hi <= L.out_lo) return hipSuccess;
   if (L.op == LOP_CONV2D)
-    return pointwise_applies(L) ? launch_pointwise(L, stream) : launch_conv_igemm(L, stream, mid);
-  return launch_rowwise_op(L, stream);
+    return pointwise_applies(L) ? launch_pointwise(L, stream, ev) : launch_conv_igemm(L, stream, ev);
+  return launch_rowwise_op(L, stream, ev);
 }
 
 int describe_op(const OpLaunch& L, char* name, size_t size) {
@@ -748,8 +748,10 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
   int rc = lop_synchronize(P);
   if (rc != LOP_OK) return rc;
   hipStream_t cs = P->s_main;
-  std::vector<hipEvent_t> ev((size_t)nb * nl * 3, nullptr);
-  std::vector<int> slices((size_t)nb * nl, 0);
+  // (start, stop) of the operator's kernel and of its finish kernel, attached to the
+  // dispatches themselves
+  std::vector<hipEvent_t> ev((size_t)nb * nl * 4, nullptr);
+  std::vector<int> used((size_t)nb * nl, 0);
   auto run = [&]() -> int {
     for (auto& e : ev) LOP_HIP(hipEventCreate(&e));
     for (int i = 0; i < nb * nl; ++i) {
@@ -762,25 +764,20 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
           const lop_rows_t r = P->t.bands[b].compute[l];
           if (r.hi <= r.lo) continue;
           const lop::OpLaunch o = make_launch(P, b, l, d_in, d_out);
-          const size_t i = ((size_t)b * nl + l) * 3;
-          slices[b * nl + l] = lop::describe_op(o, nullptr, 0);
-          LOP_HIP(hipEventRecord(ev[i], cs));
-          LOP_HIP(lop::launch_op(o, cs, ev[i + 1]));
-          LOP_HIP(hipEventRecord(ev[i + 2], cs));
+          const size_t i = ((size_t)b * nl + l) * 4;
+          lop::KernelEvents ke;
+          ke.start[0] = ev[i]; ke.stop[0] = ev[i + 1];
+          ke.start[1] = ev[i + 2]; ke.stop[1] = ev[i + 3];
+          LOP_HIP(lop::launch_op(o, cs, &ke));
+          used[b * nl + l] = ke.n;
         }
       LOP_HIP(hipStreamSynchronize(cs));
       for (int b = 0; b < nb; ++b)
         for (int l = 0; l < nl; ++l) {
-          const lop_rows_t r = P->t.bands[b].compute[l];
-          if (r.hi <= r.lo) continue;
-          const size_t i = ((size_t)b * nl + l) * 3;
+          const size_t i = ((size_t)b * nl + l) * 4;
           float ms = 0.f, fin = 0.f;
-          if (slices[b * nl + l] > 1) {
-            LOP_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
-            LOP_HIP(hipEventElapsedTime(&fin, ev[i + 1], ev[i + 2]));
-          } else {
-            LOP_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 2]));
-          }
+          if (used[b * nl + l] >= 1) LOP_HIP(hipEventElapsedTime(&ms, ev[i], ev[i + 1]));
+          if (used[b * nl + l] >= 2) LOP_HIP(hipEventElapsedTime(&fin, ev[i + 2], ev[i + 3]));
           layer_ms[b * nl + l] += ms / iters;
           if (finish_ms) finish_ms[b * nl + l] += fin / iters;
         }

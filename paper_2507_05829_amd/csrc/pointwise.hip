@@ -15,6 +15,7 @@
 
 #include "act.hpp"
 #include "kernels.hpp"
+#include "launch.hpp"
 #include "lop.h"
 
 namespace lop {
@@ -231,16 +232,13 @@ __global__ __launch_bounds__(256) void pointwise_kernel(const PwParams p) {
 }
 
 template <int NT, int KS>
-hipError_t launch_pw(PwParams& p, hipStream_t s) {
+hipError_t launch_pw(PwParams& p, hipStream_t s, KernelEvents* ev) {
   constexpr int GPW = KS >= 8 ? 1 : 2;  // must match the kernel
   const int waves = (p.groups + GPW - 1) / GPW;
   const int grid = std::max(1, (waves + 3) / 4);
   p.iters = GPW;
-  if (p.res)
-    hipLaunchKernelGGL((pointwise_kernel<NT, KS, true>), dim3(grid), dim3(256), 0, s, p);
-  else
-    hipLaunchKernelGGL((pointwise_kernel<NT, KS, false>), dim3(grid), dim3(256), 0, s, p);
-  return hipGetLastError();
+  return p.res ? launch_kernel(pointwise_kernel<NT, KS, true>, dim3(grid), dim3(256), s, ev, p)
+               : launch_kernel(pointwise_kernel<NT, KS, false>, dim3(grid), dim3(256), s, ev, p);
 }
 
 struct PwShape { int nt, ks; };
@@ -273,7 +271,7 @@ int pointwise_describe(const OpLaunch& L, char* name, size_t size) {
   return 1;
 }
 
-hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream) {
+hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   int nt = 0, ks = 0;
   if (!pw_find(L, &nt, &ks)) return hipErrorInvalidValue;
   PwParams p;
@@ -288,7 +286,7 @@ hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream) {
   if (p.M <= 0) return hipSuccess;
   p.groups = (p.M + 31) / 32;
   p.iters = 0;
-#define LOP_PW_CASE(NT, KS) if (nt == NT && ks == KS) return launch_pw<NT, KS>(p, stream)
+#define LOP_PW_CASE(NT, KS) if (nt == NT && ks == KS) return launch_pw<NT, KS>(p, stream, ev)
   LOP_PW_CASE(6, 2); LOP_PW_CASE(1, 12); LOP_PW_CASE(1, 2); LOP_PW_CASE(2, 2); LOP_PW_CASE(4, 2);
   LOP_PW_CASE(1, 4); LOP_PW_CASE(2, 4); LOP_PW_CASE(4, 4); LOP_PW_CASE(1, 8); LOP_PW_CASE(2, 8);
 #undef LOP_PW_CASE

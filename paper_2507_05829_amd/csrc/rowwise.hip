@@ -11,6 +11,7 @@
 
 #include "act.hpp"
 #include "kernels.hpp"
+#include "launch.hpp"
 #include "lop.h"
 
 namespace lop {
@@ -269,7 +270,7 @@ inline bool dw3_applies(const RowParams& p, int op, int vec) {
 }
 
 template <typename T, int VEC>
-hipError_t launch_dw3(const RowParams& p, hipStream_t s) {
+hipError_t launch_dw3(const RowParams& p, hipStream_t s, KernelEvents* ev) {
   if (p.R <= 0) return hipSuccess;
   Dw3Params q;
   q.r = p;
@@ -277,11 +278,8 @@ hipError_t launch_dw3(const RowParams& p, hipStream_t s) {
   q.cols_per_block = std::max(1, 256 / cv);
   q.chunks = (p.R + kDwRowsPerThread - 1) / kDwRowsPerThread;
   dim3 grid((p.W_out + q.cols_per_block - 1) / q.cols_per_block, q.chunks * p.N);
-  if (p.sh == 1)
-    hipLaunchKernelGGL((dwconv3x3_kernel<T, VEC, 1>), grid, dim3(256), 0, s, q);
-  else
-    hipLaunchKernelGGL((dwconv3x3_kernel<T, VEC, 2>), grid, dim3(256), 0, s, q);
-  return hipGetLastError();
+  return p.sh == 1 ? launch_kernel(dwconv3x3_kernel<T, VEC, 1>, grid, dim3(256), s, ev, q)
+                   : launch_kernel(dwconv3x3_kernel<T, VEC, 2>, grid, dim3(256), s, ev, q);
 }
 
 // Channel vector per thread of the sliding-window kernel (0: it does not apply).
@@ -293,22 +291,20 @@ inline int dw3_vec(const RowParams& p, int op, int dtype) {
 }
 
 template <typename T, int VEC>
-hipError_t launch_rowwise(RowParams& p, int op, hipStream_t s) {
+hipError_t launch_rowwise(RowParams& p, int op, hipStream_t s, KernelEvents* ev) {
   p.total = (long)p.N * p.R * p.W_out * (p.C / VEC);
   if (p.total <= 0) return hipSuccess;
   const unsigned grid = (unsigned)((p.total + 255) / 256);
   if (op == LOP_DWCONV2D)
-    hipLaunchKernelGGL((rowwise_kernel<T, VEC, 0>), dim3(grid), dim3(256), 0, s, p);
-  else if (op == LOP_MAXPOOL2D)
-    hipLaunchKernelGGL((rowwise_kernel<T, VEC, 1>), dim3(grid), dim3(256), 0, s, p);
-  else
-    hipLaunchKernelGGL((rowwise_kernel<T, VEC, 2>), dim3(grid), dim3(256), 0, s, p);
-  return hipGetLastError();
+    return launch_kernel(rowwise_kernel<T, VEC, 0>, dim3(grid), dim3(256), s, ev, p);
+  if (op == LOP_MAXPOOL2D)
+    return launch_kernel(rowwise_kernel<T, VEC, 1>, dim3(grid), dim3(256), s, ev, p);
+  return launch_kernel(rowwise_kernel<T, VEC, 2>, dim3(grid), dim3(256), s, ev, p);
 }
 
 }  // namespace
 
-hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream) {
+hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   RowParams p;
   p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = (const float*)L.w; p.bias = L.bias;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.W = L.x.w; p.C = L.x.c;
@@ -318,14 +314,14 @@ hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream) {
   p.dh = L.dh; p.dw = L.dw;
   p.act = L.act; p.out_lo = L.out_lo; p.R = L.out_hi - L.out_lo; p.N = L.x.n;
   if (const int v = dw3_vec(p, L.op, L.dtype)) {
-    if (L.dtype != LOP_BF16) return launch_dw3<float, 4>(p, stream);
-    return v == 8 ? launch_dw3<__bf16, 8>(p, stream) : launch_dw3<__bf16, 4>(p, stream);
+    if (L.dtype != LOP_BF16) return launch_dw3<float, 4>(p, stream, ev);
+    return v == 8 ? launch_dw3<__bf16, 8>(p, stream, ev) : launch_dw3<__bf16, 4>(p, stream, ev);
   }
   if (L.dtype == LOP_BF16)
-    return p.C % 8 == 0 ? launch_rowwise<__bf16, 8>(p, L.op, stream)
-                        : launch_rowwise<__bf16, 1>(p, L.op, stream);
-  return p.C % 4 == 0 ? launch_rowwise<float, 4>(p, L.op, stream)
-                      : launch_rowwise<float, 1>(p, L.op, stream);
+    return p.C % 8 == 0 ? launch_rowwise<__bf16, 8>(p, L.op, stream, ev)
+                        : launch_rowwise<__bf16, 1>(p, L.op, stream, ev);
+  return p.C % 4 == 0 ? launch_rowwise<float, 4>(p, L.op, stream, ev)
+                      : launch_rowwise<float, 1>(p, L.op, stream, ev);
 }
 
 namespace {

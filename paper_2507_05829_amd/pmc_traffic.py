@@ -17,6 +17,7 @@ import csv
 import hashlib
 import json
 import os
+import re
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -50,8 +51,38 @@ def _factor(vals) -> float:
     return max(cal) / (CALIB_BYTES / 1024.0)
 
 
+_MANGLED = re.compile(r"^_ZN3lop12_GLOBAL__N_1(\d+)")
+
+
+def demangle(name: str) -> str:
+    """The profiler leaves kernel names with a __bf16 template argument mangled; spell out the
+    few forms this library's kernels use (type and integer/bool template arguments)."""
+    m = _MANGLED.match(name)
+    if not m:
+        return name
+    start = m.end()
+    ident = name[start:start + int(m.group(1))]
+    rest = name[start + int(m.group(1)):]
+    args = []
+    if rest.startswith("I"):
+        rest = rest[1:]
+        while rest and not rest.startswith("E"):
+            if rest.startswith("DF16b"):
+                args.append("__bf16"); rest = rest[5:]
+            elif rest.startswith("f"):
+                args.append("float"); rest = rest[1:]
+            elif rest.startswith("Li"):
+                end = rest.index("E")
+                args.append(rest[2:end]); rest = rest[end + 1:]
+            elif rest.startswith("Lb"):
+                args.append("true" if rest[2] == "1" else "false"); rest = rest[4:]
+            else:
+                return name
+    return "lop::(anonymous namespace)::" + ident + ("<" + ", ".join(args) + ">" if args else "")
+
+
 def short(name: str) -> str:
-    n = name.replace("lop::(anonymous namespace)::", "").replace("void ", "")
+    n = demangle(name).replace("lop::(anonymous namespace)::", "").replace("void ", "")
     return n[:n.index("(")] if "(" in n else n
 
 
@@ -67,7 +98,7 @@ def main():
     ff, fw = _factor(fetch), _factor(write)
     kernels = {}
     for name in sorted(set(fetch) | set(write)):
-        if "lop::" not in name:
+        if "lop::" not in demangle(name):
             continue
         f, w = fetch.get(name, []), write.get(name, [])
         kernels[short(name)] = dict(
