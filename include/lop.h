@@ -97,6 +97,11 @@ typedef struct {
                                  lanes. lop_run_band must be called for bands 0,1,2,... in
                                  order.                                                   */
 #define LOP_DEFAULT_LANES 4
+#define LOP_FLAG_NO_FUSE 32u  /* run every layer as a launch of its own. By default a 1x1 conv,
+                                 a 3x3 depthwise conv and a 1x1 conv in a row whose middle
+                                 tensors nobody else reads (an inverted-residual block) run as
+                                 one launch that keeps the expanded tensor on chip; results
+                                 agree with the layer-by-layer path to fp32 summation order */
 #define LOP_FLAG_LANES(n) (((unsigned)(n) & 0xffu) << 8) /* bands are dealt round robin to n
                                  compute streams ("lanes", each with its own scratch) that run
                                  concurrently; 0 = LOP_DEFAULT_LANES, capped at the number of

@@ -12,7 +12,7 @@ struct Clamp {
   float lo, hi;
 };
 
-__device__ __forceinline__ Clamp make_clamp(int act) {
+__host__ __device__ __forceinline__ Clamp make_clamp(int act) {
   Clamp c;
   c.lo = act == LOP_ACT_NONE ? -INFINITY : 0.f;
   c.hi = act == LOP_ACT_RELU6 ? 6.f : INFINITY;

@@ -20,6 +20,10 @@ hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len
                             hipStream_t stream);
 
 hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
+bool mbconv_applies(const OpLaunch& e, const OpLaunch& d, const OpLaunch& p);
+int mbconv_describe(const OpLaunch& d, const OpLaunch& p, char* name, size_t size);
+hipError_t launch_mbconv(const OpLaunch& e, const OpLaunch& d, const OpLaunch& p, hipStream_t stream,
+                         KernelEvents* ev);
 bool pointwise_applies(const OpLaunch& L);
 int pointwise_describe(const OpLaunch& L, char* name, size_t size);
 int conv_igemm_describe(const OpLaunch& L, char* name, size_t size);
@@ -72,6 +76,11 @@ struct lop_plan_s {
   int device = -1;
   std::vector<void*> d_w;      // per layer packed weights (device) or nullptr
   std::vector<void*> d_wd;     // dense conv weights in MFMA operand order, or nullptr
+  // Layers that run as one launch: fuse_head[t] = first layer of the group whose last layer is
+  // t (else -1); fused_away[l] = 1 for the layers of a group before its last (no launch, no
+  // buffer of their own).
+  std::vector<int> fuse_head;
+  std::vector<char> fused_away;
   std::vector<float*> d_bias;  // per layer bias (device) or nullptr
   std::vector<int> k_pad;
   size_t conv_ws_bytes = 0;
@@ -191,6 +200,7 @@ void size_scratch(lop_plan_t* P) {
     size_t off = 0;
     for (int l = 0; l + 1 < nl; ++l) {
       for (int b = 0; b < t.n_bands; ++b) P->slab_off[b][l] = off;
+      if (P->fused_away[l]) continue;
       off += align_up((size_t)t.in.n * t.layers[l].h_out * t.row_elems(l) * t.esz(), 256);
     }
     worst = off;
@@ -200,7 +210,7 @@ void size_scratch(lop_plan_t* P) {
       for (int l = 0; l + 1 < nl; ++l) {  // the last layer writes the caller's output
         const lop_rows_t r = t.bands[b].need[l + 1];
         P->slab_off[b][l] = off;
-        if (r.hi > r.lo)
+        if (r.hi > r.lo && !P->fused_away[l])
           off += align_up((size_t)t.in.n * (r.hi - r.lo) * t.row_elems(l) * t.esz(), 256);
       }
       worst = off > worst ? off : worst;
@@ -258,14 +268,113 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
   return o;
 }
 
+// Operator parameters of layer l without any slab (x.c and y.c are set; res.ptr is a non-null
+// marker when the layer adds a residual): what the kernel selection looks at.
+lop::OpLaunch describe_layer(const lop_plan_t* P, int l) {
+  const lop::LayerInfo& L = P->t.layers[l];
+  lop::OpLaunch o;
+  o.op = L.d.op;
+  o.dtype = P->t.in.dtype;
+  o.x.c = L.d.c_in; o.y.c = L.d.c_out;
+  o.x.n = o.y.n = P->t.in.n;
+  if (L.d.residual_from != LOP_NO_RESIDUAL) o.res.ptr = const_cast<lop_plan_t*>(P);
+  if (!P->d_w.empty()) {  // uploaded (not a plan-only plan)
+    o.w = P->d_w[l]; o.wd = P->d_wd[l]; o.bias = P->d_bias[l];
+    o.k_pad = P->k_pad[l];
+  }
+  o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
+  o.ph = L.d.ph; o.pw = L.d.pw; o.dh = L.d.dh; o.dw = L.d.dw;
+  o.act = L.d.act;
+  return o;
+}
+
+// Groups of three layers that run as one launch (an inverted-residual block): layer h a 1x1
+// conv, h + 1 a depthwise conv reading only h, h + 2 a 1x1 conv reading only h + 1, and
+// nobody else reads h or h + 1.
+void find_fused_groups(lop_plan_t* P) {
+  const lop::Tables& t = P->t;
+  const int nl = t.n_layers();
+  P->fuse_head.assign(nl, -1);
+  P->fused_away.assign(nl, 0);
+  if (P->flags & (LOP_FLAG_NO_FUSE | LOP_FLAG_PLAN_ONLY)) return;
+  for (int h = 0; h + 2 < nl; ++h) {
+    if (P->fused_away[h] || P->fuse_head[h] >= 0) continue;
+    const int m = h + 1, q = h + 2;
+    if (t.layers[m].d.input_from != h || t.layers[q].d.input_from != m) continue;
+    bool shared = false;
+    for (int j = 0; j < nl; ++j) {
+      const lop_layer_t& d = t.layers[j].d;
+      if (j != m && d.input_from == h) shared = true;
+      if (j != q && d.input_from == m) shared = true;
+      if (d.residual_from == h || d.residual_from == m) shared = true;
+    }
+    if (shared) continue;
+    if (!lop::mbconv_applies(describe_layer(P, h), describe_layer(P, m), describe_layer(P, q))) continue;
+    P->fuse_head[q] = h;
+    P->fused_away[h] = P->fused_away[m] = 1;
+    h = q;
+  }
+}
+
+// Rows of layer l one launch of band `band` produces (none for a layer that is part of a
+// later layer's launch).
+lop_rows_t launch_rows(const lop_plan_t* P, int band, int l) {
+  if (P->fused_away[l]) return lop_rows_t{0, 0};
+  return P->t.bands[band].compute[l];
+}
+
+// Enqueue what produces layer l's rows of one band: its own kernel(s), or the fused launch
+// of the group it ends.
+hipError_t launch_layer(const lop_plan_t* P, int band, int l, const void* d_in, void* d_out,
+                        hipStream_t cs, lop::KernelEvents* ev = nullptr) {
+  const lop_rows_t r = launch_rows(P, band, l);
+  if (r.hi <= r.lo) return hipSuccess;
+  if (P->fuse_head[l] < 0) return lop::launch_op(make_launch(P, band, l, d_in, d_out), cs, ev);
+  const int h = P->fuse_head[l];
+  lop::OpLaunch e = describe_layer(P, h), d = describe_layer(P, h + 1);
+  const lop::OpLaunch p = make_launch(P, band, l, d_in, d_out);
+  e.x = slab_of(P, band, P->t.layers[h].d.input_from, d_in, d_out);
+  return lop::launch_mbconv(e, d, p, cs, ev);
+}
+
+// Kernel name (and reduction slices) of that launch.
+int describe_layer_launch(const lop_plan_t* P, int band, int l, char* name, size_t size) {
+  const lop_rows_t r = launch_rows(P, band, l);
+  if (r.hi <= r.lo) return 0;
+  if (P->fuse_head[l] < 0) return lop::describe_op(make_launch(P, band, l, nullptr, nullptr), name, size);
+  return lop::mbconv_describe(describe_layer(P, l - 1), describe_layer(P, l), name, size);
+}
+
+// Algorithmic work of that launch. A fused group: the three layers' operations on the rows
+// it computes (the expand layer on the input rows the depthwise windows touch), and the
+// bytes of the group's input rows, output rows, residual and weights only.
+void launch_work(const lop_plan_t* P, int band, int l, double* flop, double* bytes) {
+  const lop::Tables& t = P->t;
+  const lop_rows_t r = launch_rows(P, band, l);
+  *flop = 0.0;
+  *bytes = 0.0;
+  if (r.hi <= r.lo) return;
+  if (P->fuse_head[l] < 0) {
+    *flop = t.layer_flop(l, r.hi - r.lo);
+    *bytes = t.layer_bytes(band, l);
+    return;
+  }
+  const int h = P->fuse_head[l], m = h + 1;
+  const lop::LayerInfo &E = t.layers[h], &D = t.layers[m], &Q = t.layers[l];
+  const int in_lo = std::max(r.lo * D.d.sh - D.d.ph, 0);
+  const int in_hi = std::min((r.hi - 1) * D.d.sh - D.d.ph + D.d.kh, D.h_in);
+  const int rows_e = std::max(in_hi - in_lo, 0);
+  *flop = t.layer_flop(l, r.hi - r.lo) + t.layer_flop(m, r.hi - r.lo) + t.layer_flop(h, rows_e);
+  const double e = (double)t.esz();
+  double b = e * Q.n * ((double)rows_e * E.w_in * E.d.c_in + (double)(r.hi - r.lo) * Q.w_out * Q.d.c_out);
+  if (Q.d.residual_from != LOP_NO_RESIDUAL) b += e * Q.n * (double)(r.hi - r.lo) * Q.w_out * Q.d.c_out;
+  b += e * ((double)E.d.c_out * E.d.c_in + 9.0 * D.d.c_out + (double)Q.d.c_out * Q.d.c_in);
+  *bytes = b;
+}
+
 int enqueue_band_kernels(lop_plan_t* P, int band, const void* d_in, void* d_out, hipStream_t cs) {
   const int nl = P->t.n_layers();
-  for (int l = 0; l < nl; ++l) {
-    const lop_rows_t r = P->t.bands[band].compute[l];
-    if (r.hi <= r.lo) continue;
-    const lop::OpLaunch o = make_launch(P, band, l, d_in, d_out);
-    LOP_HIP(lop::launch_op(o, cs));
-  }
+  for (int l = 0; l < nl; ++l) LOP_HIP(launch_layer(P, band, l, d_in, d_out, cs));
   return LOP_OK;
 }
 
@@ -507,6 +616,7 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
   int rc = lop::build_tables(layers, n_layers, in, n_bands, (flags & LOP_FLAG_REUSE) != 0, P->t);
   if (rc != LOP_OK) { delete P; return rc; }
   P->flags = flags;
+  find_fused_groups(P);
   size_scratch(P);
   if (!(flags & LOP_FLAG_PLAN_ONLY)) {
     rc = setup_device(P);
@@ -597,8 +707,14 @@ int lop_plan_stats(const lop_plan_t* P, double* useful, double* executed, size_t
   for (int l = 0; l < P->t.n_layers(); ++l) {
     u += P->t.layer_flop(l, P->t.layers[l].h_out);
     for (int b = 0; b < P->t.n_bands; ++b) {
-      const lop_rows_t r = P->t.bands[b].compute[l];
-      if (r.hi > r.lo) e += P->t.layer_flop(l, r.hi - r.lo);
+      double f = 0.0, by = 0.0;
+      if (P->fuse_head.empty()) {  // plan-only: no kernels are chosen
+        const lop_rows_t r = P->t.bands[b].compute[l];
+        if (r.hi > r.lo) f = P->t.layer_flop(l, r.hi - r.lo);
+      } else {
+        launch_work(P, b, l, &f, &by);
+      }
+      e += f;
     }
   }
   if (useful) *useful = u;
@@ -611,9 +727,16 @@ int lop_plan_layer_work(const lop_plan_t* P, int band, int layer, double* flop, 
   if (!P) return LOP_ERR_INVALID_ARG;
   if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
     return LOP_ERR_BAND_RANGE;
-  const lop_rows_t r = P->t.bands[band].compute[layer];
-  if (flop) *flop = r.hi > r.lo ? P->t.layer_flop(layer, r.hi - r.lo) : 0.0;
-  if (bytes) *bytes = P->t.layer_bytes(band, layer);
+  double f = 0.0, by = 0.0;
+  if (P->fuse_head.empty()) {  // plan-only: no kernels are chosen
+    const lop_rows_t r = P->t.bands[band].compute[layer];
+    f = r.hi > r.lo ? P->t.layer_flop(layer, r.hi - r.lo) : 0.0;
+    by = P->t.layer_bytes(band, layer);
+  } else {
+    launch_work(P, band, layer, &f, &by);
+  }
+  if (flop) *flop = f;
+  if (bytes) *bytes = by;
   return LOP_OK;
 }
 
@@ -710,15 +833,14 @@ int lop_time_layer(lop_plan_t* P, int band, int layer, const void* d_in, void* d
     return LOP_ERR_BAND_RANGE;
   if (!P->ready) return LOP_ERR_NOT_READY;
   *ms_per_launch = 0.f;
-  const lop_rows_t r = P->t.bands[band].compute[layer];
+  const lop_rows_t r = launch_rows(P, band, layer);
   if (r.hi <= r.lo) return LOP_OK;
   int rc = ensure_timing_events(P);
   if (rc != LOP_OK) return rc;
-  const lop::OpLaunch o = make_launch(P, band, layer, d_in, d_out);
   hipStream_t cs = P->s_main;
-  LOP_HIP(lop::launch_op(o, cs));  // warm-up
+  LOP_HIP(launch_layer(P, band, layer, d_in, d_out, cs));  // warm-up
   LOP_HIP(hipEventRecord(P->ev_c0[0], cs));
-  for (int i = 0; i < iters; ++i) LOP_HIP(lop::launch_op(o, cs));
+  for (int i = 0; i < iters; ++i) LOP_HIP(launch_layer(P, band, layer, d_in, d_out, cs));
   LOP_HIP(hipEventRecord(P->ev_c1[0], cs));
   LOP_HIP(hipStreamSynchronize(cs));
   float ms = 0.f;
@@ -732,10 +854,9 @@ int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, 
   if (!P || !name || size == 0) return LOP_ERR_INVALID_ARG;
   if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
     return LOP_ERR_BAND_RANGE;
-  const lop_rows_t r = P->t.bands[band].compute[layer];
   name[0] = 0;
   int slices = 0;
-  if (r.hi > r.lo) slices = lop::describe_op(make_launch(P, band, layer, nullptr, nullptr), name, size);
+  if (!P->fuse_head.empty()) slices = describe_layer_launch(P, band, layer, name, size);
   if (k_slices) *k_slices = slices;
   return LOP_OK;
 }
@@ -761,14 +882,13 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
     for (int it = 0; it < iters; ++it) {
       for (int b = 0; b < nb; ++b)
         for (int l = 0; l < nl; ++l) {
-          const lop_rows_t r = P->t.bands[b].compute[l];
+          const lop_rows_t r = launch_rows(P, b, l);
           if (r.hi <= r.lo) continue;
-          const lop::OpLaunch o = make_launch(P, b, l, d_in, d_out);
           const size_t i = ((size_t)b * nl + l) * 4;
           lop::KernelEvents ke;
           ke.start[0] = ev[i]; ke.stop[0] = ev[i + 1];
           ke.start[1] = ev[i + 2]; ke.stop[1] = ev[i + 3];
-          LOP_HIP(lop::launch_op(o, cs, &ke));
+          LOP_HIP(launch_layer(P, b, l, d_in, d_out, cs, &ke));
           used[b * nl + l] = ke.n;
         }
       LOP_HIP(hipStreamSynchronize(cs));

@@ -166,6 +166,63 @@ def test_scaled_chains(oracle, name, kw):
     assert rel_err(dev, one) <= TOL[chain.dtype]
     serial, _ = run_gpu(chain, t, use_host=False, flags=lop.LOP_FLAG_LANES(1))
     np.testing.assert_array_equal(dev, serial)      # lanes change scheduling, not values
+    # every layer as a launch of its own (for chains without fusable groups: the same path)
+    unfused, _ = run_gpu(chain, t, use_host=False, flags=lop.LOP_FLAG_NO_FUSE)
+    assert rel_err(unfused, want) <= TOL[chain.dtype]
+
+
+def _mbconv_block(stride, residual, c_mid=192, shape=(2, 21, 19), n_bands=3, acts=("relu6", "relu6", "none")):
+    n, h, w = shape
+    c = workloads.Chain("block", (n, 32, h, w), "bf16", n_bands)
+    c.add(workloads.ELTWISE, 32, 32, act="none", has_bias=False)          # the block's input
+    c.add(workloads.CONV, 32, c_mid, 1, 1, 0, 1, acts[0])
+    c.add(workloads.DWCONV, c_mid, c_mid, 3, stride, 1, 1, acts[1])
+    c.add(workloads.CONV, c_mid, 32, 1, 1, 0, 1, acts[2],
+          residual_from=(0 if residual else workloads.NO_RESIDUAL))
+    return c
+
+
+@pytest.mark.parametrize("reuse", [0, 1])
+@pytest.mark.parametrize("cfg", [
+    dict(stride=1, residual=True),
+    dict(stride=2, residual=False),
+    dict(stride=1, residual=False, c_mid=64, shape=(1, 9, 40), acts=("relu", "none", "relu6")),
+    dict(stride=2, residual=False, c_mid=96, shape=(1, 30, 7), n_bands=5),
+])
+def test_inverted_residual_block_one_launch(oracle, cfg, reuse):
+    """The fused launch (expand, depthwise, project) against the oracle's layer-by-layer
+    definition, with ragged tiles in both directions, and against the unfused path."""
+    chain = _mbconv_block(**cfg)
+    t = workloads.make_tensors(chain, zero_bias=False, seed=17)
+    want = oracle.run_chain(chain, t)
+    flags = lop.LOP_FLAG_REUSE if reuse else 0
+    plan = lop.Plan(chain, t, flags=flags)
+    names = {plan.layer_kernel(b, 3)[0] for b in range(plan.n_bands)}
+    assert all(nm.startswith("mbconv_kernel") for nm in names), names
+    assert all(plan.layer_kernel(b, l)[0] == "" for b in range(plan.n_bands) for l in (1, 2))
+    plan.destroy()
+    dev, host = run_gpu(chain, t, flags=flags)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL["bf16"]
+    unfused, _ = run_gpu(chain, t, use_host=False, flags=flags | lop.LOP_FLAG_NO_FUSE)
+    assert rel_err(unfused, want) <= TOL["bf16"]
+    # same roundings at the same places: the two paths differ by fp32 summation order only,
+    # which can flip a bf16 rounding here and there but nothing more
+    assert rel_err(dev, unfused) <= 2.0 ** -7
+
+
+def test_inverted_residual_block_small_integers_bit_exact(oracle):
+    chain = _mbconv_block(stride=1, residual=True, c_mid=64, shape=(1, 12, 18), acts=("relu6", "relu6", "none"))
+    t = workloads.small_int_tensors(chain, seed=5)
+    for i, w_ in enumerate(t.weights):
+        if w_ is not None:
+            t.weights[i] = np.sign(w_) * (np.abs(w_) > 1)          # {-1, 0, 1}
+    t.x = (t.x > 2).astype(np.float32)
+    want = oracle.run_chain(chain, t)
+    assert np.abs(want).max() <= 256                               # bf16-exact integers
+    dev, host = run_gpu(chain, t)
+    np.testing.assert_array_equal(dev, want)
+    np.testing.assert_array_equal(host, want)
 
 
 @pytest.mark.parametrize("name", ["resnet18", "vgg16", "detector720p"])
@@ -310,7 +367,9 @@ def test_reuse_mode_scaled_chains(oracle, name, kw, graph):
         assert rel_err(got, want) <= TOL[chain.dtype], rep
         np.testing.assert_array_equal(to_nchw(h_out), got)
     u, e, _ = plan.stats()
-    assert e <= u * (1 + 1e-9)
+    # nothing is computed twice, except the expand rows a fused block launch recomputes at
+    # band borders
+    assert e <= u * (1.25 if name == "mbv2" else 1 + 1e-9)
     plan.destroy()
 
 
