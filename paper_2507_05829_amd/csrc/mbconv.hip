@@ -10,7 +10,12 @@
 //            tile's depthwise windows touch -> bias, activation, one rounding to bf16 -> LDS.
 //            Pixels outside the image are zero there (the depthwise operator pads its input,
 //            i.e. the expanded tensor, not the block's input);
-//   depthwise  fp32 on the vector ALUs out of LDS -> bias, activation, one rounding -> LDS;
+//   depthwise  also on MFMA, as nine products with diagonal weight matrices (one per tap)
+//            whose other operand is the expanded tile shifted by the tap: 31/32 of those
+//            multiplications are by zero, but the matrix pipe has them to spare, reads bf16
+//            directly and accumulates in fp32, while the same arithmetic on the vector ALUs
+//            (unpack, 9 FMAs per value) was the kernel's bottleneck -> bias, activation, one
+//            rounding -> LDS;
 //   project  MFMA: adds the chunk's contribution to the 32 output channels (accumulators stay
 //            in registers over the chunks).
 // The roundings are the ones the layer-by-layer path makes, so results agree with it to fp32
@@ -77,24 +82,21 @@ __device__ __forceinline__ u32x2 pack4(const float* f) {
 
 template <int S>
 struct MbTile {
-  static constexpr int TH = 8, TW = S == 1 ? 16 : 8;     // output pixels of a workgroup
+  static constexpr int TH = 8, TW = 16;                  // output pixels of a workgroup
   static constexpr int EH = (TH - 1) * S + 3, EW = (TW - 1) * S + 3;  // expanded pixels it needs
   static constexpr int EP = EH * EW;
   static constexpr int MT_E = (EP + 31) / 32;            // expand MFMA tiles
   static constexpr int MPW = (MT_E + 3) / 4;             // ... per wavefront
-  static constexpr int OP = TH * TW;
-  static constexpr int MT_O = OP / 32;                   // project MFMA tiles (<= 4)
-  static constexpr int RPT = S == 1 ? 4 : 2;             // depthwise output rows per thread
-  static constexpr int ER = (RPT - 1) * S + 3;           // expanded rows a thread reads
-  static constexpr int EPITCH = 72, DPITCH = 80;         // bytes per pixel in LDS (64 + pad)
+  static constexpr int OP = TH * TW;                     // = 4 MFMA tiles, one per wavefront
+  static constexpr int PITCH = 80;                       // bytes per pixel in LDS (64 + pad)
 };
 
 template <int S, bool RES>
-__global__ __launch_bounds__(256) void mbconv_kernel(const MbParams p) {
+__global__ __launch_bounds__(256, S == 1 ? 4 : 2) void mbconv_kernel(const MbParams p) {
   typedef MbTile<S> G;
   constexpr int TH = G::TH, TW = G::TW, EW = G::EW, EP = G::EP, MT_E = G::MT_E, MPW = G::MPW;
-  constexpr int MT_O = G::MT_O, RPT = G::RPT, ER = G::ER, EPITCH = G::EPITCH, DPITCH = G::DPITCH;
-  static_assert(MT_O <= 4 && TH % RPT == 0 && 8 * TW * (TH / RPT) == 256, "thread mapping");
+  constexpr int EPITCH = G::PITCH, DPITCH = G::PITCH;
+  static_assert(G::OP == 128, "one 32-pixel MFMA tile of the output per wavefront");
   __shared__ __attribute__((aligned(16))) unsigned char E_s[MT_E * 32 * EPITCH];
   __shared__ __attribute__((aligned(16))) unsigned char D_s[G::OP * DPITCH];
   __shared__ __attribute__((aligned(16))) float wd_s[10 * kMbMaxMid];  // 9 taps, then the bias
@@ -148,10 +150,20 @@ __global__ __launch_bounds__(256) void mbconv_kernel(const MbParams p) {
     }
   }
 
-  // depthwise thread mapping: 4 channels x RPT output rows of one output column
-  const int cg = tid & 7;
-  const int dcol = (tid >> 3) % TW;
-  const int drow0 = (tid / (8 * TW)) * RPT;
+  // this lane's output pixel (of the wavefront's 32) and where its window starts in E_s
+  const int o = wave * 32 + px;
+  const int orow = o / TW, ocol = o - orow * TW;
+  const unsigned char* const ewin = E_s + ((orow * S) * EW + ocol * S) * EPITCH + kg * 16;
+  // diagonal weight matrices as MFMA A operands: row (= channel) chl has its one non-zero at
+  // k = chl, i.e. in step chl / 16, lane half (chl % 16) / 8, slot chl % 8 of the 8 bf16
+  const int chl = lane & 31;
+  unsigned amask[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      amask[j][i] = ((chl >> 4) == j && ((chl >> 3) & 1) == kg && ((chl & 7) >> 1) == i) ? 0xffffffffu : 0u;
+  const int wshift = (chl & 1) * 16;
 
   f32x16 acc;
 #pragma unroll
@@ -202,49 +214,39 @@ __global__ __launch_bounds__(256) void mbconv_kernel(const MbParams p) {
     }
     __syncthreads();
 
-    // ---- depthwise 3x3 on the chunk
+    // ---- depthwise 3x3 on the chunk: D[ch][px] = sum over taps of diag(w_tap) x E(px + tap)
     {
-      const float* wc = wd_s + c * 32 + cg * 4;
-      float4 w[9];
+      f32x16 d0, d1;
 #pragma unroll
-      for (int t = 0; t < 9; ++t) w[t] = *(const float4*)(wc + t * p.C_mid);
-      const float4 b4 = *(const float4*)(wc + 9 * p.C_mid);
-      float d[RPT][4];
-#pragma unroll
-      for (int r = 0; r < RPT; ++r) {
-        d[r][0] = b4.x; d[r][1] = b4.y; d[r][2] = b4.z; d[r][3] = b4.w;
+      for (int g = 0; g < 4; ++g) {
+        const float4 b4 = *(const float4*)(wd_s + 9 * p.C_mid + c * 32 + g * 8 + kg * 4);
+        d0[g * 4 + 0] = b4.x; d0[g * 4 + 1] = b4.y; d0[g * 4 + 2] = b4.z; d0[g * 4 + 3] = b4.w;
       }
 #pragma unroll
-      for (int er = 0; er < ER; ++er)
+      for (int k = 0; k < 16; ++k) d1[k] = 0.f;
 #pragma unroll
-        for (int dc = 0; dc < 3; ++dc) {
-          const int e = (drow0 * S + er) * EW + dcol * S + dc;
-          float f[4];
-          unpack4(*(const u32x2*)(E_s + e * EPITCH + cg * 8), f);
+      for (int t = 0; t < 9; ++t) {
+        // the weights are bf16 values held as fp32: the upper 16 bits are the value
+        const unsigned wv = (__builtin_bit_cast(unsigned, wd_s[t * p.C_mid + c * 32 + chl]) >> 16) << wshift;
+        const u32x4 a0 = u32x4{wv & amask[0][0], wv & amask[0][1], wv & amask[0][2], wv & amask[0][3]};
+        const u32x4 a1 = u32x4{wv & amask[1][0], wv & amask[1][1], wv & amask[1][2], wv & amask[1][3]};
+        const unsigned char* src = ewin + ((t / 3) * EW + (t % 3)) * EPITCH;
+        d0 = mma_bf16(a0, *(const u32x4*)src, d0);
+        d1 = mma_bf16(a1, *(const u32x4*)(src + 32), d1);
+      }
 #pragma unroll
-          for (int r = 0; r < RPT; ++r) {
-            const int kr = er - r * S;
-            if (kr < 0 || kr > 2) continue;
-            const float4 wt = w[kr * 3 + dc];
-            d[r][0] += wt.x * f[0];
-            d[r][1] += wt.y * f[1];
-            d[r][2] += wt.z * f[2];
-            d[r][3] += wt.w * f[3];
-          }
-        }
-#pragma unroll
-      for (int r = 0; r < RPT; ++r) {
+      for (int g = 0; g < 4; ++g) {
         float v[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = clamp_act(d[r][k], p.cd);
-        *(u32x2*)(D_s + ((drow0 + r) * TW + dcol) * DPITCH + cg * 8) = pack4(v);
+        for (int k = 0; k < 4; ++k) v[k] = clamp_act(d0[g * 4 + k] + d1[g * 4 + k], p.cd);
+        *(u32x2*)(D_s + o * DPITCH + g * 16 + kg * 8) = pack4(v);
       }
     }
     __syncthreads();
 
     // ---- project: this chunk's 32 channels are the reduction axis
-    if (wave < MT_O) {
-      const unsigned char* src = D_s + (wave * 32 + px) * DPITCH + kg * 16;
+    {
+      const unsigned char* src = D_s + o * DPITCH + kg * 16;
       const u32x4 b0 = *(const u32x4*)src;
       const u32x4 b1 = *(const u32x4*)(src + 32);
       acc = mma_bf16(wpf[0], b0, acc);
@@ -255,9 +257,6 @@ __global__ __launch_bounds__(256) void mbconv_kernel(const MbParams p) {
   }
 
   // ---- bias, residual, activation, the one rounding; 8 bytes per lane and channel group
-  if (wave >= MT_O) return;
-  const int o = wave * 32 + px;
-  const int orow = o / TW, ocol = o - orow * TW;
   const int oh = oh0 + orow, ow = ow0 + ocol;
   if (oh >= p.out_lo + p.R || ow >= p.W_out) return;
   const size_t yoff = ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * kMbC;
@@ -325,7 +324,7 @@ hipError_t launch_mbconv(const OpLaunch& e, const OpLaunch& d, const OpLaunch& p
   q.out_lo = p.out_lo; q.R = p.out_hi - p.out_lo; q.N = e.x.n;
   if (q.R <= 0 || q.N <= 0) return hipSuccess;
   const int s = d.sh;
-  const int tw = s == 1 ? MbTile<1>::TW : MbTile<2>::TW, th = MbTile<1>::TH;
+  const int tw = MbTile<1>::TW, th = MbTile<1>::TH;
   q.tiles_x = (q.W_out + tw - 1) / tw;
   q.tiles_y = (q.R + th - 1) / th;
   const dim3 grid((unsigned)(q.tiles_x * q.tiles_y * q.N));
