@@ -383,6 +383,38 @@ def test_reuse_mode_full_size(oracle, name):
     assert rel_err(dev, want) <= TOL[chain.dtype]
 
 
+@pytest.mark.parametrize("name", ["resnet18", "vgg16", "detector720p", "mbv2"])
+def test_bench_configuration_full_size(oracle, name):
+    """The launch configuration bench.py times (reuse mode, graph replay, default lanes,
+    fused blocks) at the full sizes: five chains in a row so that every lane's graph is
+    replayed, the last one compared with the oracle. mbv2 (batch 8, 640x640): three sampled
+    (image, band) pairs recomputed by the oracle's banded path, the rest checked finite."""
+    chain = workloads.CONFIGS[name]()
+    t = workloads.make_tensors(chain)
+    plan = lop.Plan(chain, t, flags=lop.LOP_FLAG_REUSE | lop.LOP_FLAG_GRAPH)
+    d_in = to_device_nhwc(t.x, chain.dtype)
+    d_out = empty_out(plan.out_shape(), chain.dtype)
+    h_out = empty_out(plan.out_shape(), chain.dtype, pinned=True)
+    for _ in range(5):
+        plan.run_chain(d_in, d_out, h_out)
+    plan.synchronize()
+    dev, host = to_nchw(d_out), to_nchw(h_out)
+    plan.destroy()
+    np.testing.assert_array_equal(dev, host)
+    if name != "mbv2":
+        want = oracle.run_chain(chain, t)
+        assert rel_err(dev, want) <= TOL[chain.dtype]
+        return
+    assert np.isfinite(dev).all()
+    from oracle import planner
+    for img, band in ((1, 0), (4, 5), (6, 7)):
+        one = workloads.mbv2_chain(n=1)
+        t1 = workloads.Tensors(np.ascontiguousarray(t.x[img:img + 1]), t.weights, t.biases)
+        slab = oracle.run_band(one, t1, planner.plan(one)[band])
+        got = dev[img:img + 1, :, slab.row0:slab.row0 + slab.rows]
+        assert rel_err(got, slab.data) <= TOL["bf16"]
+
+
 def test_reuse_mode_small_integers_bit_exact(oracle):
     chain = workloads.Chain("ints", (2, 8, 40, 24), "f32", 5)
     chain.add(workloads.CONV, 8, 8, 3, 1, 1, act="relu")
