@@ -189,3 +189,23 @@ int oracle_eltwise(const float* x, int x_row0, int x_rows, int N, int C, int H, 
       }
   return bad ? ORACLE_ERR_SLAB : ORACLE_OK;
 }
+
+/* Row-wise local operator (Intra-DP Sec. IV-A, Eq. 1): rows [row0, row0 + rows) of
+ * y = act(x * W^T + bias + res) for a matrix x of m rows and k columns (row-major) and a
+ * parameter matrix W of n rows and k columns (one row per output column) that every row of x
+ * meets whole. x, res and y are full matrices; only the named rows of y are written, each from
+ * the same row of x (and of res) alone. Accumulation in double over j = 0..k-1, one rounding. */
+int oracle_rowwise(const float* x, int m, int k, const float* w, int n, const float* bias,
+                   const float* res, int act, int dtype, float* y, int row0, int rows) {
+  if (row0 < 0 || rows < 0 || row0 + rows > m) return ORACLE_ERR_ARG;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int i = row0; i < row0 + rows; ++i)
+    for (int c = 0; c < n; ++c) {
+      double acc = 0.0;
+      for (int j = 0; j < k; ++j) acc += (double)x[(size_t)i * k + j] * (double)w[(size_t)c * k + j];
+      if (bias) acc += (double)bias[c];
+      if (res) acc += (double)res[(size_t)i * n + c];
+      y[(size_t)i * n + c] = store(activate(acc, act), dtype);
+    }
+  return ORACLE_OK;
+}

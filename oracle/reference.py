@@ -180,3 +180,38 @@ def run_chain_reuse(chain, t, n_bands: Optional[int] = None) -> np.ndarray:
                              chain.dtype, lo, hi - lo, h, w)
             bufs[i].data[:, :, lo:hi, :] = part.data
     return bufs[nl - 1].data
+
+
+# ---- row-wise local operators (Sec. IV-A, Eq. 1) ----
+
+def rowwise(x: np.ndarray, w: np.ndarray, b, res, act: str, dtype: str,
+            y: Optional[np.ndarray] = None, row0: int = 0, rows: Optional[int] = None) -> np.ndarray:
+    """Rows [row0, row0 + rows) of act(x W^T + b + res) written into y (m x n); the other rows
+    of y are left as they are."""
+    m, k = x.shape
+    n = w.shape[0]
+    assert w.shape == (n, k)
+    if y is None:
+        y = np.full((m, n), np.nan, np.float32)
+    rows = m - row0 if rows is None else rows
+    rc = lib().oracle_rowwise(_fp(x), m, k, _fp(w), n, _fp(b), _fp(res), ACT[act], DTYPE[dtype],
+                              _fp(y), row0, rows)
+    if rc != 0:
+        raise RuntimeError(f"oracle_rowwise failed with code {rc}")
+    return y
+
+
+def run_row_chain(chain, t, bands=None) -> np.ndarray:
+    """A chain of row-wise operators on the whole matrix (bands=None: the definition), or
+    band after band on the given list of (lo, hi) row intervals: every band runs the whole
+    chain on its own rows before the next band starts."""
+    m = chain.m
+    outs = {-1: t.x}
+    for i, L in enumerate(chain.layers):
+        outs[i] = np.full((m, L.n), np.nan, np.float32)
+    for lo, hi in ([(0, m)] if bands is None else bands):
+        for i, L in enumerate(chain.layers):
+            res = outs[L.residual_from] if L.residual_from != -2 else None
+            rowwise(outs[L.input_from], t.weights[i], t.biases[i], res, L.act, chain.dtype,
+                    outs[i], lo, hi - lo)
+    return outs[len(chain.layers) - 1]

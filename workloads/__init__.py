@@ -247,3 +247,63 @@ def small_int_tensors(chain: Chain, seed: int = 7) -> Tensors:
             ws.append(None)
         bs.append(rng.integers(-4, 5, L.c_out).astype(np.float32) if L.has_bias else None)
     return Tensors(x, ws, bs)
+
+
+# ---- row-wise local operators (matrix chains): shapes only, like the chains above ----
+
+@dataclass
+class RowLayer:
+    k: int                               # columns of the input matrix
+    n: int                               # columns of the output matrix
+    act: str = ACT_NONE
+    input_from: int = CHAIN_INPUT
+    residual_from: int = NO_RESIDUAL
+    has_bias: bool = True
+
+
+@dataclass
+class RowChain:
+    """y_l = act(x_l W_l^T + b_l + residual) on a matrix of m rows, W_l of n x k."""
+    name: str
+    m: int
+    k: int
+    dtype: str
+    n_bands: int
+    layers: List[RowLayer] = field(default_factory=list)
+    seed: int = BASE_SEED + 100
+
+    def add(self, n: int, act: str = ACT_NONE, residual_from: int = NO_RESIDUAL,
+            has_bias: bool = True, input_from: Optional[int] = None) -> "RowChain":
+        src = (len(self.layers) - 1) if input_from is None else input_from
+        k = self.k if src < 0 else self.layers[src].n
+        self.layers.append(RowLayer(k, n, act, src, residual_from, has_bias))
+        return self
+
+
+def mlp_chain(m: int = 65536, k: int = 1024, hidden: int = 4096, dtype: str = "bf16",
+              n_bands: int = 8) -> RowChain:
+    """Two matrix products with a ReLU between and a residual around: the feed-forward block
+    of a transformer-style model as a chain of row-wise local operators."""
+    c = RowChain("mlp", m, k, dtype, n_bands)
+    c.add(hidden, ACT_RELU)
+    c.add(k, ACT_NONE, residual_from=CHAIN_INPUT)
+    return c
+
+
+def make_row_tensors(chain: RowChain, zero_bias: bool = True, seed: Optional[int] = None) -> Tensors:
+    """Input matrix ~ U[-1, 1], then per layer W ~ N(0, sqrt(2/k)) (n x k) and the bias."""
+    rng = np.random.Generator(np.random.PCG64(chain.seed if seed is None else seed))
+    x = rng.random((chain.m, chain.k), dtype=np.float32) * np.float32(2) - np.float32(1)
+    ws, bs = [], []
+    for L in chain.layers:
+        w = rng.standard_normal((L.n, L.k), dtype=np.float32) * np.float32(np.sqrt(2.0 / L.k))
+        b = None
+        if L.has_bias:
+            b = (np.zeros(L.n, np.float32) if zero_bias
+                 else rng.random(L.n, dtype=np.float32) - np.float32(0.5))
+        ws.append(w)
+        bs.append(b)
+    if chain.dtype == "bf16":
+        x = to_bf16_values(x)
+        ws = [to_bf16_values(w) for w in ws]
+    return Tensors(x, ws, bs)
