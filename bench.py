@@ -24,7 +24,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet18")
-    ap.add_argument("--also", default="resnet18:independent,tiny,vgg16,detector720p,mbv2",
+    ap.add_argument("--also", default="resnet18:independent,tiny,vgg16,detector720p,mbv2,mlp",
                     help="comma list of further workload[:mode] entries reported under 'also' "
                          "(fewer steps; mode defaults to --mode)")
     ap.add_argument("--bands", type=int, default=None, help="override the workload's band count")
@@ -47,7 +47,10 @@ def parse():
 
 def device_tensors(torch, chain, tensors, plan, n_buf=2):
     import numpy as np
-    x = torch.from_numpy(np.ascontiguousarray(tensors.x.transpose(0, 2, 3, 1)))
+    if tensors.x.ndim == 2:   # a matrix of a row-wise chain: already row-major m x k
+        x = torch.from_numpy(tensors.x)
+    else:
+        x = torch.from_numpy(np.ascontiguousarray(tensors.x.transpose(0, 2, 3, 1)))
     td = torch.bfloat16 if chain.dtype == "bf16" else torch.float32
     d_in = x.to(td).cuda()
     n, c, h, w = plan.out_shape()
@@ -158,17 +161,19 @@ def measured_traffic(workload, kernel_name):
 
 
 def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iters, lanes=0, graph=1, dma=0, replicas=1, mode="independent"):
-    chain = workloads.CONFIGS[name]()
+    rowwise = name == "mlp"   # chain of row-wise operators (matrix products), Eq. 1
+    chain = workloads.mlp_chain() if rowwise else workloads.CONFIGS[name]()
     if bands:
         chain.n_bands = bands
-    tensors = workloads.make_tensors(chain)
+    tensors = workloads.make_row_tensors(chain) if rowwise else workloads.make_tensors(chain)
     flags = (lop.LOP_FLAG_LANES(lanes) | (lop.LOP_FLAG_GRAPH if graph else 0)
              | (lop.LOP_FLAG_DMA_COPY if dma else 0)
              | (lop.LOP_FLAG_REUSE if mode == "reuse" else 0))
-    plans = [lop.Plan(chain, tensors, flags=flags) for _ in range(max(1, replicas))]
+    make_plan = lop.Plan.rowwise if rowwise else lop.Plan
+    plans = [make_plan(chain, tensors, flags=flags) for _ in range(max(1, replicas))]
     plan = plans[0]
     d_in, d_out, h_out = device_tensors(torch, chain, tensors, plan, n_buf=max(2, len(plans), 8 if mode == "reuse" else 2))
-    n_img = chain.in_shape[0]
+    n_img = 1 if rowwise else chain.in_shape[0]   # a matrix counts as one image
     useful, executed, scratch = plan.stats()
 
     t_c = timed_steps(torch, plans, d_in, d_out, h_out, steps, warmup, copy=True)
@@ -202,6 +207,9 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
         scratch_mb=round(scratch / 2 ** 20, 2),
         kernels=[{k: v for k, v in kk.items() if not k.endswith("_per_launch")} for kk in kernels],
     )
+    if rowwise:
+        res["rows_per_s"] = round(chain.m * steps / t_c, 1)
+        res["matrix"] = f"{chain.m} x {chain.k} -> " + " -> ".join(str(L.n) for L in chain.layers)
     roof = roofline_of(next(k for k in kernels if k["flop_per_launch"] > 0), chain.dtype)
     roof["traffic"] = measured_traffic(f"{name}_{mode}", roof["kernel"])
     roof["algorithmic_bytes_per_launch"] = round(
@@ -217,9 +225,10 @@ def cpu_baseline(chain, tensors, budget_s):
     reference.build()
     times = []
     t_all = time.perf_counter()
+    run = reference.run_row_chain if hasattr(chain, "m") else reference.run_chain
     while True:
         t0 = time.perf_counter()
-        reference.run_chain(chain, tensors)
+        run(chain, tensors)
         times.append(time.perf_counter() - t0)
         if len(times) >= 3 or time.perf_counter() - t_all > budget_s:
             break
@@ -260,7 +269,7 @@ def main():
         mode = mode or a.mode
         if name == a.workload and mode == a.mode:
             continue
-        heavy = name == "mbv2"
+        heavy = name in ("mbv2", "mlp")
         _, _, r, rf = run_workload(torch, lop, workloads, name, 10 if heavy else max(a.steps // 4, 10),
                                    2 if heavy else 5, None, 3 if heavy else a.profile_iters,
                                    a.lanes, a.graph, a.dma_copy, a.replicas, mode)

@@ -170,6 +170,28 @@ LOP_API int lop_run_chain(lop_plan_t* plan, const void* d_in, void* d_out, void*
 /* Wait for everything the plan has enqueued on its own and on the passed streams. */
 LOP_API int lop_synchronize(lop_plan_t* plan);
 
+/* Row-wise local operators (Sec. IV-A, Eq. 1): a chain of matrix products on a matrix of m
+ * rows. A row of a layer's output depends on the same row of its input and on the whole
+ * parameter matrix, which every band uses unpartitioned (replicated): row bands need no halo
+ * and no exchange. Layer l computes y = act(x W^T + bias + residual) with x of m x k and W of
+ * n x k (one row of W per output column, the layout of a fully connected layer's weight). */
+typedef struct {
+  int k, n;            /* columns of the input and of the output matrix                      */
+  int act;             /* lop_act_t                                                          */
+  int input_from;      /* LOP_INPUT or the index of an earlier layer (k must be its n)       */
+  int residual_from;   /* LOP_NO_RESIDUAL, LOP_INPUT or an earlier layer with n columns      */
+  const void* weight;  /* host; n x k row-major in the plan's storage type; copied           */
+  const float* bias;   /* host; n fp32 values or NULL; copied                                */
+} lop_rowwise_t;
+
+/* Plan a chain of row-wise operators on an m x k matrix (row-major, storage type `dtype`),
+ * its rows split into n_bands intervals as in lop_plan. The plan is used with every other
+ * function of this header: d_in is the m x k matrix, d_out / h_out the m x n_last result, a
+ * band's rows are matrix rows; lop_plan_out_desc reports {n = 1, c = n_last, h = m, w = 1}.
+ * The matrix product runs on the kernels of the 1x1 convolution. Errors as lop_plan. */
+LOP_API int lop_plan_rowwise(const lop_rowwise_t* layers, int n_layers, int m, int k, int dtype,
+                             int n_bands, unsigned flags, lop_plan_t** out_plan);
+
 /* Time one layer's kernel of one band in isolation: `iters` launches on the plan's
  * compute stream between two events, on the plan's own scratch (contents are whatever
  * the last run left). Writes the mean milliseconds per launch. Measurement aid. */

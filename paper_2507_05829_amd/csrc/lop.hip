@@ -627,6 +627,30 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
   return LOP_OK;
 }
 
+int lop_plan_rowwise(const lop_rowwise_t* layers, int n_layers, int m, int k, int dtype, int n_bands,
+                     unsigned flags, lop_plan_t** out_plan) {
+  if (!out_plan) return LOP_ERR_INVALID_ARG;
+  *out_plan = nullptr;
+  if (!layers || n_layers < 1 || m < 1 || k < 1) return LOP_ERR_INVALID_ARG;
+  // a matrix row is a pixel of an m x 1 image with k channels; the product is a 1x1 conv
+  std::vector<lop_layer_t> conv((size_t)n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    const lop_rowwise_t& r = layers[l];
+    lop_layer_t& c = conv[l];
+    c.op = LOP_CONV2D;
+    c.c_in = r.k; c.c_out = r.n;
+    c.kh = c.kw = c.sh = c.sw = c.dh = c.dw = 1;
+    c.ph = c.pw = 0;
+    c.act = r.act;
+    c.input_from = r.input_from;
+    c.residual_from = r.residual_from;
+    c.weight = r.weight;
+    c.bias = r.bias;
+  }
+  const lop_tensor_desc_t in{1, k, m, 1, dtype};
+  return lop_plan(conv.data(), n_layers, &in, n_bands, flags, out_plan);
+}
+
 void lop_plan_destroy(lop_plan_t* P) {
   if (!P) return;
   for (Lane& L : P->lanes) {

@@ -46,7 +46,7 @@ EXPORTS = [
     "lop_plan_band_layer_rows", "lop_plan_stats", "lop_plan_layer_work", "lop_run_band",
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
     "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
-    "lop_plan_band_compute_rows",
+    "lop_plan_band_compute_rows", "lop_plan_rowwise",
 ]
 
 
@@ -56,6 +56,11 @@ class lop_layer_t(Structure):
                 ("ph", c_int), ("pw", c_int), ("dh", c_int), ("dw", c_int),
                 ("act", c_int), ("input_from", c_int), ("residual_from", c_int),
                 ("weight", c_void_p), ("bias", c_void_p)]
+
+
+class lop_rowwise_t(Structure):
+    _fields_ = [("k", c_int), ("n", c_int), ("act", c_int), ("input_from", c_int),
+                ("residual_from", c_int), ("weight", c_void_p), ("bias", c_void_p)]
 
 
 class lop_tensor_desc_t(Structure):
@@ -82,6 +87,8 @@ def _load() -> ctypes.CDLL:
     sig = {
         "lop_plan": (c_int, [POINTER(lop_layer_t), c_int, POINTER(lop_tensor_desc_t), c_int, c_uint,
                              POINTER(P)]),
+        "lop_plan_rowwise": (c_int, [POINTER(lop_rowwise_t), c_int, c_int, c_int, c_int, c_int, c_uint,
+                                     POINTER(P)]),
         "lop_plan_out_desc": (c_int, [P, POINTER(lop_tensor_desc_t)]),
         "lop_plan_layer_desc": (c_int, [P, c_int, POINTER(lop_tensor_desc_t)]),
         "lop_plan_n_bands": (c_int, [P]),
@@ -152,6 +159,15 @@ def lop_plan(layers: Sequence[lop_layer_t], in_desc: lop_tensor_desc_t, n_bands:
     arr = (lop_layer_t * len(layers))(*layers) if len(layers) else None
     out = c_void_p(0)
     _check(_lib.lop_plan(arr, len(layers), byref(in_desc), n_bands, flags, byref(out)), "lop_plan")
+    return out
+
+
+def lop_plan_rowwise(layers: Sequence[lop_rowwise_t], m: int, k: int, dtype: int, n_bands: int,
+                     flags: int = 0) -> c_void_p:
+    arr = (lop_rowwise_t * len(layers))(*layers) if len(layers) else None
+    out = c_void_p(0)
+    _check(_lib.lop_plan_rowwise(arr, len(layers), m, k, dtype, n_bands, flags, byref(out)),
+           "lop_plan_rowwise")
     return out
 
 
@@ -320,6 +336,33 @@ class Plan:
         self.n_bands = lop_plan_n_bands(self.handle)
         self.n_layers = lop_plan_n_layers(self.handle)
         self.dtype = chain.dtype
+
+    @classmethod
+    def rowwise(cls, chain, tensors=None, n_bands: Optional[int] = None, flags: int = 0) -> "Plan":
+        """Plan for a chain of row-wise operators (duck-typed: .m, .k, .dtype, .n_bands and
+        .layers with k, n, act, input_from, residual_from) through lop_plan_rowwise."""
+        keep, layers = [], []
+        for i, L in enumerate(chain.layers):
+            d = lop_rowwise_t(L.k, L.n, _ACTS[L.act], L.input_from, L.residual_from, None, None)
+            if tensors is not None:
+                w = _storage(tensors.weights[i], chain.dtype)
+                keep.append(w)
+                d.weight = w.ctypes.data
+                if tensors.biases[i] is not None:
+                    b = np.ascontiguousarray(tensors.biases[i], dtype=np.float32)
+                    keep.append(b)
+                    d.bias = b.ctypes.data
+            layers.append(d)
+        if tensors is None:
+            flags |= LOP_FLAG_PLAN_ONLY
+        self = cls.__new__(cls)
+        self.handle = lop_plan_rowwise(layers, chain.m, chain.k, _DTYPES[chain.dtype],
+                                       chain.n_bands if n_bands is None else n_bands, flags)
+        del keep
+        self.n_bands = lop_plan_n_bands(self.handle)
+        self.n_layers = lop_plan_n_layers(self.handle)
+        self.dtype = chain.dtype
+        return self
 
     def destroy(self) -> None:
         if getattr(self, "handle", None):

@@ -180,3 +180,27 @@ def test_reuse_planner_random_chains():
             for l in range(len(chain.layers)):
                 exp = want[b][l]
                 assert plan.band_compute_rows(b, l) == ((0, 0) if exp is None else exp), (chain, b, l)
+
+
+def test_rowwise_plan_rows_and_errors():
+    """lop_plan_rowwise: bands are numpy.array_split of the matrix rows, no halo anywhere."""
+    chain = workloads.RowChain("c", 1000, 48, "f32", 7)
+    chain.add(96, "relu").add(48, "none", residual_from=-1)
+    plan = lop.Plan.rowwise(chain)
+    assert plan.out_shape() == (1, 48, 1000, 1)
+    want = [(int(a[0]), int(a[-1]) + 1) for a in np.array_split(np.arange(1000), 7)]
+    for b in range(7):
+        assert plan.band_out_rows(b) == want[b]
+        assert plan.band_in_rows(b) == want[b]
+        for l in range(2):
+            assert plan.band_layer_rows(b, l) == want[b]
+    u, e, _ = plan.stats()
+    assert u == e == 2.0 * 1000 * (48 * 96 + 96 * 48)
+    plan.destroy()
+    with pytest.raises(lop.LopError) as ei:
+        lop.lop_plan_rowwise([], 10, 4, 0, 2, lop.LOP_FLAG_PLAN_ONLY)
+    assert ei.value.code == -1
+    bad = lop.lop_rowwise_t(5, 8, 0, -1, -2, None, None)          # k does not match the input
+    with pytest.raises(lop.LopError) as ei:
+        lop.lop_plan_rowwise([bad], 10, 4, 0, 2, lop.LOP_FLAG_PLAN_ONLY)
+    assert ei.value.code in (-1, -3)

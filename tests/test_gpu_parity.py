@@ -447,3 +447,69 @@ def test_reuse_mode_run_band_in_order(oracle):
         assert rel_err(to_nchw(h_out)[:, :, :hi], want[:, :, :hi]) <= TOL["f32"]
         assert np.isnan(to_nchw(h_out)[:, :, hi:]).all()
     plan.destroy()
+
+
+# ---- row-wise local operators (Eq. 1) through lop_plan_rowwise ----
+
+def _run_rows(chain, t, flags=0, order=None):
+    plan = lop.Plan.rowwise(chain, t, flags=flags)
+    td = torch.bfloat16 if chain.dtype == "bf16" else torch.float32
+    d_in = torch.from_numpy(t.x).to(td).cuda()
+    n_out = chain.layers[-1].n
+    d_out = torch.full((chain.m, n_out), float("nan"), dtype=td, device="cuda")
+    h_out = torch.full((chain.m, n_out), float("nan"), dtype=td).pin_memory()
+    torch.cuda.synchronize()
+    if order is None:
+        plan.run_chain(d_in, d_out, h_out)
+    else:
+        for b in order:
+            plan.run_band(b, d_in, d_out, h_out)
+    plan.synchronize()
+    names = {plan.layer_kernel(b, l)[0] for b in range(plan.n_bands) for l in range(plan.n_layers)}
+    plan.destroy()
+    return d_out.float().cpu().numpy(), h_out.float().numpy(), names
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(1000, 48, 96, 7), (257, 256, 1024, 3), (40, 100, 36, 5)])
+def test_rowwise_chain_against_oracle(oracle, shape, dtype):
+    m, k, hidden, bands = shape
+    chain = workloads.RowChain("mlp", m, k, dtype, bands)
+    chain.add(hidden, "relu").add(k, "none", residual_from=-1)
+    t = workloads.make_row_tensors(chain, zero_bias=False, seed=23)
+    want = oracle.run_row_chain(chain, t)
+    dev, host, _ = _run_rows(chain, t)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL[dtype]
+    # bands in reverse order, one lop_run_band each: the same rows, bit for bit
+    again, _, _ = _run_rows(chain, t, order=list(range(bands))[::-1])
+    np.testing.assert_array_equal(again, dev)
+
+
+def test_rowwise_small_integers_bit_exact(oracle):
+    chain = workloads.RowChain("ints", 333, 64, "f32", 4)
+    chain.add(32, "relu").add(16, "none")
+    rng = np.random.Generator(np.random.PCG64(9))
+    t = workloads.Tensors(rng.integers(-3, 4, (333, 64)).astype(np.float32),
+                          [rng.integers(-2, 3, (32, 64)).astype(np.float32),
+                           rng.integers(-2, 3, (16, 32)).astype(np.float32)],
+                          [rng.integers(-4, 5, 32).astype(np.float32), None])
+    chain.layers[1].has_bias = False
+    want = oracle.run_row_chain(chain, t)
+    dev, host, _ = _run_rows(chain, t)
+    np.testing.assert_array_equal(dev, want)
+    np.testing.assert_array_equal(host, want)
+
+
+def test_rowwise_full_size_sampled_rows(oracle):
+    """The bench's matrix chain (65536 x 1024 -> 4096 -> 1024, bf16) in the bench's launch
+    configuration; the oracle recomputes 64 sampled rows (a row needs only itself)."""
+    chain = workloads.mlp_chain()
+    t = workloads.make_row_tensors(chain)
+    dev, host, _ = _run_rows(chain, t, flags=lop.LOP_FLAG_REUSE | lop.LOP_FLAG_GRAPH)
+    np.testing.assert_array_equal(dev, host)
+    assert np.isfinite(dev).all()
+    rows = np.random.Generator(np.random.PCG64(1)).choice(chain.m, 64, replace=False)
+    sub = workloads.RowChain("sub", 64, chain.k, chain.dtype, 1, chain.layers)
+    want = oracle.run_row_chain(sub, workloads.Tensors(np.ascontiguousarray(t.x[rows]), t.weights, t.biases))
+    assert rel_err(dev[rows], want) <= TOL["bf16"]

@@ -272,6 +272,11 @@ class RowChain:
     layers: List[RowLayer] = field(default_factory=list)
     seed: int = BASE_SEED + 100
 
+    @property
+    def in_shape(self) -> Tuple[int, int, int, int]:
+        """The matrix seen as a tensor: one image of m x 1 pixels with k channels."""
+        return (1, self.k, self.m, 1)
+
     def add(self, n: int, act: str = ACT_NONE, residual_from: int = NO_RESIDUAL,
             has_bias: bool = True, input_from: Optional[int] = None) -> "RowChain":
         src = (len(self.layers) - 1) if input_from is None else input_from
