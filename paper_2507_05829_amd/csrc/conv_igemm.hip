@@ -91,6 +91,15 @@ __device__ __forceinline__ void mma<float>(const u32x4& wa, const u32x4& px, f32
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
 }
 
+// LDS traffic inside one wavefront needs no barrier (the hardware keeps a wavefront's LDS
+// instructions in issue order); only the compiler must not reorder a write and a later read
+// of another lane's data.
+__device__ __forceinline__ void lds_wave_order() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Output pixel m -> element offsets of its channel vector in y and in the residual.
 struct PixelAddr {
   size_t y, r;
@@ -335,42 +344,44 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   // store (and residual load) of a wavefront covers contiguous runs of memory.
   constexpr int VE = 16 / (int)sizeof(T);  // output elements per 16-byte store
   if (p.C_out % VE == 0) {
-    constexpr int CP = BN + 4;  // fp32 pitch of the staged tile: conflict-free float4 rows
-    static_assert(BM * CP * 4 <= 2 * (BM + BN) * ROWB, "staged tile must fit the K-loop LDS");
-    float* const Cs = (float*)smem;
+    // one wavefront stages one of its 32-pixel tiles at a time in a slot of its own: no
+    // workgroup barrier beyond the first, and the slots need far less LDS than the K loop
+    constexpr int CPW = TN * 32 + 4;  // fp32 pitch: conflict-free float4 rows
+    static_assert(4 * 32 * CPW * 4 <= 2 * (BM + BN) * ROWB, "staging slots must fit the K-loop LDS");
+    float* const Cw = (float*)smem + wave * (32 * CPW);
     __syncthreads();  // every wavefront is done reading the operand tiles
+    constexpr int CPR = TN * 32 / VE;  // 16-byte pieces per pixel of the wavefront's tile
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+    for (int tm = 0; tm < TM; ++tm) {
+      lds_wave_order();  // the previous tile's reads are issued before these writes
 #pragma unroll
       for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int row = (wm * TM + tm) * 32 + (lane & 31);
-          const int col = (wn * TN + tn) * 32 + g * 8 + (lane >> 5) * 4;
-          *(float4*)(Cs + row * CP + col) =
+        for (int g = 0; g < 4; ++g)
+          *(float4*)(Cw + (lane & 31) * CPW + tn * 32 + g * 8 + (lane >> 5) * 4) =
               make_float4(acc[tn][tm][g * 4], acc[tn][tm][g * 4 + 1], acc[tn][tm][g * 4 + 2],
                           acc[tn][tm][g * 4 + 3]);
+      lds_wave_order();
+#pragma unroll
+      for (int slot = lane; slot < 32 * CPR; slot += 64) {
+        const int row = slot / CPR, c = (slot % CPR) * VE;
+        const int m = m0 + (wm * TM + tm) * 32 + row, co = co0 + wn * TN * 32 + c;
+        if (m >= p.M || co >= p.C_out) continue;
+        float v[VE];
+#pragma unroll
+        for (int j = 0; j < VE; j += 4) {
+          const float4 t = *(const float4*)(Cw + row * CPW + c + j);
+          v[j] = t.x; v[j + 1] = t.y; v[j + 2] = t.z; v[j + 3] = t.w;
         }
-    __syncthreads();
-    constexpr int CPR = BN / VE;  // 16-byte pieces per pixel of the tile
-    for (int slot = tid; slot < BM * CPR; slot += 256) {
-      const int row = slot / CPR, c = (slot % CPR) * VE;
-      const int m = m0 + row, co = co0 + c;
-      if (m >= p.M || co >= p.C_out) continue;
-      float v[VE];
+        if (p.ws) {
+          float* dst = p.ws + ((size_t)blockIdx.z * p.M + m) * p.C_out + co;
 #pragma unroll
-      for (int j = 0; j < VE; j += 4) {
-        const float4 t = *(const float4*)(Cs + row * CP + c + j);
-        v[j] = t.x; v[j + 1] = t.y; v[j + 2] = t.z; v[j + 3] = t.w;
+          for (int j = 0; j < VE; j += 4)
+            *(float4*)(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+          continue;
+        }
+        finish_vec<T, VE>(p, m, co, v);
       }
-      if (p.ws) {
-        float* dst = p.ws + ((size_t)blockIdx.z * p.M + m) * p.C_out + co;
-#pragma unroll
-        for (int j = 0; j < VE; j += 4)
-          *(float4*)(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
-        continue;
-      }
-      finish_vec<T, VE>(p, m, co, v);
     }
     return;
   }
@@ -646,13 +657,18 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
 
 // Whether (and how) the direct kernel takes a launch: only layers that the tiled kernel
 // would cut along the reduction axis, with vectorisable channel counts.
+constexpr int kComputeUnits = 256;
+
 struct DirectChoice {
   int wk, nt;      // wk == 0: not applicable
   int z, per_z;    // slices of the reduction across workgroups, steps per slice
 };
 DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
   const int ke = dtype == LOP_BF16 ? 8 : 4;
-  if (!p.wd || splits <= 1 || p.C_in % ke != 0 || p.C_out % ke != 0) return {0, 0, 0, 0};
+  // (also layers whose tile grid is a fraction of the chip even without a cut: they are
+  // latency-bound, and this kernel has fewer rounds of latency)
+  const long tiles = (long)((p.M + 31) / 32) * ((p.C_out + 31) / 32);
+  if (!p.wd || (splits <= 1 && tiles > kComputeUnits) || p.C_in % ke != 0 || p.C_out % ke != 0) return {0, 0, 0, 0};
   const int steps = (p.K + 2 * ke - 1) / (2 * ke);
   const long mt32 = (p.M + 31) / 32, nt32 = (p.C_out + 31) / 32;
   // one workgroup per tile streams steps KiB of weights and as much of activations, and
@@ -699,7 +715,6 @@ struct Choice {
 
 constexpr int kBKB = 128;       // bytes of the reduction axis per row and step
 constexpr int kStages = 3;      // steps of global loads kept in flight
-constexpr int kComputeUnits = 256;
 
 // Largest tile that still gives every compute unit a workgroup; layers too small for
 // that take the smallest tile and cut the reduction axis into slices until the grid
