@@ -192,6 +192,47 @@ typedef struct {
 LOP_API int lop_plan_rowwise(const lop_rowwise_t* layers, int n_layers, int m, int k, int dtype,
                              int n_bands, unsigned flags, lop_plan_t** out_plan);
 
+/* ---- Local-operation scheduling model (Sec. IV-C): host arithmetic only, no GPU ----
+ *
+ * A vertex's operations are its output rows. A schedule gives every vertex two contiguous
+ * row intervals, x_M on the mobile device and x_R on the server, that together cover all rows
+ * (partitioning and operation-batching constraints); overlap is replication. The chain input
+ * is whole on M, the result must be whole on M. */
+typedef struct {
+  int n_ops;          /* output rows                                                        */
+  int input_from;     /* LOP_INPUT or an earlier vertex: the windowed edge                  */
+  int residual_from;  /* LOP_NO_RESIDUAL, LOP_INPUT or an earlier vertex of n_ops rows: an
+                         identity edge (row i needs row i)                                  */
+  int k, s, p, d;     /* rows of the parent one output row reads: window, stride, padding,
+                         dilation along the row axis                                        */
+  double cm_fixed, cm_row; /* C_M(v) = cm_fixed + cm_row * |x_M(v)| seconds (0 if empty)    */
+  double cr_fixed, cr_row; /* the same for the server                                       */
+  double row_bytes;   /* bytes of one output row                                            */
+} lop_loss_layer_t;
+
+typedef struct { int m_lo, m_hi, r_lo, r_hi; } lop_loss_alloc_t; /* x_M = [m_lo, m_hi), x_R */
+
+/* T = s_M(output) (Eq. 2) of a schedule under the dependency recurrence (Eq. 3): rows of a
+ * parent that a device consumes but did not produce arrive from the peer latency + rows *
+ * row_bytes / bandwidth seconds after the peer has finished that parent; several parents
+ * combine by max; a device runs its vertices in index order. s_m (n_layers + 1 doubles, the
+ * last is T) and s_r (n_layers) receive the start times if not NULL; *violations (optional)
+ * the number of edges that carry rows out of a vertex whose output is larger than the raw
+ * input (transmission-efficiency constraint). LOP_ERR_INVALID_ARG: malformed problem;
+ * LOP_ERR_BAND_RANGE: an allocation that is not two intervals covering the vertex's rows. */
+LOP_API int lop_loss_eval(const lop_loss_layer_t* layers, int n_layers, int in_rows, double in_row_bytes,
+                          double bandwidth, double latency, const lop_loss_alloc_t* sched, double* T,
+                          double* s_m, double* s_r, int* violations);
+
+/* Search a schedule of small T by differential evolution (DE/rand/1/bin, F 0.6, CR 0.9) over
+ * x_M = [0, A), x_R = [B, n) with B <= A per vertex, seeded with the two one-device schedules;
+ * schedules that break the transmission-efficiency constraint lose against all that keep it.
+ * population <= 0: ten per decision variable. Deterministic for a given seed. Writes the best
+ * schedule found (n_layers entries), its T and its violation count. */
+LOP_API int lop_loss_solve(const lop_loss_layer_t* layers, int n_layers, int in_rows, double in_row_bytes,
+                           double bandwidth, double latency, int population, int generations,
+                           unsigned long long seed, lop_loss_alloc_t* best, double* T, int* violations);
+
 /* Time one layer's kernel of one band in isolation: `iters` launches on the plan's
  * compute stream between two events, on the plan's own scratch (contents are whatever
  * the last run left). Writes the mean milliseconds per launch. Measurement aid. */

@@ -46,7 +46,7 @@ EXPORTS = [
     "lop_plan_band_layer_rows", "lop_plan_stats", "lop_plan_layer_work", "lop_run_band",
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
     "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
-    "lop_plan_band_compute_rows", "lop_plan_rowwise",
+    "lop_plan_band_compute_rows", "lop_plan_rowwise", "lop_loss_eval", "lop_loss_solve",
 ]
 
 
@@ -61,6 +61,17 @@ class lop_layer_t(Structure):
 class lop_rowwise_t(Structure):
     _fields_ = [("k", c_int), ("n", c_int), ("act", c_int), ("input_from", c_int),
                 ("residual_from", c_int), ("weight", c_void_p), ("bias", c_void_p)]
+
+
+class lop_loss_layer_t(Structure):
+    _fields_ = [("n_ops", c_int), ("input_from", c_int), ("residual_from", c_int),
+                ("k", c_int), ("s", c_int), ("p", c_int), ("d", c_int),
+                ("cm_fixed", c_double), ("cm_row", c_double), ("cr_fixed", c_double),
+                ("cr_row", c_double), ("row_bytes", c_double)]
+
+
+class lop_loss_alloc_t(Structure):
+    _fields_ = [("m_lo", c_int), ("m_hi", c_int), ("r_lo", c_int), ("r_hi", c_int)]
 
 
 class lop_tensor_desc_t(Structure):
@@ -89,6 +100,12 @@ def _load() -> ctypes.CDLL:
                              POINTER(P)]),
         "lop_plan_rowwise": (c_int, [POINTER(lop_rowwise_t), c_int, c_int, c_int, c_int, c_int, c_uint,
                                      POINTER(P)]),
+        "lop_loss_eval": (c_int, [POINTER(lop_loss_layer_t), c_int, c_int, c_double, c_double, c_double,
+                                  POINTER(lop_loss_alloc_t), POINTER(c_double), POINTER(c_double),
+                                  POINTER(c_double), POINTER(c_int)]),
+        "lop_loss_solve": (c_int, [POINTER(lop_loss_layer_t), c_int, c_int, c_double, c_double, c_double,
+                                   c_int, c_int, ctypes.c_ulonglong, POINTER(lop_loss_alloc_t),
+                                   POINTER(c_double), POINTER(c_int)]),
         "lop_plan_out_desc": (c_int, [P, POINTER(lop_tensor_desc_t)]),
         "lop_plan_layer_desc": (c_int, [P, c_int, POINTER(lop_tensor_desc_t)]),
         "lop_plan_n_bands": (c_int, [P]),
@@ -169,6 +186,37 @@ def lop_plan_rowwise(layers: Sequence[lop_rowwise_t], m: int, k: int, dtype: int
     _check(_lib.lop_plan_rowwise(arr, len(layers), m, k, dtype, n_bands, flags, byref(out)),
            "lop_plan_rowwise")
     return out
+
+
+def _loss_layers(layers):
+    """lop_loss_layer_t array from objects with the fields of the struct (duck-typed)."""
+    return (lop_loss_layer_t * len(layers))(*[
+        lop_loss_layer_t(L.n_ops, L.input_from, L.residual_from, L.k, L.s, L.p, L.d,
+                         L.cm_fixed, L.cm_row, L.cr_fixed, L.cr_row, L.row_bytes) for L in layers])
+
+
+def lop_loss_eval(layers, in_rows: int, in_row_bytes: float, bandwidth: float, latency: float,
+                  sched: Sequence[Tuple[Tuple[int, int], Tuple[int, int]]]):
+    """sched: per vertex ((m_lo, m_hi), (r_lo, r_hi)). Returns (T, s_m, s_r, violations)."""
+    n = len(layers)
+    arr = (lop_loss_alloc_t * n)(*[lop_loss_alloc_t(m[0], m[1], r[0], r[1]) for m, r in sched])
+    T, viol = c_double(0.0), c_int(0)
+    s_m, s_r = (c_double * (n + 1))(), (c_double * n)()
+    _check(_lib.lop_loss_eval(_loss_layers(layers), n, in_rows, in_row_bytes, bandwidth, latency,
+                              arr, byref(T), s_m, s_r, byref(viol)), "lop_loss_eval")
+    return T.value, list(s_m), list(s_r), viol.value
+
+
+def lop_loss_solve(layers, in_rows: int, in_row_bytes: float, bandwidth: float, latency: float,
+                   population: int = 0, generations: int = 200, seed: int = 1):
+    """Returns (schedule as in lop_loss_eval, T, violations)."""
+    n = len(layers)
+    best = (lop_loss_alloc_t * n)()
+    T, viol = c_double(0.0), c_int(0)
+    _check(_lib.lop_loss_solve(_loss_layers(layers), n, in_rows, in_row_bytes, bandwidth, latency,
+                               population, generations, seed, best, byref(T), byref(viol)),
+           "lop_loss_solve")
+    return [((a.m_lo, a.m_hi), (a.r_lo, a.r_hi)) for a in best], T.value, viol.value
 
 
 def lop_plan_destroy(plan) -> None:
