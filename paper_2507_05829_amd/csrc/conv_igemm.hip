@@ -39,6 +39,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 struct ConvParams {
   const void* x;
   void* y;
+  void* y2;  // second destination with y's layout, or nullptr
   const void* res;
   const void* w;   // [c_out_pad][k_pad]
   const void* wd;  // the same weights in MFMA operand order (conv_direct_kernel), or nullptr
@@ -137,6 +138,10 @@ __device__ __forceinline__ void finish4(const ConvParams& p, const PixelAddr& a,
     for (int j = 0; j < 4; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
     if (sizeof(T) == 2) *(uint2*)(yg + a.y + co) = *(const uint2*)o;
     else *(u32x4*)(yg + a.y + co) = *(const u32x4*)o;
+    if (p.y2) {
+      if (sizeof(T) == 2) *(uint2*)((T*)p.y2 + a.y + co) = *(const uint2*)o;
+      else *(u32x4*)((T*)p.y2 + a.y + co) = *(const u32x4*)o;
+    }
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -144,7 +149,9 @@ __device__ __forceinline__ void finish4(const ConvParams& p, const PixelAddr& a,
       float u = v[j];
       if (p.bias) u += p.bias[co + j];
       if (rg) u += to_f32(rg[a.r + co + j]);
-      yg[a.y + co + j] = from_f32<T>(apply_act(u, p.act));
+      const T o1 = from_f32<T>(apply_act(u, p.act));
+      yg[a.y + co + j] = o1;
+      if (p.y2) ((T*)p.y2)[a.y + co + j] = o1;
     }
   }
 }
@@ -171,6 +178,7 @@ __device__ __forceinline__ void finish_vec(const ConvParams& p, int m, int co, f
 #pragma unroll
   for (int j = 0; j < VE; ++j) o[j] = from_f32<T>(apply_act(v[j], p.act));
   *(u32x4*)((T*)p.y + pa.y + co) = *(const u32x4*)o;
+  if (p.y2) *(u32x4*)((T*)p.y2 + pa.y + co) = *(const u32x4*)o;
 }
 
 // BM pixels x BN channels per workgroup; WM x WN wavefronts; BKB bytes of the reduction
@@ -652,6 +660,7 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
     for (int j = 0; j < VE; ++j)
       o[j] = from_f32<T>(clamp_act(v[s][j] + e_bias[s][j] + to_f32(rr[j]), cl));
     *(u32x4*)((T*)p.y + e_y[s]) = *(const u32x4*)o;
+    if (p.y2) *(u32x4*)((T*)p.y2 + e_y[s]) = *(const u32x4*)o;
   }
 }
 
@@ -787,7 +796,7 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
 
 ConvParams make_params(const OpLaunch& L) {
   ConvParams p;
-  p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = L.w; p.wd = L.wd; p.bias = L.bias;
+  p.x = L.x.ptr; p.y = L.y.ptr; p.y2 = L.y2; p.res = L.res.ptr; p.w = L.w; p.wd = L.wd; p.bias = L.bias;
   p.ws = nullptr;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.H = L.x.h; p.W = L.x.w; p.C_in = L.x.c;
   p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w; p.C_out = L.y.c;

@@ -19,6 +19,8 @@ struct OpLaunch {
   int op = 0;     // lop_op_t
   int dtype = 0;  // lop_dtype_t
   Slab x, y, res; // res.ptr == nullptr: no residual
+  void* y2 = nullptr;  // optional second destination laid out exactly like y (mapped host
+                       // memory): every output element is stored to both
   const void* w = nullptr;      // device, kernel layout (see pack_* below)
   const void* wd = nullptr;     // dense conv: the weights in operand order, or nullptr
   const float* bias = nullptr;  // device or nullptr
@@ -54,6 +56,8 @@ struct KernelEvents {
 
 // Enqueue the kernel(s) for one operator on `stream`; `ev` (optional) times them.
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev = nullptr);
+// Whether launch_op's kernel for this operator honours OpLaunch::y2.
+bool stores_second_output(const OpLaunch& L);
 // Name of the kernel instance launch_op would pick, as a profiler prints it (without the
 // namespace and argument list), written to name[size]. Returns the number of K slices
 // (1: a single kernel; > 1: followed by splitk_finish_kernel).

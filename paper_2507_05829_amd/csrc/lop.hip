@@ -36,6 +36,10 @@ hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   return launch_rowwise_op(L, stream, ev);
 }
 
+bool stores_second_output(const OpLaunch& L) {
+  return L.op != LOP_CONV2D || !pointwise_applies(L);
+}
+
 int describe_op(const OpLaunch& L, char* name, size_t size) {
   if (L.op != LOP_CONV2D) return rowwise_describe(L, name, size);
   return pointwise_applies(L) ? pointwise_describe(L, name, size) : conv_igemm_describe(L, name, size);
@@ -326,10 +330,14 @@ lop_rows_t launch_rows(const lop_plan_t* P, int band, int l) {
 // Enqueue what produces layer l's rows of one band: its own kernel(s), or the fused launch
 // of the group it ends.
 hipError_t launch_layer(const lop_plan_t* P, int band, int l, const void* d_in, void* d_out,
-                        hipStream_t cs, lop::KernelEvents* ev = nullptr) {
+                        hipStream_t cs, lop::KernelEvents* ev = nullptr, void* y2 = nullptr) {
   const lop_rows_t r = launch_rows(P, band, l);
   if (r.hi <= r.lo) return hipSuccess;
-  if (P->fuse_head[l] < 0) return lop::launch_op(make_launch(P, band, l, d_in, d_out), cs, ev);
+  if (P->fuse_head[l] < 0) {
+    lop::OpLaunch o = make_launch(P, band, l, d_in, d_out);
+    o.y2 = y2;
+    return lop::launch_op(o, cs, ev);
+  }
   const int h = P->fuse_head[l];
   lop::OpLaunch e = describe_layer(P, h), d = describe_layer(P, h + 1);
   const lop::OpLaunch p = make_launch(P, band, l, d_in, d_out);
@@ -372,9 +380,32 @@ void launch_work(const lop_plan_t* P, int band, int l, double* flop, double* byt
   *bytes = b;
 }
 
-int enqueue_band_kernels(lop_plan_t* P, int band, const void* d_in, void* d_out, hipStream_t cs) {
+void* device_view_of_host(lop_plan_t* P, void* h_out);
+
+// Small band outputs leave through the last layer's own stores: its kernel writes every
+// element to the device tensor and to the mapped host buffer, so there is no copy launch to
+// wait for on the lane. Larger outputs keep the paced copy kernel (stores over PCIe from a
+// whole grid hold up the HBM writes of the kernels beside them).
+constexpr size_t kDirectHostStoreMax = 256 * 1024;
+
+// Device view of h_out if band `band` can deliver its rows that way, else nullptr.
+void* direct_host_target(lop_plan_t* P, int band, void* h_out) {
+  if (!h_out || (P->flags & (LOP_FLAG_NO_D2H | LOP_FLAG_DMA_COPY))) return nullptr;
+  const lop::Tables& t = P->t;
+  const int last = t.n_layers() - 1;
+  if (P->fuse_head[last] >= 0) return nullptr;
+  const lop_rows_t r = t.bands[band].need[t.n_layers()];
+  const size_t bytes = (size_t)t.in.n * (r.hi - r.lo) * t.row_elems(last) * t.esz();
+  if (bytes == 0 || bytes > kDirectHostStoreMax) return nullptr;
+  if (!lop::stores_second_output(make_launch(P, band, last, nullptr, nullptr))) return nullptr;
+  return device_view_of_host(P, h_out);
+}
+
+int enqueue_band_kernels(lop_plan_t* P, int band, const void* d_in, void* d_out, hipStream_t cs,
+                         void* y2 = nullptr) {
   const int nl = P->t.n_layers();
-  for (int l = 0; l < nl; ++l) LOP_HIP(launch_layer(P, band, l, d_in, d_out, cs));
+  for (int l = 0; l < nl; ++l)
+    LOP_HIP(launch_layer(P, band, l, d_in, d_out, cs, nullptr, l == nl - 1 ? y2 : nullptr));
   return LOP_OK;
 }
 
@@ -491,10 +522,20 @@ int enqueue_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h
   if (P->copied_valid[band] && !capturing)
     LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[band], 0));
   if (timing) LOP_HIP(hipEventRecord(P->ev_c0[band], cs));
-  int rc = enqueue_band_kernels(P, band, d_in, d_out, cs);
+  void* const direct = direct_host_target(P, band, h_out);
+  int rc = enqueue_band_kernels(P, band, d_in, d_out, cs, direct);
   if (rc != LOP_OK) return rc;
   if (timing) LOP_HIP(hipEventRecord(P->ev_c1[band], cs));
-  if (h_out && !(P->flags & LOP_FLAG_NO_D2H)) {
+  if (direct) {  // the rows are on their way already: nothing to copy, nothing to wait for
+    if (timing) {
+      LOP_HIP(hipEventRecord(P->ev_d0[band], cs));
+      LOP_HIP(hipEventRecord(P->ev_d1[band], cs));
+    }
+    if (!capturing) {
+      LOP_HIP(hipEventRecord(P->ev_copied[band], cs));
+      P->copied_valid[band] = 1;
+    }
+  } else if (h_out && !(P->flags & LOP_FLAG_NO_D2H)) {
     if (ds != cs) {  // stream order already gates a copy on the kernels' own stream
       LOP_HIP(hipEventRecord(P->ev_done[band], cs));
       LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[band], 0));

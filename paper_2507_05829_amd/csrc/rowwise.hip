@@ -20,6 +20,7 @@ namespace {
 struct RowParams {
   const void* x;
   void* y;
+  void* y2;  // second destination with y's layout, or nullptr
   const void* res;
   const float* w;  // depthwise: [kh*kw][C] fp32
   const float* bias;
@@ -151,7 +152,9 @@ __global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = clamp_act(acc[i], make_clamp(p.act));
   }
-  Vec<T, VEC>::store((T*)p.y + ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C + c, acc);
+  const size_t yo = ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C + c;
+  Vec<T, VEC>::store((T*)p.y + yo, acc);
+  if (p.y2) Vec<T, VEC>::store((T*)p.y2 + yo, acc);
 }
 
 
@@ -257,7 +260,9 @@ __global__ __launch_bounds__(256) void dwconv3x3_kernel(const Dw3Params q) {
       }
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = clamp_act(acc[i], clamp);
-    Vec<T, VEC>::store(yg + ((size_t)(n * p.y_rows + oh0 + r - p.y_row0) * p.W_out + ow) * p.C + c, acc);
+    const size_t yo = ((size_t)(n * p.y_rows + oh0 + r - p.y_row0) * p.W_out + ow) * p.C + c;
+    Vec<T, VEC>::store(yg + yo, acc);
+    if (p.y2) Vec<T, VEC>::store((T*)p.y2 + yo, acc);
   }
 }
 
@@ -306,7 +311,7 @@ hipError_t launch_rowwise(RowParams& p, int op, hipStream_t s, KernelEvents* ev)
 
 hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   RowParams p;
-  p.x = L.x.ptr; p.y = L.y.ptr; p.res = L.res.ptr; p.w = (const float*)L.w; p.bias = L.bias;
+  p.x = L.x.ptr; p.y = L.y.ptr; p.y2 = L.y2; p.res = L.res.ptr; p.w = (const float*)L.w; p.bias = L.bias;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.W = L.x.w; p.C = L.x.c;
   p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w;
   p.r_row0 = L.res.row0; p.r_rows = L.res.rows;
