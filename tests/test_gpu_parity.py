@@ -299,6 +299,28 @@ def test_no_d2h_flag_leaves_host_untouched():
     assert not np.isnan(dev).any() and np.isnan(host).all()
 
 
+@pytest.mark.parametrize("name,kw", [("tiny", dict()), ("mbv2", dict(h=48, w=40, n=2))])
+@pytest.mark.parametrize("how", ["dma_flag", "pageable"])
+def test_band_copies_through_the_copy_engines(oracle, name, kw, how):
+    """The other two ways a band's rows reach the host: LOP_FLAG_DMA_COPY with pinned memory,
+    and a host buffer that is not pinned at all (batch 2: strided copies)."""
+    chain = workloads.CONFIGS[name](**kw)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    plan = lop.Plan(chain, t, flags=lop.LOP_FLAG_DMA_COPY if how == "dma_flag" else 0)
+    d_in = to_device_nhwc(t.x, chain.dtype)
+    d_out = empty_out(plan.out_shape(), chain.dtype)
+    h_out = empty_out(plan.out_shape(), chain.dtype, pinned=(how == "dma_flag"))
+    if how == "pageable":
+        h_out = h_out.cpu()
+        assert not h_out.is_pinned()
+    plan.run_chain(d_in, d_out, h_out)
+    plan.synchronize()
+    plan.destroy()
+    np.testing.assert_array_equal(to_nchw(h_out), to_nchw(d_out))
+    assert rel_err(to_nchw(d_out), want) <= TOL[chain.dtype]
+
+
 def test_timing_struct_is_filled():
     chain = workloads.tiny_chain()
     t = workloads.make_tensors(chain)
