@@ -43,6 +43,7 @@ struct ConvParams {
   const void* res;
   const void* w;   // [c_out_pad][k_pad]
   const void* wd;  // the same weights in MFMA operand order (conv_direct_kernel), or nullptr
+  const void* wd16;  // ... in the operand order of 16 x 16 tiles (conv_narrow_kernel), or nullptr
   const float* bias;
   float* ws;  // split-K partial sums [split][M][C_out], or nullptr
   int x_row0, x_rows, H, W, C_in;
@@ -666,11 +667,154 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
 
 // Whether (and how) the direct kernel takes a launch: only layers that the tiled kernel
 // would cut along the reduction axis, with vectorisable channel counts.
+// 16 x 16 MFMA tiles of the same operand-direct scheme, for the layers with very few pixels
+// and megabytes of weights (the last stages of a backbone once it is banded): a 16-pixel x
+// 16-channel tile per workgroup gives four times as many workgroups as 32 x 32 tiles, enough to
+// pull the whole weight tensor through the compute units' load paths in one launch, so the
+// reduction need not be cut across workgroups and no finish kernel follows. Its 16 wavefronts
+// split the reduction axis; weights come from a third packing ([channel tile of 16][step]
+// [lane] 16 bytes, lane = quarter*16 + channel, holding k = step*MK + quarter*KE ... + KE,
+// MK = 4 vectors), pixels straight from the input slab; the 16 partial tiles are added through
+// LDS in wavefront order by the first wavefront, which also applies the epilogue.
+template <typename T>
+__device__ __forceinline__ void mma16(const u32x4& wa, const u32x4& px, f32x4& acc);
+template <>
+__device__ __forceinline__ void mma16<__bf16>(const u32x4& wa, const u32x4& px, f32x4& acc) {
+  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wa),
+                                                __builtin_bit_cast(bf16x8, px), acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f32x4& acc) {
+  const f32x4 a = __builtin_bit_cast(f32x4, wa), b = __builtin_bit_cast(f32x4, px);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], b[0], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], b[1], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], b[2], acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], acc, 0, 0, 0);
+}
+
+constexpr int kNarrowWaves = 16;
+
+template <typename T>
+__global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const ConvParams p) {
+  constexpr int WK = kNarrowWaves;
+  constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
+  constexpr int MK = 4 * KE;               // reduction elements per step (four lane quarters)
+  constexpr int U = 8;                     // steps of loads in flight
+  constexpr int CP = 20;                   // fp32 pitch of a staged 16 x 16 partial tile
+  constexpr int VE = KE;
+  constexpr int CPR = 16 / VE;             // 16-byte pieces per pixel of the tile
+  constexpr int SLOTS = 16 * CPR;          // <= 64: the first wavefront finishes the tile
+  __shared__ __attribute__((aligned(16))) float part[WK][16 * CP];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int px = lane & 15, kq = lane >> 4;
+  const int m0 = blockIdx.x * 16, co0 = blockIdx.y * 16;
+  const T* __restrict__ xg = (const T*)p.x;
+  const u32x4* __restrict__ wg = (const u32x4*)p.wd16;
+
+  // ---- epilogue operands of the finishing lanes, in flight during the reduction
+  const int e_row = tid / CPR, e_c = (tid % CPR) * VE;
+  const bool e_ok = tid < SLOTS && m0 + e_row < p.M && co0 + e_c < p.C_out;
+  size_t e_y = 0;
+  float e_bias[VE];
+  u32x4 e_res = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int j = 0; j < VE; ++j) e_bias[j] = 0.f;
+  if (e_ok) {
+    const int co = co0 + e_c;
+    const PixelAddr pa = pixel_addr(p, m0 + e_row);
+    e_y = pa.y + co;
+    if (p.bias) {
+#pragma unroll
+      for (int j = 0; j < VE; j += 4) {
+        const float4 b4 = *(const float4*)(p.bias + co + j);
+        e_bias[j] = b4.x; e_bias[j + 1] = b4.y; e_bias[j + 2] = b4.z; e_bias[j + 3] = b4.w;
+      }
+    }
+    if (p.res) e_res = *(const u32x4*)((const T*)p.res + pa.r + co);
+  }
+
+  // ---- this lane's pixel
+  const int m = m0 + px;
+  const bool m_ok = m < p.M;
+  int ih0, iw0, nrow;
+  {
+    const int mm = m_ok ? m : 0;
+    const int ow = mm % p.W_out;
+    const int q = mm / p.W_out;
+    const int r = q % p.R, n = q / p.R;
+    ih0 = (p.out_lo + r) * p.sh - p.ph;
+    iw0 = ow * p.sw - p.pw;
+    nrow = n * p.x_rows - p.x_row0;
+  }
+  const int steps_pad = p.k_pad / MK;         // pitch of the packed weights
+  const int steps_all = (p.K + MK - 1) / MK;  // steps that hold anything
+  const int per_wave = (steps_all + WK - 1) / WK;
+  const int s0 = wave * per_wave, s1 = min(steps_all, s0 + per_wave);
+  int ci, kwi, khi;  // position of this lane's vector: k = (khi*kw + kwi)*C_in + ci
+  {
+    const int k = s0 * MK + kq * KE;
+    const int tap = k / p.C_in;
+    ci = k - tap * p.C_in;
+    khi = tap / p.kw;
+    kwi = tap - khi * p.kw;
+  }
+  const u32x4* const wtile = wg + (size_t)blockIdx.y * steps_pad * 64 + lane;
+
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int sb = s0; sb < s1; sb += U) {
+    u32x4 a[U], w[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool live = sb + u < s1;
+      w[u] = u32x4{0u, 0u, 0u, 0u};
+      if (live) w[u] = wtile[(size_t)(sb + u) * 64];
+      const int ih = ih0 + khi * p.dh, iw = iw0 + kwi * p.dw;
+      const bool ok = live && m_ok && khi < p.kh && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
+                      iw >= 0 && iw < p.W;
+      a[u] = u32x4{0u, 0u, 0u, 0u};
+      if (ok) a[u] = *(const u32x4*)(xg + ((size_t)(nrow + ih) * p.W + iw) * p.C_in + ci);
+      ci += MK;
+      while (ci >= p.C_in) {
+        ci -= p.C_in;
+        if (++kwi == p.kw) { kwi = 0; ++khi; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) mma16<T>(w[u], a[u], acc);
+  }
+
+  // ---- in the accumulator a lane holds channels kq*4 + {0..3} of pixel px
+  *(float4*)(part[wave] + px * CP + kq * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  __syncthreads();
+  if (!e_ok) return;
+  float v[VE];
+#pragma unroll
+  for (int j = 0; j < VE; ++j) v[j] = 0.f;
+#pragma unroll
+  for (int w = 0; w < WK; ++w)
+#pragma unroll
+    for (int j = 0; j < VE; j += 4) {
+      const float4 q = *(const float4*)(&part[w][e_row * CP + e_c + j]);
+      v[j] += q.x; v[j + 1] += q.y; v[j + 2] += q.z; v[j + 3] += q.w;
+    }
+  const Clamp cl = make_clamp(p.act);
+  alignas(16) T rr[VE];
+  *(u32x4*)rr = e_res;
+  alignas(16) T o[VE];
+#pragma unroll
+  for (int j = 0; j < VE; ++j) o[j] = from_f32<T>(clamp_act(v[j] + e_bias[j] + to_f32(rr[j]), cl));
+  *(u32x4*)((T*)p.y + e_y) = *(const u32x4*)o;
+  if (p.y2) *(u32x4*)((T*)p.y2 + e_y) = *(const u32x4*)o;
+}
+
 constexpr int kComputeUnits = 256;
 
 struct DirectChoice {
   int wk, nt;      // wk == 0: not applicable
   int z, per_z;    // slices of the reduction across workgroups, steps per slice
+  bool narrow = false;  // conv_narrow_kernel (16 x 16 tiles, one launch) instead
 };
 DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
   const int ke = dtype == LOP_BF16 ? 8 : 4;
@@ -689,6 +833,15 @@ DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
     while (d.wk < 16 && (steps + d.wk - 1) / d.wk > 8) d.wk *= 2;
     return d;
   }
+  // few pixels and at most two rounds of loads per wavefront: 16 x 16 tiles finish the layer
+  // in one launch (with more pixels every pixel tile would pull the weights again, with a
+  // longer reduction the tiles' own latency chain and, in fp32, MFMA time exceed the cut's)
+  const int steps16 = (p.K + 4 * ke - 1) / (4 * ke);
+  if (p.wd16 && p.M <= 128 && steps16 <= 16 * kNarrowWaves) {
+    d.narrow = true;
+    d.z = 1;
+    return d;
+  }
   // a slice is one round of loads per wavefront (4 wavefronts x 8 steps)
   d.z = std::min(64, (steps + 31) / 32);
   d.per_z = (steps + d.z - 1) / d.z;
@@ -705,6 +858,10 @@ hipError_t launch_direct(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
 template <typename T>
 hipError_t launch_direct_any(const ConvParams& p, const DirectChoice& d, hipStream_t s,
                              KernelEvents* ev) {
+  if (d.narrow) {
+    dim3 grid((p.M + 15) / 16, (p.C_out + 15) / 16);
+    return launch_kernel(conv_narrow_kernel<T>, grid, dim3(64 * kNarrowWaves), s, ev, p);
+  }
   if (d.nt == 2) {
     if (d.wk == 4) return launch_direct<T, 4, 2>(p, s, ev);
     if (d.wk == 8) return launch_direct<T, 8, 2>(p, s, ev);
@@ -796,7 +953,7 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
 
 ConvParams make_params(const OpLaunch& L) {
   ConvParams p;
-  p.x = L.x.ptr; p.y = L.y.ptr; p.y2 = L.y2; p.res = L.res.ptr; p.w = L.w; p.wd = L.wd; p.bias = L.bias;
+  p.x = L.x.ptr; p.y = L.y.ptr; p.y2 = L.y2; p.res = L.res.ptr; p.w = L.w; p.wd = L.wd; p.wd16 = L.wd16; p.bias = L.bias;
   p.ws = nullptr;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.H = L.x.h; p.W = L.x.w; p.C_in = L.x.c;
   p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w; p.C_out = L.y.c;
@@ -846,7 +1003,8 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
   if (d.wk) {
     if (name && size)
-      snprintf(name, size, "conv_direct_kernel<%s, %d, %d>", bf ? "__bf16" : "float", d.wk, d.nt);
+      if (d.narrow) snprintf(name, size, "conv_narrow_kernel<%s>", bf ? "__bf16" : "float");
+      else snprintf(name, size, "conv_direct_kernel<%s, %d, %d>", bf ? "__bf16" : "float", d.wk, d.nt);
     return d.z;
   }
   if (name && size)

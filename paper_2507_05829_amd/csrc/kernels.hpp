@@ -23,6 +23,7 @@ struct OpLaunch {
                        // memory): every output element is stored to both
   const void* w = nullptr;      // device, kernel layout (see pack_* below)
   const void* wd = nullptr;     // dense conv: the weights in operand order, or nullptr
+  const void* wd16 = nullptr;   // dense conv: ... in the operand order of 16 x 16 tiles, or nullptr
   const float* bias = nullptr;  // device or nullptr
   int kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0, dh = 1, dw = 1;
   int act = 0;
@@ -37,7 +38,9 @@ struct OpLaunch {
 // Layers whose c_in and c_out are multiples of the 16-byte vector get a second packing in
 // MFMA operand order for the small-layer kernel: [c_out_pad / 32][k_pad / MK][64 lanes] x 16
 // bytes, MK = 2 vectors of elements; lane = half*32 + (co % 32) holds
-// w[co][step*MK + half*KE ... + KE) of the first packing.
+// w[co][step*MK + half*KE ... + KE) of the first packing. A third one serves 16 x 16 tiles:
+// [c_out_pad / 16][k_pad / MK16][64 lanes] x 16 bytes, MK16 = 4 vectors, lane = quarter*16 +
+// (co % 16) holds w[co][step*MK16 + quarter*KE ... + KE).
 constexpr int kConvCoutPad = 128;
 int conv_k_pad(int c_in, int kh, int kw, int dtype);
 inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvCoutPad * kConvCoutPad; }

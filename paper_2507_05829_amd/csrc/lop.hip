@@ -80,6 +80,7 @@ struct lop_plan_s {
   int device = -1;
   std::vector<void*> d_w;      // per layer packed weights (device) or nullptr
   std::vector<void*> d_wd;     // dense conv weights in MFMA operand order, or nullptr
+  std::vector<void*> d_wd16;   // ... in the operand order of 16 x 16 tiles, or nullptr
   // Layers that run as one launch: fuse_head[t] = first layer of the group whose last layer is
   // t (else -1); fused_away[l] = 1 for the layers of a group before its last (no launch, no
   // buffer of their own).
@@ -129,6 +130,7 @@ int upload_weights(lop_plan_t* P) {
   const bool bf = t.in.dtype == LOP_BF16;
   P->d_w.assign(nl, nullptr);
   P->d_wd.assign(nl, nullptr);
+  P->d_wd16.assign(nl, nullptr);
   P->d_bias.assign(nl, nullptr);
   P->k_pad.assign(nl, 0);
   for (int l = 0; l < nl; ++l) {
@@ -166,6 +168,19 @@ int upload_weights(lop_plan_t* P) {
             }
         LOP_HIP(hipMalloc(&P->d_wd[l], ord.size()));
         LOP_HIP(hipMemcpy(P->d_wd[l], ord.data(), ord.size(), hipMemcpyHostToDevice));
+        if (kp % (4 * ke) == 0) {
+          // ... and in the order of 16 x 16 tiles: [co / 16][step][quarter*16 + co % 16] x 16 B
+          const size_t steps16 = (size_t)kp / (4 * ke);
+          for (int co = 0; co < cp; ++co)
+            for (size_t st = 0; st < steps16; ++st)
+              for (int q = 0; q < 4; ++q) {
+                const size_t src = (size_t)co * kp + st * 4 * ke + (size_t)q * ke;
+                const size_t dst = (((size_t)(co / 16) * steps16 + st) * 64 + q * 16 + co % 16) * ke;
+                std::memcpy(&ord[dst * esz], &host[src * esz], 16);
+              }
+          LOP_HIP(hipMalloc(&P->d_wd16[l], ord.size()));
+          LOP_HIP(hipMemcpy(P->d_wd16[l], ord.data(), ord.size(), hipMemcpyHostToDevice));
+        }
       }
     } else if (d.op == LOP_DWCONV2D) {
       if (!d.weight) return LOP_ERR_INVALID_ARG;
@@ -261,6 +276,7 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
   if (L.d.residual_from != LOP_NO_RESIDUAL) o.res = slab_of(P, band, L.d.residual_from, d_in, d_out);
   o.w = P->d_w[l];
   o.wd = P->d_wd[l];
+  o.wd16 = P->d_wd16[l];
   o.bias = P->d_bias[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
   o.ph = L.d.ph; o.pw = L.d.pw; o.dh = L.d.dh; o.dw = L.d.dw;
@@ -283,7 +299,7 @@ lop::OpLaunch describe_layer(const lop_plan_t* P, int l) {
   o.x.n = o.y.n = P->t.in.n;
   if (L.d.residual_from != LOP_NO_RESIDUAL) o.res.ptr = const_cast<lop_plan_t*>(P);
   if (!P->d_w.empty()) {  // uploaded (not a plan-only plan)
-    o.w = P->d_w[l]; o.wd = P->d_wd[l]; o.bias = P->d_bias[l];
+    o.w = P->d_w[l]; o.wd = P->d_wd[l]; o.wd16 = P->d_wd16[l]; o.bias = P->d_bias[l];
     o.k_pad = P->k_pad[l];
   }
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
@@ -702,6 +718,7 @@ void lop_plan_destroy(lop_plan_t* P) {
   if (P->s_copy) (void)hipStreamSynchronize(P->s_copy);
   for (void* w : P->d_w) if (w) (void)hipFree(w);
   for (void* w : P->d_wd) if (w) (void)hipFree(w);
+  for (void* w : P->d_wd16) if (w) (void)hipFree(w);
   for (float* b : P->d_bias) if (b) (void)hipFree(b);
   for (auto* v : {&P->ev_done, &P->ev_copied, &P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);

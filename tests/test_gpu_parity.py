@@ -56,6 +56,8 @@ CONV_GRID = [
     (256, 64, 3, 1, 1, 1, (1, 6, 9)),      # fp32: reduction also cut across workgroups
     (512, 40, 3, 2, 1, 1, (1, 9, 8)),      # bf16: reduction also cut across workgroups
     (40, 24, 5, 1, 4, 2, (1, 12, 9)),      # dilated 5x5, K = 1000: half-filled last step
+    (512, 24, 3, 1, 1, 1, (1, 30, 9)),     # K = 4608 on ~90 pixels: fp32 cut, bf16 16x16 tiles
+    (1024, 40, 3, 1, 1, 1, (1, 6, 5)),     # K = 9216: cut across workgroups in both types
 ]
 
 
@@ -105,10 +107,12 @@ def test_small_layer_kernel_is_selected():
                 for b in range(plan.n_bands):
                     name, slices = plan.layer_kernel(b, 0)
                     if name.startswith("conv_direct_kernel"):
-                        seen.add((dtype, slices > 1))
+                        seen.add((dtype, "cut" if slices > 1 else "one launch"))
+                    if name.startswith("conv_narrow_kernel"):
+                        seen.add((dtype, "16x16 tiles"))
             finally:
                 plan.destroy()
-    assert seen == {("f32", False), ("f32", True), ("bf16", False), ("bf16", True)}
+    assert seen == {(d, v) for d in ("f32", "bf16") for v in ("one launch", "cut", "16x16 tiles")}
 
 
 ROW_GRID = [
