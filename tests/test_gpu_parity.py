@@ -539,3 +539,71 @@ def test_rowwise_full_size_sampled_rows(oracle):
     sub = workloads.RowChain("sub", 64, chain.k, chain.dtype, 1, chain.layers)
     want = oracle.run_row_chain(sub, workloads.Tensors(np.ascontiguousarray(t.x[rows]), t.weights, t.biases))
     assert rel_err(dev[rows], want) <= TOL["bf16"]
+
+
+# ---- seeded random shapes: every kernel choice the library can make, against the oracle ----
+
+def _random_conv_chain(rng, dtype):
+    """Two to four layers with random (valid) hyper-parameters, channel counts that are and are
+    not multiples of the vector width, an optional residual and pool, random band count."""
+    vec = 8 if dtype == "bf16" else 4
+    n = int(rng.choice([1, 1, 2, 3]))
+    h, w = int(rng.integers(9, 40)), int(rng.integers(5, 33))
+    c = int(rng.choice([3, vec, 2 * vec, 24, 5 * vec, 64, 96]))
+    chain = workloads.Chain("rand", (n, c, h, w), dtype, int(rng.integers(1, 7)))
+    for _ in range(int(rng.integers(2, 5))):
+        kind = rng.choice(["conv", "conv", "conv", "dw", "pool", "pw"])
+        hh = workloads_h(chain)
+        if kind == "conv":
+            k = int(rng.choice([1, 2, 3, 3, 5])); d = int(rng.choice([1, 1, 2]))
+            p = int(rng.integers(0, d * (k - 1) // 2 + 1)); s_ = int(rng.choice([1, 1, 2]))
+            if hh + 2 * p - d * (k - 1) < 2 or min_w(chain) + 2 * p - d * (k - 1) < 2:
+                continue
+            c_out = int(rng.choice([vec, 2 * vec, 6, 40, 64, 72, 128]))
+            same = (c_out == c and s_ == 1 and 2 * p == d * (k - 1))
+            res = len(chain.layers) - 1 if (same and rng.random() < 0.5) else workloads.NO_RESIDUAL
+            chain.add(workloads.CONV, c, c_out, k, s_, p, d, str(rng.choice(["none", "relu", "relu6"])),
+                      residual_from=res)
+            c = c_out
+        elif kind == "pw":
+            c_out = int(rng.choice([32, 64, 96, 192])) if dtype == "bf16" else int(rng.choice([vec, 48]))
+            chain.add(workloads.CONV, c, c_out, 1, 1, 0, 1, str(rng.choice(["none", "relu6"])))
+            c = c_out
+        elif kind == "dw":
+            s_ = int(rng.choice([1, 2]))
+            if hh < 3 or min_w(chain) < 3:
+                continue
+            chain.add(workloads.DWCONV, c, c, 3, s_, 1, 1, str(rng.choice(["relu6", "none"])))
+        else:
+            if hh < 4 or min_w(chain) < 4:
+                continue
+            chain.add(workloads.MAXPOOL, c, c, 2, 2, 0, 1, "none", has_bias=False)
+    return chain if chain.layers else None
+
+
+def workloads_h(chain):
+    from oracle import planner
+    return planner.infer_shapes(chain)[-1][2] if chain.layers else chain.in_shape[2]
+
+
+def min_w(chain):
+    from oracle import planner
+    return planner.infer_shapes(chain)[-1][3] if chain.layers else chain.in_shape[3]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("reuse", [0, 1])
+def test_random_chains(oracle, dtype, reuse):
+    rng = np.random.Generator(np.random.PCG64(1234 + 17 * reuse + (dtype == "bf16")))
+    done = 0
+    while done < 24:
+        chain = _random_conv_chain(rng, dtype)
+        if chain is None:
+            continue
+        t = workloads.make_tensors(chain, zero_bias=False, seed=int(rng.integers(1, 1 << 30)))
+        want = oracle.run_chain(chain, t)
+        dev, host = run_gpu(chain, t, flags=lop.LOP_FLAG_REUSE if reuse else 0)
+        desc = [(L.op, L.c_in, L.c_out, L.k, L.s, L.p, L.d, L.act, L.residual_from) for L in chain.layers]
+        np.testing.assert_array_equal(dev, host, err_msg=str((chain.in_shape, chain.n_bands, desc)))
+        assert rel_err(dev, want) <= TOL[dtype], (chain.in_shape, chain.n_bands, desc)
+        done += 1
