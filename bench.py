@@ -295,6 +295,11 @@ def main():
                    "hip_graph": bool(a.graph), "lanes": a.lanes or "default",
                    "replicas": a.replicas},
         "roofline": roof,
+        # the other two figures the metric names, for the whole chain: executed matrix FLOP per
+        # second against the MFMA peak of the arithmetic type, and the share of the per-band
+        # copy time that did not lengthen the step
+        "mfma_utilisation": round(res["executed_tflops"] / (2500.0 if chain.dtype == "bf16" else 157.3), 4),
+        "d2h_hidden": res["d2h_hidden_steady"],
         "detail": res,
         "also": also,
     }
