@@ -214,6 +214,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 
   // ---- the pixels this thread gathers (fixed over the K loop)
   int a_ih0[A_IT], a_iw0[A_IT], a_nrow[A_IT];
+  long a_off[A_IT];
   bool a_ok[A_IT];
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
@@ -227,7 +228,15 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
     a_ih0[i] = (p.out_lo + r) * p.sh - p.ph;
     a_iw0[i] = ow * p.sw - p.pw;
     a_nrow[i] = n * p.x_rows - p.x_row0;
+    // element offset of tap (0, 0), channel 0 of this pixel (may lie before the slab: only
+    // ever used together with a tap offset that the bounds check has accepted)
+    a_off[i] = ((long)(a_nrow[i] + a_ih0[i]) * p.W + a_iw0[i]) * p.C_in;
   }
+  // rows of the packed weights this thread loads (never guarded: the packing is padded)
+  size_t b_off[B_IT];
+#pragma unroll
+  for (int i = 0; i < B_IT; ++i) b_off[i] = (size_t)(co0 + lrow + RPP * i) * p.k_pad + chunk * KE;
+  const long tap_row = (long)p.dh * p.W * p.C_in, tap_col = (long)p.dw * p.C_in;
   // position of this thread's vector inside the reduction axis (VEC_A path)
   int ci = 0, kwi = 0, khi = 0;
   if (VEC_A) {
@@ -243,16 +252,17 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 
   auto gather = [&](int kc, u32x4 (&ra)[A_IT], u32x4 (&rb)[B_IT]) __attribute__((always_inline)) {
     if (VEC_A) {
+      // the tap's offset is the same for every pixel of this thread: one address add per load
+      const long toff = khi * tap_row + kwi * tap_col + ci;
+      const int dih = khi * p.dh, diw = kwi * p.dw;
+      const bool tap_ok = khi < p.kh;
 #pragma unroll
       for (int i = 0; i < A_IT; ++i) {
-        const int ih = a_ih0[i] + khi * p.dh, iw = a_iw0[i] + kwi * p.dw;
-        const bool ok = a_ok[i] && khi < p.kh && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
+        const int ih = a_ih0[i] + dih, iw = a_iw0[i] + diw;
+        const bool ok = a_ok[i] && tap_ok && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
                         iw >= 0 && iw < p.W;
         u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (ok) {
-          const size_t off = ((size_t)(a_nrow[i] + ih) * p.W + iw) * p.C_in + ci;
-          v = *(const u32x4*)(xg + off);
-        }
+        if (ok) v = *(const u32x4*)(xg + (a_off[i] + toff));
         ra[i] = v;
       }
       ci += BKE;
@@ -280,8 +290,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
       const int row = lrow + RPP * i;
-      if (BN % RPP == 0 || row < BN)
-        rb[i] = *(const u32x4*)(wg + (size_t)(co0 + row) * p.k_pad + kc * BKE + chunk * KE);
+      if (BN % RPP == 0 || row < BN) rb[i] = *(const u32x4*)(wg + (b_off[i] + (size_t)kc * BKE));
     }
   };
   auto stash = [&](int buf, const u32x4 (&ra)[A_IT], const u32x4 (&rb)[B_IT]) __attribute__((always_inline)) {
