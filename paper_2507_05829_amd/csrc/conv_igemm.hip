@@ -1011,9 +1011,10 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   static const int wm[] = {2, 2, 2, 4}, wn[] = {2, 2, 2, 1};
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
   if (d.wk) {
-    if (name && size)
+    if (name && size) {
       if (d.narrow) snprintf(name, size, "conv_narrow_kernel<%s>", bf ? "__bf16" : "float");
       else snprintf(name, size, "conv_direct_kernel<%s, %d, %d>", bf ? "__bf16" : "float", d.wk, d.nt);
+    }
     return d.z;
   }
   if (name && size)
