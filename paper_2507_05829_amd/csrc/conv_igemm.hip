@@ -182,6 +182,33 @@ __device__ __forceinline__ void finish_vec(const ConvParams& p, int m, int co, f
   if (p.y2) *(u32x4*)((T*)p.y2 + pa.y + co) = *(const u32x4*)o;
 }
 
+// Which tile a workgroup takes. The hardware hands workgroups to the 8 XCDs round-robin in
+// launch order (x fastest), and every XCD has an L2 of its own: in launch order the 64
+// workgroups that are resident on one XCD at a time would be scattered over the whole grid
+// and each would pull its own pixel tile and weight tile through that L2. Instead XCD k takes
+// the k-th contiguous eighth of a walk over the tiles that goes down groups of kGroupM pixel
+// tiles and then across the channel tiles, so its resident workgroups form a block of about
+// 8 x 8 tiles that shares 8 pixel tiles and 8 weight tiles. Reduction slices are outermost.
+struct TileId { int m, n, z; };
+constexpr int kXcds = 8, kGroupM = 8;
+__device__ __forceinline__ TileId xcd_tile(int mx, int ny, int nz) {
+  const int total = mx * ny * nz;
+  const int launch = blockIdx.x + mx * (blockIdx.y + ny * blockIdx.z);
+  const int xcd = launch % kXcds, slot = launch / kXcds;
+  const int q = total / kXcds, r = total % kXcds;
+  const int v = xcd * q + min(xcd, r) + slot;  // XCD k owns q (+1 for the first r) consecutive tiles
+  const int per_z = mx * ny;
+  const int z = v / per_z, t = v - z * per_z;
+  const int group = t / (kGroupM * ny), in_group = t - group * (kGroupM * ny);
+  const int first = group * kGroupM;
+  const int gm = min(kGroupM, mx - first);
+  TileId id;
+  id.z = z;
+  id.n = in_group / gm;
+  id.m = first + in_group - id.n * gm;
+  return id;
+}
+
 // BM pixels x BN channels per workgroup; WM x WN wavefronts; BKB bytes of the reduction
 // axis per row and step; VEC_A: c_in is a multiple of the 16-byte vector so one vector
 // never straddles two taps. blockIdx.z selects a slice of the reduction (split-K): the
@@ -203,18 +230,19 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
-  const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+  const TileId tile = xcd_tile(gridDim.x, gridDim.y, gridDim.z);
+  const int m0 = tile.m * BM, co0 = tile.n * BN;
   const int lrow = tid / CH, chunk = tid % CH;
   const T* __restrict__ xg = (const T*)p.x;
   const T* __restrict__ wg = (const T*)p.w;
 
   const int nk_all = p.k_pad / BKE;
-  const int kc0 = blockIdx.z * p.kc_per_split;
+  const int kc0 = tile.z * p.kc_per_split;
   const int kc1 = min(nk_all, kc0 + p.kc_per_split);
 
   // ---- the pixels this thread gathers (fixed over the K loop)
   int a_ih0[A_IT], a_iw0[A_IT], a_nrow[A_IT];
-  long a_off[A_IT];
+  int a_off[A_IT];
   bool a_ok[A_IT];
 #pragma unroll
   for (int i = 0; i < A_IT; ++i) {
@@ -229,14 +257,16 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
     a_iw0[i] = ow * p.sw - p.pw;
     a_nrow[i] = n * p.x_rows - p.x_row0;
     // element offset of tap (0, 0), channel 0 of this pixel (may lie before the slab: only
-    // ever used together with a tap offset that the bounds check has accepted)
-    a_off[i] = ((long)(a_nrow[i] + a_ih0[i]) * p.W + a_iw0[i]) * p.C_in;
+    // ever used together with a tap offset that the bounds check has accepted). 32 bits: the
+    // host refuses a slab of 4 GiB or more, and so every load below is "uniform 64-bit base +
+    // 32-bit per-thread byte offset", the cheapest form in registers and address arithmetic.
+    a_off[i] = ((a_nrow[i] + a_ih0[i]) * p.W + a_iw0[i]) * p.C_in;
   }
   // rows of the packed weights this thread loads (never guarded: the packing is padded)
-  size_t b_off[B_IT];
-#pragma unroll
-  for (int i = 0; i < B_IT; ++i) b_off[i] = (size_t)(co0 + lrow + RPP * i) * p.k_pad + chunk * KE;
-  const long tap_row = (long)p.dh * p.W * p.C_in, tap_col = (long)p.dw * p.C_in;
+  // this thread's byte offset inside a group of RPP weight rows; the group and the step are
+  // uniform and go into the base
+  const unsigned b_voff = (unsigned)((lrow * p.k_pad + chunk * KE) * (int)sizeof(T));
+  const int tap_row = p.dh * p.W * p.C_in, tap_col = p.dw * p.C_in;
   // position of this thread's vector inside the reduction axis (VEC_A path)
   int ci = 0, kwi = 0, khi = 0;
   if (VEC_A) {
@@ -250,20 +280,28 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   // NS steps of global loads in flight
   u32x4 ra0[A_IT], ra1[A_IT], ra2[A_IT], rb0[B_IT], rb1[B_IT], rb2[B_IT];
 
-  auto gather = [&](int kc, u32x4 (&ra)[A_IT], u32x4 (&rb)[B_IT]) __attribute__((always_inline)) {
+  // `okm` gets one bit per A vector: set when its tap lies inside the image and the slab.
+  auto gather = [&](int kc, u32x4 (&ra)[A_IT], u32x4 (&rb)[B_IT], unsigned& okm) __attribute__((always_inline)) {
+    okm = VEC_A ? 0u : ~0u;
     if (VEC_A) {
       // the tap's offset is the same for every pixel of this thread: one address add per load
-      const long toff = khi * tap_row + kwi * tap_col + ci;
+      const int toff = khi * tap_row + kwi * tap_col + ci;
       const int dih = khi * p.dh, diw = kwi * p.dw;
       const bool tap_ok = khi < p.kh;
 #pragma unroll
       for (int i = 0; i < A_IT; ++i) {
         const int ih = a_ih0[i] + dih, iw = a_iw0[i] + diw;
-        const bool ok = a_ok[i] && tap_ok && ih >= p.x_row0 && ih < p.x_row0 + p.x_rows &&
-                        iw >= 0 && iw < p.W;
-        u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (ok) v = *(const u32x4*)(xg + (a_off[i] + toff));
-        ra[i] = v;
+        // (bitwise, not short-circuit: the test itself must not become a branch either)
+        const bool ok = a_ok[i] & tap_ok & (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows) &
+                        (iw >= 0) & (iw < p.W);
+        // No branch around the load, and no use of its result here: a tap outside the image or
+        // the slab reads the slab's first vector (always there) and is zeroed when the stage is
+        // written to LDS. With the same number of loads on every path, and nothing consuming them
+        // before that, the wait in front of a stage is "all but the two younger stages"; a
+        // skipped load on some path, or a select right here, makes it "everything".
+        const unsigned boff = (unsigned)((a_off[i] + toff) & -(int)ok) * (unsigned)sizeof(T);
+        ra[i] = *(const u32x4*)((const unsigned char*)xg + boff);
+        okm |= (unsigned)ok << i;
       }
       ci += BKE;
       while (ci >= p.C_in) {
@@ -290,14 +328,16 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
       const int row = lrow + RPP * i;
-      if (BN % RPP == 0 || row < BN) rb[i] = *(const u32x4*)(wg + (b_off[i] + (size_t)kc * BKE));
+      const unsigned char* group = (const unsigned char*)(wg + ((size_t)(co0 + RPP * i) * p.k_pad + (size_t)kc * BKE));
+      if (BN % RPP == 0 || row < BN) rb[i] = *(const u32x4*)(group + b_voff);
     }
   };
-  auto stash = [&](int buf, const u32x4 (&ra)[A_IT], const u32x4 (&rb)[B_IT]) __attribute__((always_inline)) {
+  auto stash = [&](int buf, const u32x4 (&ra)[A_IT], const u32x4 (&rb)[B_IT], unsigned okm) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < A_IT; ++i) {
       const int row = lrow + RPP * i;
-      if (BM % RPP == 0 || row < BM) *(u32x4*)(As + (buf * BM + row) * ROWB + chunk * 16) = ra[i];
+      if (BM % RPP == 0 || row < BM)
+        *(u32x4*)(As + (buf * BM + row) * ROWB + chunk * 16) = (okm >> i & 1u) ? ra[i] : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int i = 0; i < B_IT; ++i) {
@@ -320,9 +360,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
   // (every stage is a variable of its own and the step body is written out once per
   // stage: indexed through an array of stages they end up in private memory)
   static_assert(NS == 3, "the pipeline below is written out for three stages");
-  if (kc0 + 0 < kc1) gather(kc0 + 0, ra0, rb0);
-  if (kc0 + 1 < kc1) gather(kc0 + 1, ra1, rb1);
-  if (kc0 + 2 < kc1) gather(kc0 + 2, ra2, rb2);
+  unsigned ok0 = 0, ok1 = 0, ok2 = 0;
   auto multiply = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int ks = 0; ks < BKB / 32; ++ks) {
@@ -338,21 +376,53 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
       for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
+      // keep at most two sub-steps' fragments live: without this the LDS reads of all four are
+      // hoisted to the top and the big tile no longer fits two workgroups' registers
+      if (ks & 1) __builtin_amdgcn_sched_barrier(0);
     }
   };
-#define LOP_CONV_STEP(ST, RA, RB)                                   \
+#define LOP_CONV_STEP(ST, RA, RB, OK)                               \
   if (kc + ST < kc1) {                                              \
     const int buf = (kc - kc0 + ST) & 1;                            \
-    stash(buf, RA, RB);                                             \
+    stash(buf, RA, RB, OK);                                         \
     __syncthreads();                                                \
-    if (kc + ST + NS < kc1) gather(kc + ST + NS, RA, RB);           \
+    if (kc + ST + NS < kc1) gather(kc + ST + NS, RA, RB, OK);       \
     multiply(buf);                                                  \
   }
-  for (int kc = kc0; kc < kc1; kc += NS) {
-    LOP_CONV_STEP(0, ra0, rb0)
-    LOP_CONV_STEP(1, ra1, rb1)
-    LOP_CONV_STEP(2, ra2, rb2)
+#define LOP_CONV_STEP_FULL(ST, RA, RB, OK)                          \
+  {                                                                 \
+    const int buf = (kc - kc0 + ST) & 1;                            \
+    stash(buf, RA, RB, OK);                                         \
+    __syncthreads();                                                \
+    gather(kc + ST + NS, RA, RB, OK);                               \
+    multiply(buf);                                                  \
   }
+  int kc = kc0;
+  if (VEC_A && kc0 + 2 * NS <= kc1) {
+    // Steady state (vector gathers only; the element-wise gather of a narrow first layer has
+    // one or two steps and its loads are conditional anyway): every step exists and so does the step NS ahead of it. Nothing about the
+    // loads is conditional here, neither in the loop nor on the way into it, which is what
+    // lets the wait in front of a stage leave the two younger stages in flight.
+    gather(kc0 + 0, ra0, rb0, ok0);
+    gather(kc0 + 1, ra1, rb1, ok1);
+    gather(kc0 + 2, ra2, rb2, ok2);
+    for (; kc + 2 * NS <= kc1; kc += NS) {
+      LOP_CONV_STEP_FULL(0, ra0, rb0, ok0)
+      LOP_CONV_STEP_FULL(1, ra1, rb1, ok1)
+      LOP_CONV_STEP_FULL(2, ra2, rb2, ok2)
+    }
+  } else {
+    if (kc0 + 0 < kc1) gather(kc0 + 0, ra0, rb0, ok0);
+    if (kc0 + 1 < kc1) gather(kc0 + 1, ra1, rb1, ok1);
+    if (kc0 + 2 < kc1) gather(kc0 + 2, ra2, rb2, ok2);
+  }
+  // the last steps (fewer than 2 * NS), each guarded
+  for (; kc < kc1; kc += NS) {
+    LOP_CONV_STEP(0, ra0, rb0, ok0)
+    LOP_CONV_STEP(1, ra1, rb1, ok1)
+    LOP_CONV_STEP(2, ra2, rb2, ok2)
+  }
+#undef LOP_CONV_STEP_FULL
 #undef LOP_CONV_STEP
 
   // ---- epilogue. In the accumulator a lane holds, per 32x32 tile, pixel (lane & 31) and
@@ -392,7 +462,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
           v[j] = t.x; v[j + 1] = t.y; v[j + 2] = t.z; v[j + 3] = t.w;
         }
         if (p.ws) {
-          float* dst = p.ws + ((size_t)blockIdx.z * p.M + m) * p.C_out + co;
+          float* dst = p.ws + ((size_t)tile.z * p.M + m) * p.C_out + co;
 #pragma unroll
           for (int j = 0; j < VE; j += 4)
             *(float4*)(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
@@ -420,7 +490,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = acc[tn][tm][g * 4 + j];
         if (p.ws) {
-          float* dst = p.ws + ((size_t)blockIdx.z * p.M + m) * p.C_out + co;
+          float* dst = p.ws + ((size_t)tile.z * p.M + m) * p.C_out + co;
           if ((p.C_out & 3) == 0) {
             *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
           } else {
@@ -937,6 +1007,8 @@ template <typename T>
 hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, KernelEvents* ev) {
   constexpr int KE = 16 / (int)sizeof(T);
   const bool vec_a = p.C_in % KE == 0;
+  // the kernels address a slab with 32-bit byte offsets
+  if ((size_t)p.N * p.x_rows * p.W * p.C_in * sizeof(T) >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   const Choice c = choose(p, dtype);
   const DirectChoice d = choose_direct(p, dtype, c.splits);
   if (d.wk) {
