@@ -312,3 +312,25 @@ def make_row_tensors(chain: RowChain, zero_bias: bool = True, seed: Optional[int
         x = to_bf16_values(x)
         ws = [to_bf16_values(w) for w in ws]
     return Tensors(x, ws, bs)
+
+
+# ---- two-party schedules (Sec. IV-C variables x_M(v), x_R(v)) ----
+def random_schedule(heights: Sequence[int], seed: int, overlap: int = 2):
+    """One pair of contiguous intervals per layer whose union is [0, h): party M takes
+    [0, a), party R takes [b, h) with b <= a (the overlap is replication); either party may
+    end up with nothing, and which party takes the top rows is drawn per layer."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for h in heights:
+        a = int(rng.integers(0, h + 1))
+        b = max(0, a - int(rng.integers(0, overlap + 1)))
+        first, second = (0, a), (b, h)
+        if a == 0:
+            second = (0, h)
+        if b >= h:
+            second = (0, 0)
+        if rng.integers(0, 2):
+            out.append({"M": first, "R": second})
+        else:
+            out.append({"M": second, "R": first})
+    return out
