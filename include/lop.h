@@ -233,6 +233,38 @@ LOP_API int lop_loss_solve(const lop_loss_layer_t* layers, int n_layers, int in_
                            double bandwidth, double latency, int population, int generations,
                            unsigned long long seed, lop_loss_alloc_t* best, double* T, int* violations);
 
+/* Result of lop_run_two_party. */
+typedef struct {
+  float total_ms;      /* from the client's start until the whole result is on the client      */
+  double bytes_to_m;   /* bytes the client received over the emulated link                      */
+  double bytes_to_r;   /* bytes the server received                                             */
+  int transfers;       /* messages (contiguous row ranges of one tensor) over the link, both ways */
+} lop_two_party_stats_t;
+
+/* Runtime stage with two parties (Sec. IV-D, Alg. 1 client / Alg. 2 server), emulated on the
+ * one GPU: party M (client) holds the chain input and must end up with the whole result,
+ * party R (server) starts with nothing. Each party is a stream with full-height buffers of its
+ * own for every layer; for every layer, in chain order, a party computes its interval of
+ * sched[layer] (x_M = [m_lo, m_hi), x_R = [r_lo, r_hi); one launch per party and layer,
+ * operation batching), then for every edge out of that layer the rows its consumer on the other
+ * party reads and does not hold yet are copied across (Send / Receive / combine: they land at
+ * their position in the receiver's buffer). A consumer's launch waits only for its own
+ * messages. The link is one stream per direction: a message is a device-to-device copy followed
+ * by a wait of latency + bytes / bandwidth seconds (bandwidth in bytes per second), so messages
+ * in one direction queue behind each other. If costs is not NULL (n_layers entries, only the
+ * cm_ and cr_ fields are read) every launch is followed by a wait of its modelled time
+ * C_D(v) = fixed + per_row * rows on that party's stream, which makes the party as slow as the
+ * device it stands for. Fused launches are not used here. The plan's banding is ignored.
+ *   d_in  device, whole input (N x H x W x C, the client's copy); d_out device, whole output.
+ *   sched host, n_sched == number of layers, every entry two intervals covering the layer's
+ *         rows, else LOP_ERR_BAND_RANGE. stats host, optional.
+ * No single emulated wait may exceed 2 s (LOP_ERR_INVALID_ARG). Allocates and frees its
+ * buffers and streams inside the call and returns when both parties are done (synchronous).
+ * Values are those of the unpartitioned chain whatever the schedule (Sec. IV-B). */
+LOP_API int lop_run_two_party(lop_plan_t* plan, const void* d_in, void* d_out, const lop_loss_alloc_t* sched,
+                              int n_sched, const lop_loss_layer_t* costs, double bandwidth, double latency,
+                              lop_two_party_stats_t* stats);
+
 /* Time one layer's kernel of one band in isolation: `iters` launches on the plan's
  * compute stream between two events, on the plan's own scratch (contents are whatever
  * the last run left). Writes the mean milliseconds per launch. Measurement aid. */

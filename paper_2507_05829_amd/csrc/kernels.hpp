@@ -47,6 +47,8 @@ inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvC
 
 // Bytes of split-K scratch the dense conv launch needs (0: none).
 size_t conv_workspace_bytes(const OpLaunch& L);
+// True when a 1x1 dense conv takes the streaming kernel (which needs no workspace).
+bool pointwise_applies(const OpLaunch& L);
 
 // Events that time the kernels of one operator: pair 0 the operator's kernel, pair 1 the
 // finish kernel of a dense conv whose reduction axis is cut into slices. `n` counts the

@@ -25,7 +25,6 @@ bool mbconv_applies(const OpLaunch& e, const OpLaunch& d, const OpLaunch& p);
 int mbconv_describe(const OpLaunch& d, const OpLaunch& p, char* name, size_t size);
 hipError_t launch_mbconv(const OpLaunch& e, const OpLaunch& d, const OpLaunch& p, hipStream_t stream,
                          KernelEvents* ev);
-bool pointwise_applies(const OpLaunch& L);
 int pointwise_describe(const OpLaunch& L, char* name, size_t size);
 int conv_igemm_describe(const OpLaunch& L, char* name, size_t size);
 int rowwise_describe(const OpLaunch& L, char* name, size_t size);

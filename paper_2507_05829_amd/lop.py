@@ -47,6 +47,7 @@ EXPORTS = [
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
     "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
     "lop_plan_band_compute_rows", "lop_plan_rowwise", "lop_loss_eval", "lop_loss_solve",
+    "lop_run_two_party",
 ]
 
 
@@ -72,6 +73,11 @@ class lop_loss_layer_t(Structure):
 
 class lop_loss_alloc_t(Structure):
     _fields_ = [("m_lo", c_int), ("m_hi", c_int), ("r_lo", c_int), ("r_hi", c_int)]
+
+
+class lop_two_party_stats_t(Structure):
+    _fields_ = [("total_ms", c_float), ("bytes_to_m", c_double), ("bytes_to_r", c_double),
+                ("transfers", c_int)]
 
 
 class lop_tensor_desc_t(Structure):
@@ -124,6 +130,9 @@ def _load() -> ctypes.CDLL:
         "lop_plan_layer_kernel": (c_int, [P, c_int, c_int, ctypes.c_char_p, c_size_t, POINTER(c_int)]),
         "lop_profile_chain": (c_int, [P, c_void_p, c_void_p, c_int, POINTER(c_float), POINTER(c_float)]),
         "lop_copy_chain": (c_int, [P, c_void_p, c_void_p]),
+        "lop_run_two_party": (c_int, [P, c_void_p, c_void_p, POINTER(lop_loss_alloc_t), c_int,
+                                      POINTER(lop_loss_layer_t), c_double, c_double,
+                                      POINTER(lop_two_party_stats_t)]),
         "lop_strerror": (c_char_p, [c_int]),
         "lop_last_hip_error": (c_int, []),
     }
@@ -325,6 +334,18 @@ def lop_copy_chain(plan, d_out, h_out) -> None:
     _check(_lib.lop_copy_chain(plan, _ptr(d_out), _ptr(h_out)), "lop_copy_chain")
 
 
+def lop_run_two_party(plan, d_in, d_out, sched, bandwidth: float, latency: float = 0.0, costs=None):
+    """sched: per layer ((m_lo, m_hi), (r_lo, r_hi)); costs: objects with the lop_loss_layer_t
+    fields or None. Returns the filled lop_two_party_stats_t."""
+    n = len(sched)
+    arr = (lop_loss_alloc_t * n)(*[lop_loss_alloc_t(m[0], m[1], r[0], r[1]) for m, r in sched])
+    st = lop_two_party_stats_t()
+    _check(_lib.lop_run_two_party(plan, _ptr(d_in), _ptr(d_out), arr, n,
+                                  _loss_layers(costs) if costs is not None else None,
+                                  bandwidth, latency, byref(st)), "lop_run_two_party")
+    return st
+
+
 def lop_strerror(code: int) -> str:
     return _lib.lop_strerror(code).decode()
 
@@ -449,6 +470,9 @@ class Plan:
     def layer_kernel(self, b, l): return lop_plan_layer_kernel(self.handle, b, l)
     def profile_chain(self, d_in, d_out, iters=5): return lop_profile_chain(self.handle, d_in, d_out, iters)
     def copy_chain(self, d_out, h_out): lop_copy_chain(self.handle, d_out, h_out)
+
+    def run_two_party(self, d_in, d_out, sched, bandwidth, latency=0.0, costs=None):
+        return lop_run_two_party(self.handle, d_in, d_out, sched, bandwidth, latency, costs)
 
     def time_layer(self, band, layer, d_in, d_out, iters=20):
         return lop_time_layer(self.handle, band, layer, d_in, d_out, iters)

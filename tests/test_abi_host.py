@@ -204,3 +204,30 @@ def test_rowwise_plan_rows_and_errors():
     with pytest.raises(lop.LopError) as ei:
         lop.lop_plan_rowwise([bad], 10, 4, 0, 2, lop.LOP_FLAG_PLAN_ONLY)
     assert ei.value.code in (-1, -3)
+
+
+def test_two_party_schedule_is_checked_on_the_host():
+    """The schedule's constraints (two intervals covering OP(v), Sec. IV-C) are checked before
+    anything touches the GPU, so a plan-only plan is enough to see the codes."""
+    h = lop.lop_plan([_layer(), _layer(src=0)], _desc(), 2, lop.LOP_FLAG_PLAN_ONLY)
+
+    def code(sched, bandwidth=1e9, latency=0.0):
+        try:
+            lop.lop_run_two_party(h, 1, 1, sched, bandwidth, latency)
+        except lop.LopError as e:
+            return e.code
+        return 0
+
+    try:
+        good = [((0, 5), (5, 8)), ((0, 8), (0, 0))]
+        assert code(good) == lop.LOP_ERR_NOT_READY                      # valid, but nothing uploaded
+        assert code(good[:1]) == lop.LOP_ERR_INVALID_ARG                # one entry per layer
+        assert code(good, bandwidth=0.0) == lop.LOP_ERR_INVALID_ARG
+        assert code(good, latency=-1.0) == lop.LOP_ERR_INVALID_ARG
+        assert code([((0, 4), (5, 8)), ((0, 8), (0, 0))]) == lop.LOP_ERR_BAND_RANGE   # row 4 missing
+        assert code([((0, 9), (0, 0)), ((0, 8), (0, 0))]) == lop.LOP_ERR_BAND_RANGE   # outside OP(v)
+        assert code([((3, 2), (0, 8)), ((0, 8), (0, 0))]) == lop.LOP_ERR_BAND_RANGE   # lo > hi
+        assert code([((2, 6), (0, 3)), ((0, 8), (0, 0))]) == lop.LOP_ERR_BAND_RANGE   # rows 6, 7 missing
+        assert code([((2, 8), (0, 3)), ((0, 0), (0, 8))]) == lop.LOP_ERR_NOT_READY    # overlap is fine
+    finally:
+        lop.lop_plan_destroy(h)

@@ -6,6 +6,7 @@ import pytest
 import torch
 
 import workloads
+from oracle import planner
 from gpu_util import TOL, empty_out, rel_err, run_gpu, to_device_nhwc, to_nchw
 from paper_2507_05829_amd import lop
 
@@ -607,3 +608,108 @@ def test_random_chains(oracle, dtype, reuse):
         np.testing.assert_array_equal(dev, host, err_msg=str((chain.in_shape, chain.n_bands, desc)))
         assert rel_err(dev, want) <= TOL[dtype], (chain.in_shape, chain.n_bands, desc)
         done += 1
+
+
+# ---- two parties executing a schedule (Sec. IV-D, Alg. 1 / Alg. 2) ----
+def _heights(chain):
+    return [s[2] for s in planner.infer_shapes(chain)]
+
+
+def _as_pairs(sched):
+    return [(a["M"], a["R"]) for a in sched]
+
+
+def _run_two_party(chain, t, sched, bandwidth=1e12, latency=0.0, costs=None, flags=0):
+    plan = lop.Plan(chain, t, 1, flags)
+    try:
+        d_in = to_device_nhwc(t.x, chain.dtype)
+        d_out = empty_out(plan.out_shape(), chain.dtype)
+        st = plan.run_two_party(d_in, d_out, _as_pairs(sched), bandwidth, latency, costs)
+        return to_nchw(d_out), st
+    finally:
+        plan.destroy()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name,kw", [
+    ("tiny", {}),
+    ("resnet18", dict(h=64, w=48)),
+    ("mbv2", dict(h=48, w=40, n=2)),
+    ("detector720p", dict(h=90, w=64)),
+    ("vgg16", dict(h=64, w=32)),
+])
+def test_two_party_random_schedules(oracle, name, kw):
+    """Any schedule that covers every layer gives the unpartitioned result, and the bytes and
+    messages that cross the link are those the oracle's Alg. 1 / Alg. 2 exchange."""
+    from oracle import two_party
+    chain = workloads.CONFIGS[name](**kw)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    for seed in range(3):
+        sched = workloads.random_schedule(_heights(chain), seed=200 + seed, overlap=3)
+        _, ost = two_party.run(chain, t, sched)
+        got, st = _run_two_party(chain, t, sched)
+        assert not np.isnan(got).any()
+        assert rel_err(got, want) <= TOL[chain.dtype]
+        assert st.bytes_to_m == ost.bytes_to("M") and st.bytes_to_r == ost.bytes_to("R")
+        assert st.transfers == len(ost.transfers)
+
+
+@pytest.mark.gpu
+def test_two_party_small_integers_bit_exact(oracle):
+    """Integer-valued data: every partial sum is exact, so the two-party result equals the
+    oracle bit for bit whatever the split."""
+    chain = workloads.resnet18_chain(h=40, w=24)
+    chain.layers = chain.layers[:4]          # conv7x7 s2, max-pool, conv3x3, conv3x3 + shortcut
+    t = workloads.small_int_tensors(chain, seed=4)
+    want = oracle.run_chain(chain, t)
+    assert 0 < np.abs(want).max() < 2 ** 24   # every value and partial sum is an exact fp32 integer
+    for seed in (1, 2):
+        sched = workloads.random_schedule(_heights(chain), seed=seed, overlap=2)
+        got, _ = _run_two_party(chain, t, sched)
+        np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.gpu
+def test_two_party_single_party_extremes(oracle):
+    from oracle import two_party
+    chain = workloads.resnet18_chain(h=64, w=48)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    shapes = planner.infer_shapes(chain)
+    got, st = _run_two_party(chain, t, two_party.all_on(chain, "M"))
+    assert rel_err(got, want) <= TOL["f32"] and st.transfers == 0 and st.bytes_to_r == 0
+    got, st = _run_two_party(chain, t, two_party.all_on(chain, "R"))
+    assert rel_err(got, want) <= TOL["f32"] and st.transfers == 2
+    assert st.bytes_to_r == int(np.prod(chain.in_shape)) * 4
+    assert st.bytes_to_m == int(np.prod(shapes[-1])) * 4
+
+
+@pytest.mark.gpu
+def test_two_party_time_follows_the_model(oracle):
+    """With modelled compute times and a slow link far above the real kernel and copy times,
+    the measured completion time of the server-only schedule is the sum the dependency
+    recurrence (Eq. 3) gives for it: input transfer + the server's layers + result transfer
+    (nothing overlaps in that schedule, so queueing on the link plays no part)."""
+    from oracle import loss, two_party
+    chain = workloads.tiny_chain()
+    t = workloads.make_tensors(chain)
+    shapes = planner.infer_shapes(chain)
+    esz = 4
+    layers = []
+    for i, L in enumerate(chain.layers):
+        n, c, h, w = shapes[i]
+        layers.append(loss.LossLayer(n_ops=h, input_from=L.input_from, residual_from=L.residual_from,
+                                     k=L.k[0], s=L.s[0], p=L.p[0], d=L.d[0],
+                                     cm_fixed=0.004, cm_row=0.0005, cr_fixed=0.002, cr_row=0.0001,
+                                     row_bytes=float(n * c * w * esz)))
+    n, c, h, w = chain.in_shape
+    bandwidth, latency = 50e6, 0.003
+    for party in ("R", "M"):
+        sched = two_party.all_on(chain, party)
+        pairs = _as_pairs(sched)
+        T, _, _, _ = loss.evaluate(layers, h, float(n * c * w * esz), bandwidth, latency,
+                                   [loss.Alloc(m, r) for m, r in pairs])
+        got, st = _run_two_party(chain, t, sched, bandwidth, latency, layers)
+        assert rel_err(got, oracle.run_chain(chain, t)) <= TOL["f32"]
+        assert T * 1e3 <= st.total_ms <= T * 1e3 * 1.05 + 1.0, (party, T, st.total_ms)
