@@ -117,9 +117,6 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
       const double c = cost_seconds(v, d, x.hi - x.lo);
       if (!(c >= 0.0) || c > kMaxDelaySeconds) return LOP_ERR_INVALID_ARG;
     }
-  for (int u = -1; u < nl; ++u)
-    if (latency + (double)t.in.n * rows_of(u) * row_bytes(u) / bandwidth > kMaxDelaySeconds)
-      return LOP_ERR_INVALID_ARG;
 
   int device = 0, clock_khz = 0;
   LOP_HIP(hipGetDevice(&device));
@@ -198,7 +195,8 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
 
   // Send / Receive / combine for every edge out of u (Alg. 1 and 2, the loop over edges): the
   // rows party d will read and does not hold travel from its peer on the link into d.
-  auto exchange = [&](int u) -> int {
+  // dry: only follow who holds what and check that every wait is short enough to emulate.
+  auto exchange = [&](int u, bool dry) -> int {
     struct Edge { int v; bool identity; };
     std::vector<Edge> edges;
     for (int v = 0; v < nl; ++v) {
@@ -215,6 +213,12 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
         if (e.v == nl) need = d == 0 ? Piece{0, rows_of(u)} : Piece{0, 0};  // the result stays on the client
         else need = reads(e.v, xrows(e.v, d), u, e.identity);
         for (const Piece& pc : subtract(need, me.held[u + 1])) {
+          if (dry) {
+            if (latency + (double)(pc.hi - pc.lo) * rb * t.in.n / bandwidth > kMaxDelaySeconds)
+              return LOP_ERR_INVALID_ARG;
+            me.held[u + 1].push_back(pc);
+            continue;
+          }
           LOP_HIP(hipStreamWaitEvent(me.link_in, peer.done[u + 1], 0));
           LOP_HIP(hipMemcpy2DAsync((char*)me.buf[u + 1] + (size_t)pc.lo * rb, pitch,
                                    (const char*)peer.buf[u + 1] + (size_t)pc.lo * rb, pitch,
@@ -236,6 +240,19 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
     return LOP_OK;
   };
 
+  // first pass without the GPU: the messages this schedule causes, checked against the limit
+  for (int u = -1; u < nl; ++u) {
+    if (u >= 0)
+      for (int d = 0; d < 2; ++d) {
+        const Piece x = xrows(u, d);
+        if (x.hi > x.lo) S.party[d].held[u + 1].push_back(x);
+      }
+    const int rc_dry = exchange(u, true);
+    if (rc_dry != LOP_OK) return rc_dry;
+  }
+  for (Party& p : S.party) p.held.assign(nl + 1, {});
+  S.party[0].held[0].push_back(Piece{0, rows_of(-1)});
+
   LOP_HIP(hipEventCreate(&S.t0));
   LOP_HIP(hipEventCreate(&S.t1));
   LOP_HIP(hipDeviceSynchronize());
@@ -246,7 +263,7 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
   LOP_HIP(hipStreamWaitEvent(S.party[1].link_in, S.t0, 0));
   LOP_HIP(hipEventRecord(S.party[0].done[0], S.party[0].compute));
   LOP_HIP(hipEventRecord(S.party[1].done[0], S.party[1].compute));
-  int rc = exchange(-1);
+  int rc = exchange(-1, false);
   if (rc != LOP_OK) return rc;
   for (int u = 0; u < nl; ++u) {
     for (int d = 0; d < 2; ++d) {
@@ -264,7 +281,7 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
       }
       LOP_HIP(hipEventRecord(p.done[u + 1], p.compute));
     }
-    rc = exchange(u);
+    rc = exchange(u, false);
     if (rc != LOP_OK) return rc;
   }
   for (hipEvent_t e : S.party[0].wait_for[nl]) LOP_HIP(hipStreamWaitEvent(S.party[0].compute, e, 0));
