@@ -23,6 +23,12 @@ vertex combine by max; a device runs its operators one after another in chain or
 per operator), so s_D(v) >= s_D(v - 1) + C_D(v - 1) also when v - 1 is not a parent; transfers
 do not queue behind each other on the link (the recurrence has no such term); the volume of an
 edge is counted in whole rows of the parent's output.
+
+``evaluate_queued`` is the same model with the link as the runtime stage uses it (Sec. IV-D,
+Alg. 1 and 2): after every layer u the parties exchange, edge by edge, the rows the consumers
+will read; a message occupies its direction of the link for latency + bytes / bandwidth, so
+messages of one direction queue in the order they are issued; a party keeps what it received,
+so rows it already holds are not sent again. A consumer waits only for its own messages.
 """
 from __future__ import annotations
 
@@ -142,6 +148,88 @@ def evaluate(layers: Sequence[LossLayer], in_rows: int, in_row_bytes: float, ban
             start[dev][v] = ready(dev, peer, edges, v - 1 if v > 0 else None)
     last = n - 1
     t_out = ready("M", "R", [(last, (0, layers[last].n_ops))], last)
+    s_m = [start["M"][v] for v in range(n)] + [t_out]
+    s_r = [start["R"][v] for v in range(n)]
+    return t_out, s_m, s_r, violations
+
+
+def _minus(need: Interval, held: Sequence[Interval]) -> List[Interval]:
+    out = [need] if _len(need) else []
+    for h in held:
+        if not _len(h):
+            continue
+        nxt = []
+        for a, b in out:
+            if h[1] <= a or h[0] >= b:
+                nxt.append((a, b))
+                continue
+            if a < h[0]:
+                nxt.append((a, h[0]))
+            if h[1] < b:
+                nxt.append((h[1], b))
+        out = nxt
+    return out
+
+
+def evaluate_queued(layers: Sequence[LossLayer], in_rows: int, in_row_bytes: float, bandwidth: float,
+                    latency: float, sched: Sequence[Alloc]):
+    """Same returns as evaluate(), with the link shared as the runtime stage shares it."""
+    check(layers, sched)
+    n = len(layers)
+    rows_of = lambda u: in_rows if u == INPUT else layers[u].n_ops
+    bytes_of = lambda u: in_row_bytes if u == INPUT else layers[u].row_bytes
+    x = {"M": lambda v: sched[v].m, "R": lambda v: sched[v].r}
+    raw_input_bytes = in_rows * in_row_bytes
+    held = {D: {u: [] for u in range(-1, n)} for D in "MR"}
+    held["M"][INPUT] = [(0, in_rows)]
+    finish = {D: {INPUT: 0.0} for D in "MR"}        # when D's own rows of u exist
+    start = {D: {} for D in "MR"}
+    arrive = {D: {v: 0.0 for v in range(n + 1)} for D in "MR"}   # last message for consumer v
+    link_free = {"M": 0.0, "R": 0.0}                # direction into that party
+    violations = 0
+
+    def exchange(u):
+        nonlocal violations
+        for v in range(n + 1):
+            kinds = []
+            if v == n:
+                if u == n - 1:
+                    kinds.append(True)
+            else:
+                if layers[v].input_from == u:
+                    kinds.append(False)
+                if layers[v].residual_from == u:
+                    kinds.append(True)
+            for identity in kinds:
+                for D, O in (("M", "R"), ("R", "M")):
+                    if v == n:
+                        need = (0, rows_of(u)) if D == "M" else (0, 0)
+                    else:
+                        need = consumed_rows(layers[v], x[D](v), rows_of(u), identity)
+                    for lo, hi in _minus(need, held[D][u]):
+                        begin = max(finish[O][u], link_free[D])
+                        done = begin + latency + (hi - lo) * bytes_of(u) / bandwidth
+                        link_free[D] = done
+                        arrive[D][v] = max(arrive[D][v], done)
+                        held[D][u].append((lo, hi))
+                        if rows_of(u) * bytes_of(u) > raw_input_bytes:
+                            violations += 1
+
+    exchange(INPUT)
+    for u, L in enumerate(layers):
+        for D in "MR":
+            s = arrive[D][u]
+            if u > 0:
+                s = max(s, finish[D][u - 1])
+            start[D][u] = s
+            rows = _len(x[D](u))
+            c = 0.0
+            if rows:
+                c = (L.cm_fixed + L.cm_row * rows) if D == "M" else (L.cr_fixed + L.cr_row * rows)
+                held[D][u].append(x[D](u))
+            finish[D][u] = s + c
+        exchange(u)
+    t_out = max(finish["M"][n - 1], arrive["M"][n])
     s_m = [start["M"][v] for v in range(n)] + [t_out]
     s_r = [start["R"][v] for v in range(n)]
     return t_out, s_m, s_r, violations

@@ -102,3 +102,51 @@ def test_brute_force_optimum_beats_the_two_one_device_schedules():
     t_r = ev(layers, loss.all_on(layers, "R"), bw=2.0)[0]
     assert best <= min(t_m, t_r) and math.isfinite(best)
     assert ev(layers, sched, bw=2.0)[0] == best
+
+
+# ---- the same model with the link shared as the runtime stage shares it (Sec. IV-D) ----
+def test_queued_link_equals_the_recurrence_when_messages_never_meet():
+    """On the timelines above no two messages of one direction are in flight together and no
+    row is asked for twice, so sharing the link changes nothing."""
+    sched = [Alloc((0, 2), (2, 3)), Alloc((0, 2), (2, 3))]
+    for layers, s in ((unit_chain(), sched), (unit_chain(3, 1), sched),
+                      (unit_chain(), loss.all_on(unit_chain(), "M")),
+                      (unit_chain(), loss.all_on(unit_chain(), "R")),
+                      (unit_chain(3, 1), [Alloc((0, 2), (1, 3)), Alloc((0, 2), (2, 3))])):
+        assert loss.evaluate_queued(layers, 3, 1.0, 1.0, 0.0, s) == loss.evaluate(layers, 3, 1.0, 1.0, 0.0, s)
+
+
+def test_queued_link_hand_worked_halo_example():
+    """Two 3-row-window operators on 6 rows, M rows 0..2 and R rows 3..5 of both; 2 time units
+    per row on M, 1 on R, 1 per transmitted row. By hand along Alg. 1 / Alg. 2:
+    input rows 2..5 go up (0 -> 4); M's first operator 0 -> 6, R's 4 -> 7; row 3 comes down
+    7 -> 8 and row 2 goes up 6 -> 7 (the up link has been free since 4); second operator: M
+    8 -> 14, R 7 -> 10; R's three result rows come down 10 -> 13. T = 14."""
+    layers = [LossLayer(6, -1, k=3, p=1, cm_row=2, cr_row=1, row_bytes=1),
+              LossLayer(6, 0, k=3, p=1, cm_row=2, cr_row=1, row_bytes=1)]
+    sched = [Alloc((0, 3), (3, 6))] * 2
+    t, s_m, s_r, _ = loss.evaluate_queued(layers, 6, 1.0, 1.0, 0.0, sched)
+    assert (t, s_m, s_r) == (14.0, [0.0, 8.0, 14.0], [4.0, 7.0])
+
+
+def test_queued_link_makes_a_second_message_wait_for_the_first():
+    """An element-wise operator on M, then one on R that also adds the chain input. The input's
+    four rows go up first (0 -> 4, issued when the input exists); the first operator's rows are
+    ready at 1 but the link is busy until 4, so they arrive at 8 (the recurrence as printed
+    lets them arrive at 5); R computes 8 -> 12; the result comes down 12 -> 16 (13 as printed)."""
+    layers = [LossLayer(4, -1, cm_row=0.25, cr_row=1, row_bytes=1),
+              LossLayer(4, 0, residual_from=-1, cm_row=0.25, cr_row=1, row_bytes=1)]
+    sched = [Alloc((0, 4), (0, 0)), Alloc((0, 0), (0, 4))]
+    assert loss.evaluate_queued(layers, 4, 1.0, 1.0, 0.0, sched)[0] == 16.0
+    assert loss.evaluate(layers, 4, 1.0, 1.0, 0.0, sched)[0] == 13.0
+
+
+def test_queued_link_does_not_send_rows_twice():
+    """Both operators on R: the input is sent once although two edges leave it (0 -> 4), R
+    computes 4 -> 8 -> 12, the result comes down by 16; with a latency of 10 per message a
+    second copy of the input would show."""
+    layers = [LossLayer(4, -1, cm_row=0.25, cr_row=1, row_bytes=1),
+              LossLayer(4, 0, residual_from=-1, cm_row=0.25, cr_row=1, row_bytes=1)]
+    sched = loss.all_on(layers, "R")
+    assert loss.evaluate_queued(layers, 4, 1.0, 1.0, 0.0, sched)[0] == 16.0
+    assert loss.evaluate_queued(layers, 4, 1.0, 1.0, 10.0, sched)[0] == 36.0
