@@ -212,17 +212,27 @@ typedef struct {
 
 typedef struct { int m_lo, m_hi, r_lo, r_hi; } lop_loss_alloc_t; /* x_M = [m_lo, m_hi), x_R */
 
+/* How transfers share the link in the model. INDEPENDENT: Eq. 3 as printed, every edge's rows
+ * take latency + rows * row_bytes / bandwidth by themselves. QUEUED: as the runtime stage moves
+ * them (Sec. IV-D, lop_run_two_party): after every vertex the rows its consumers on the other
+ * device read travel as messages, a message occupies its direction of the link for latency +
+ * bytes / bandwidth, messages of one direction queue in issue order, and rows a device already
+ * holds are not sent again. */
+#define LOP_LINK_INDEPENDENT 0
+#define LOP_LINK_QUEUED 1
+
 /* T = s_M(output) (Eq. 2) of a schedule under the dependency recurrence (Eq. 3): rows of a
  * parent that a device consumes but did not produce arrive from the peer latency + rows *
  * row_bytes / bandwidth seconds after the peer has finished that parent; several parents
  * combine by max; a device runs its vertices in index order. s_m (n_layers + 1 doubles, the
  * last is T) and s_r (n_layers) receive the start times if not NULL; *violations (optional)
  * the number of edges that carry rows out of a vertex whose output is larger than the raw
- * input (transmission-efficiency constraint). LOP_ERR_INVALID_ARG: malformed problem;
+ * input (transmission-efficiency constraint). link_model: LOP_LINK_INDEPENDENT or
+ * LOP_LINK_QUEUED. LOP_ERR_INVALID_ARG: malformed problem;
  * LOP_ERR_BAND_RANGE: an allocation that is not two intervals covering the vertex's rows. */
 LOP_API int lop_loss_eval(const lop_loss_layer_t* layers, int n_layers, int in_rows, double in_row_bytes,
                           double bandwidth, double latency, const lop_loss_alloc_t* sched, double* T,
-                          double* s_m, double* s_r, int* violations);
+                          double* s_m, double* s_r, int* violations, int link_model);
 
 /* Search a schedule of small T by differential evolution (DE/rand/1/bin, F 0.6, CR 0.9) over
  * x_M = [0, A), x_R = [B, n) with B <= A per vertex, seeded with the two one-device schedules;
@@ -231,7 +241,8 @@ LOP_API int lop_loss_eval(const lop_loss_layer_t* layers, int n_layers, int in_r
  * schedule found (n_layers entries), its T and its violation count. */
 LOP_API int lop_loss_solve(const lop_loss_layer_t* layers, int n_layers, int in_rows, double in_row_bytes,
                            double bandwidth, double latency, int population, int generations,
-                           unsigned long long seed, lop_loss_alloc_t* best, double* T, int* violations);
+                           unsigned long long seed, lop_loss_alloc_t* best, double* T, int* violations,
+                           int link_model);
 
 /* Result of lop_run_two_party. */
 typedef struct {

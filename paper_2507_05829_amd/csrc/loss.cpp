@@ -9,7 +9,8 @@
 // read rows of u that D did not produce receives them from the peer after the peer has
 // finished u, taking latency + rows * row_bytes(u) / bandwidth. Several parent edges combine
 // by max; a device runs its operators one after another in chain order; transfers do not
-// queue behind each other. Edges out of a vertex whose output is larger than the raw input
+// queue behind each other (LOP_LINK_INDEPENDENT, Eq. 3 as printed) or share the link as the
+// runtime stage does (LOP_LINK_QUEUED, see evaluate_queued). Edges out of a vertex whose output is larger than the raw input
 // must carry nothing (transmission-efficiency constraint): counted as violations.
 #include <algorithm>
 #include <cmath>
@@ -58,10 +59,12 @@ struct Problem {
   int n;
   int in_rows;
   double in_row_bytes, bandwidth, latency;
+  int link_model;
 };
 
 bool valid_problem(const Problem& P) {
   if (!P.layers || P.n < 1 || P.in_rows < 1 || !(P.bandwidth > 0.0) || P.latency < 0.0) return false;
+  if (P.link_model != LOP_LINK_INDEPENDENT && P.link_model != LOP_LINK_QUEUED) return false;
   for (int v = 0; v < P.n; ++v) {
     const lop_loss_layer_t& L = P.layers[v];
     if (L.n_ops < 1 || L.k < 1 || L.s < 1 || L.d < 1 || L.p < 0) return false;
@@ -138,6 +141,109 @@ double evaluate(const Problem& P, const lop_loss_alloc_t* sched, double* s_m, do
   return sm[n];
 }
 
+// need minus the union of held (sorted disjoint pieces; at most a handful)
+void minus(Iv need, const std::vector<Iv>& held, std::vector<Iv>& out) {
+  out.clear();
+  if (need.len()) out.push_back(need);
+  std::vector<Iv> nxt;
+  for (const Iv& h : held) {
+    if (!h.len()) continue;
+    nxt.clear();
+    for (const Iv& p : out) {
+      if (h.hi <= p.lo || h.lo >= p.hi) { nxt.push_back(p); continue; }
+      if (p.lo < h.lo) nxt.push_back({p.lo, h.lo});
+      if (h.hi < p.hi) nxt.push_back({h.hi, p.hi});
+    }
+    out.swap(nxt);
+  }
+}
+
+// The same model with the link shared the way the runtime stage shares it (Sec. IV-D, Alg. 1
+// and 2): after every vertex u the rows its consumers on the other device will read travel as
+// messages, edge by edge; a message occupies its direction of the link for latency + bytes /
+// bandwidth, so messages of one direction queue in issue order; rows a device already holds
+// are not sent again; a consumer waits only for its own messages.
+double evaluate_queued(const Problem& P, const lop_loss_alloc_t* sched, double* s_m, double* s_r,
+                       int* violations) {
+  const int n = P.n;
+  auto rows_of = [&](int u) { return u == LOP_INPUT ? P.in_rows : P.layers[u].n_ops; };
+  auto bytes_of = [&](int u) { return u == LOP_INPUT ? P.in_row_bytes : P.layers[u].row_bytes; };
+  auto x = [&](int dev, int v) -> Iv {
+    return dev == 0 ? Iv{sched[v].m_lo, sched[v].m_hi} : Iv{sched[v].r_lo, sched[v].r_hi};
+  };
+  const double raw_input = (double)P.in_rows * P.in_row_bytes;
+  std::vector<std::vector<Iv>> held[2];
+  std::vector<double> finish[2], start[2], arrive[2];
+  for (int d = 0; d < 2; ++d) {
+    held[d].assign(n + 1, {});
+    finish[d].assign(n + 1, 0.0);  // [u + 1]
+    start[d].assign(n, 0.0);
+    arrive[d].assign(n + 1, 0.0);  // [consumer]; n = the result
+  }
+  held[0][0].push_back({0, P.in_rows});
+  double link_free[2] = {0.0, 0.0};  // direction into that device
+  int viol = 0;
+  std::vector<Iv> pieces;
+  auto exchange = [&](int u) {
+    for (int v = 0; v <= n; ++v) {
+      bool kinds[2];
+      int nk = 0;
+      if (v == n) {
+        if (u == n - 1) kinds[nk++] = true;
+      } else {
+        if (P.layers[v].input_from == u) kinds[nk++] = false;
+        if (P.layers[v].residual_from == u) kinds[nk++] = true;
+      }
+      for (int k = 0; k < nk; ++k)
+        for (int d = 0; d < 2; ++d) {
+          Iv need;
+          if (v == n) need = d == 0 ? Iv{0, rows_of(u)} : Iv{0, 0};
+          else need = consumed(P.layers[v], x(d, v), rows_of(u), kinds[k]);
+          minus(need, held[d][u + 1], pieces);
+          for (const Iv& pc : pieces) {
+            const double begin = std::max(finish[1 - d][u + 1], link_free[d]);
+            const double done = begin + P.latency + pc.len() * bytes_of(u) / P.bandwidth;
+            link_free[d] = done;
+            arrive[d][v] = std::max(arrive[d][v], done);
+            held[d][u + 1].push_back(pc);
+            if ((double)rows_of(u) * bytes_of(u) > raw_input) ++viol;
+          }
+        }
+    }
+  };
+  exchange(LOP_INPUT);
+  for (int u = 0; u < n; ++u) {
+    const lop_loss_layer_t& L = P.layers[u];
+    for (int d = 0; d < 2; ++d) {
+      double s = arrive[d][u];
+      if (u > 0) s = std::max(s, finish[d][u]);
+      start[d][u] = s;
+      const int rows = x(d, u).len();
+      double c = 0.0;
+      if (rows) {
+        c = d == 0 ? L.cm_fixed + L.cm_row * rows : L.cr_fixed + L.cr_row * rows;
+        held[d][u + 1].push_back(x(d, u));
+      }
+      finish[d][u + 1] = s + c;
+    }
+    exchange(u);
+  }
+  const double t_out = std::max(finish[0][n], arrive[0][n]);
+  if (s_m) {
+    std::copy(start[0].begin(), start[0].end(), s_m);
+    s_m[n] = t_out;
+  }
+  if (s_r) std::copy(start[1].begin(), start[1].end(), s_r);
+  if (violations) *violations = viol;
+  return t_out;
+}
+
+double evaluate_any(const Problem& P, const lop_loss_alloc_t* sched, double* s_m, double* s_r,
+                    int* violations) {
+  return P.link_model == LOP_LINK_QUEUED ? evaluate_queued(P, sched, s_m, s_r, violations)
+                                         : evaluate(P, sched, s_m, s_r, violations);
+}
+
 // splitmix64: the differential evolution's only source of randomness
 struct Rng {
   uint64_t s;
@@ -168,7 +274,7 @@ void decode(const Problem& P, const std::vector<double>& g, lop_loss_alloc_t* ou
 double fitness(const Problem& P, const std::vector<double>& g, std::vector<lop_loss_alloc_t>& tmp) {
   decode(P, g, tmp.data());
   int viol = 0;
-  const double t = evaluate(P, tmp.data(), nullptr, nullptr, &viol);
+  const double t = evaluate_any(P, tmp.data(), nullptr, nullptr, &viol);
   // a schedule that breaks the transmission-efficiency constraint loses against every one
   // that keeps it, and among such schedules fewer violations win
   return viol ? 1e30 * viol + t : t;
@@ -180,19 +286,20 @@ extern "C" {
 
 int lop_loss_eval(const lop_loss_layer_t* layers, int n_layers, int in_rows, double in_row_bytes,
                   double bandwidth, double latency, const lop_loss_alloc_t* sched, double* T,
-                  double* s_m, double* s_r, int* violations) {
-  const Problem P{layers, n_layers, in_rows, in_row_bytes, bandwidth, latency};
+                  double* s_m, double* s_r, int* violations, int link_model) {
+  const Problem P{layers, n_layers, in_rows, in_row_bytes, bandwidth, latency, link_model};
   if (!sched || !T || !valid_problem(P)) return LOP_ERR_INVALID_ARG;
   for (int v = 0; v < n_layers; ++v)
     if (!covers(sched[v], layers[v].n_ops)) return LOP_ERR_BAND_RANGE;
-  *T = evaluate(P, sched, s_m, s_r, violations);
+  *T = evaluate_any(P, sched, s_m, s_r, violations);
   return LOP_OK;
 }
 
 int lop_loss_solve(const lop_loss_layer_t* layers, int n_layers, int in_rows, double in_row_bytes,
                    double bandwidth, double latency, int population, int generations,
-                   unsigned long long seed, lop_loss_alloc_t* best, double* T, int* violations) {
-  const Problem P{layers, n_layers, in_rows, in_row_bytes, bandwidth, latency};
+                   unsigned long long seed, lop_loss_alloc_t* best, double* T, int* violations,
+                   int link_model) {
+  const Problem P{layers, n_layers, in_rows, in_row_bytes, bandwidth, latency, link_model};
   if (!best || !T || !valid_problem(P) || generations < 0) return LOP_ERR_INVALID_ARG;
   const int dim = 2 * n_layers;
   const int np = std::max(population > 0 ? population : 10 * dim, 8);
@@ -232,7 +339,7 @@ int lop_loss_solve(const lop_loss_layer_t* layers, int n_layers, int in_rows, do
     }
   const int bi = (int)(std::min_element(fit.begin(), fit.end()) - fit.begin());
   decode(P, pop[bi], best);
-  *T = evaluate(P, best, nullptr, nullptr, violations);
+  *T = evaluate_any(P, best, nullptr, nullptr, violations);
   return LOP_OK;
 }
 

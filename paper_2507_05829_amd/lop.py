@@ -34,6 +34,7 @@ LOP_MAX_BANDS = 64
 LOP_FLAG_NO_D2H, LOP_FLAG_PLAN_ONLY, LOP_FLAG_GRAPH, LOP_FLAG_DMA_COPY = 1, 2, 4, 8
 LOP_FLAG_REUSE = 16
 LOP_FLAG_NO_FUSE = 32
+LOP_LINK_INDEPENDENT, LOP_LINK_QUEUED = 0, 1
 
 
 def LOP_FLAG_LANES(n: int) -> int:
@@ -108,10 +109,10 @@ def _load() -> ctypes.CDLL:
                                      POINTER(P)]),
         "lop_loss_eval": (c_int, [POINTER(lop_loss_layer_t), c_int, c_int, c_double, c_double, c_double,
                                   POINTER(lop_loss_alloc_t), POINTER(c_double), POINTER(c_double),
-                                  POINTER(c_double), POINTER(c_int)]),
+                                  POINTER(c_double), POINTER(c_int), c_int]),
         "lop_loss_solve": (c_int, [POINTER(lop_loss_layer_t), c_int, c_int, c_double, c_double, c_double,
                                    c_int, c_int, ctypes.c_ulonglong, POINTER(lop_loss_alloc_t),
-                                   POINTER(c_double), POINTER(c_int)]),
+                                   POINTER(c_double), POINTER(c_int), c_int]),
         "lop_plan_out_desc": (c_int, [P, POINTER(lop_tensor_desc_t)]),
         "lop_plan_layer_desc": (c_int, [P, c_int, POINTER(lop_tensor_desc_t)]),
         "lop_plan_n_bands": (c_int, [P]),
@@ -205,25 +206,25 @@ def _loss_layers(layers):
 
 
 def lop_loss_eval(layers, in_rows: int, in_row_bytes: float, bandwidth: float, latency: float,
-                  sched: Sequence[Tuple[Tuple[int, int], Tuple[int, int]]]):
+                  sched: Sequence[Tuple[Tuple[int, int], Tuple[int, int]]], link_model: int = 0):
     """sched: per vertex ((m_lo, m_hi), (r_lo, r_hi)). Returns (T, s_m, s_r, violations)."""
     n = len(layers)
     arr = (lop_loss_alloc_t * n)(*[lop_loss_alloc_t(m[0], m[1], r[0], r[1]) for m, r in sched])
     T, viol = c_double(0.0), c_int(0)
     s_m, s_r = (c_double * (n + 1))(), (c_double * n)()
     _check(_lib.lop_loss_eval(_loss_layers(layers), n, in_rows, in_row_bytes, bandwidth, latency,
-                              arr, byref(T), s_m, s_r, byref(viol)), "lop_loss_eval")
+                              arr, byref(T), s_m, s_r, byref(viol), link_model), "lop_loss_eval")
     return T.value, list(s_m), list(s_r), viol.value
 
 
 def lop_loss_solve(layers, in_rows: int, in_row_bytes: float, bandwidth: float, latency: float,
-                   population: int = 0, generations: int = 200, seed: int = 1):
+                   population: int = 0, generations: int = 200, seed: int = 1, link_model: int = 0):
     """Returns (schedule as in lop_loss_eval, T, violations)."""
     n = len(layers)
     best = (lop_loss_alloc_t * n)()
     T, viol = c_double(0.0), c_int(0)
     _check(_lib.lop_loss_solve(_loss_layers(layers), n, in_rows, in_row_bytes, bandwidth, latency,
-                               population, generations, seed, best, byref(T), byref(viol)),
+                               population, generations, seed, best, byref(T), byref(viol), link_model),
            "lop_loss_solve")
     return [((a.m_lo, a.m_hi), (a.r_lo, a.r_hi)) for a in best], T.value, viol.value
 

@@ -1,10 +1,10 @@
 """Bandwidth study of the two-party runtime (Sec. IV-C scheduling + Sec. IV-D runtime, the
 setting of the paper's bandwidth-sensitivity experiment) on one GPU.
 
-For each bandwidth the library searches a schedule (lop_loss_solve), predicts its completion
-time T (Eq. 2) and then executes it with lop_run_two_party, where both parties are streams of
-the one GPU slowed down to modelled device speeds and the link is a timed wait. Device-only
-and server-only schedules run beside it. Synthetic weights and input; the device speeds are
+For each bandwidth the library searches a schedule (lop_loss_solve with the link model of the
+runtime, LOP_LINK_QUEUED), predicts its completion time T (Eq. 2) and then executes it with
+lop_run_two_party, where both parties are streams of the one GPU slowed down to modelled
+device speeds and the link is a timed wait. Device-only and server-only schedules run beside it. Synthetic weights and input; the device speeds are
 parameters, not measurements of any robot.
 
     python -m paper_2507_05829_amd.two_party_study --workload resnet18 --bandwidths 1,2,5,10,20,50
@@ -79,10 +79,11 @@ def main() -> None:
         bw = bw_mb * 1e6
         cells = []
         for sched in (only_m, only_r):
-            T = lop.lop_loss_eval(layers, hi, in_row_bytes, bw, lat, sched)[0]
+            T = lop.lop_loss_eval(layers, hi, in_row_bytes, bw, lat, sched, lop.LOP_LINK_QUEUED)[0]
             st = plan.run_two_party(d_in, d_out, sched, bw, lat, layers)
             cells.append(f"{T * 1e3:.1f} / {st.total_ms:.1f}")
-        best, T, viol = lop.lop_loss_solve(layers, hi, in_row_bytes, bw, lat, 0, a.generations, a.seed)
+        best, T, viol = lop.lop_loss_solve(layers, hi, in_row_bytes, bw, lat, 0, a.generations, a.seed,
+                                           lop.LOP_LINK_QUEUED)
         st = plan.run_two_party(d_in, d_out, best, bw, lat, layers)
         on_m = sum(m[1] - m[0] for m, _ in best) / sum(L.n_ops for L in layers)
         cells.append(f"{T * 1e3:.1f} / {st.total_ms:.1f}")

@@ -713,3 +713,35 @@ def test_two_party_time_follows_the_model(oracle):
         got, st = _run_two_party(chain, t, sched, bandwidth, latency, layers)
         assert rel_err(got, oracle.run_chain(chain, t)) <= TOL["f32"]
         assert T * 1e3 <= st.total_ms <= T * 1e3 * 1.05 + 1.0, (party, T, st.total_ms)
+
+
+@pytest.mark.gpu
+def test_two_party_time_follows_the_queued_link_model_on_random_schedules(oracle):
+    """Random schedules of a backbone with residual edges, modelled compute times and a slow
+    link: the measured completion time is the one the evaluator with the runtime's link model
+    predicts (LOP_LINK_QUEUED), up to the real kernel and copy times, which are tiny beside the
+    modelled ones."""
+    from oracle import loss
+    chain = workloads.resnet18_chain(h=64, w=48)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    shapes = planner.infer_shapes(chain)
+    layers = []
+    for i, L in enumerate(chain.layers):
+        n, c, h, w = shapes[i]
+        layers.append(loss.LossLayer(n_ops=h, input_from=L.input_from, residual_from=L.residual_from,
+                                     k=L.k[0], s=L.s[0], p=L.p[0], d=L.d[0],
+                                     cm_fixed=5e-4, cm_row=5e-5, cr_fixed=2e-4, cr_row=1e-5,
+                                     row_bytes=float(n * c * w * 4)))
+    n, c, h, w = chain.in_shape
+    bandwidth, latency = 20e6, 5e-4
+    for seed in (1, 2, 3):
+        sched = workloads.random_schedule(_heights(chain), seed=300 + seed, overlap=2)
+        allocs = [loss.Alloc(a["M"], a["R"]) for a in sched]
+        T = loss.evaluate_queued(layers, h, float(n * c * w * 4), bandwidth, latency, allocs)[0]
+        T_abi = lop.lop_loss_eval(layers, h, float(n * c * w * 4), bandwidth, latency, _as_pairs(sched),
+                                  lop.LOP_LINK_QUEUED)[0]
+        assert T_abi == pytest.approx(T, rel=1e-12)
+        got, st = _run_two_party(chain, t, sched, bandwidth, latency, layers)
+        assert rel_err(got, want) <= TOL["f32"]
+        assert T * 1e3 * 0.999 <= st.total_ms <= T * 1e3 * 1.05 + 2.0, (seed, T, st.total_ms)

@@ -81,6 +81,50 @@ def test_evaluator_equals_oracle_on_random_chains():
         np.testing.assert_allclose(got[2], want[2], rtol=1e-14)
 
 
+def test_queued_link_evaluator_equals_oracle_on_random_chains():
+    """The link model of the runtime stage (messages queue per direction, held rows are not
+    resent) through the C ABI against the oracle's."""
+    rng = np.random.Generator(np.random.PCG64(17))
+    checked = 0
+    for trial in range(300):
+        layers, in_rows, in_bytes = random_problem(rng, int(rng.integers(1, 9)))
+        sched = random_sched(rng, layers)
+        bw, lat = float(rng.uniform(1.0, 1e4)), float(rng.choice([0.0, 0.01]))
+        try:
+            want = O.evaluate_queued(layers, in_rows, in_bytes, bw, lat, sched)
+        except ValueError:
+            continue
+        got = lop.lop_loss_eval(layers, in_rows, in_bytes, bw, lat, as_sched(sched), lop.LOP_LINK_QUEUED)
+        assert got[3] == want[3]
+        np.testing.assert_allclose(got[0], want[0], rtol=1e-14)
+        np.testing.assert_allclose(got[1], want[1], rtol=1e-14)
+        np.testing.assert_allclose(got[2], want[2], rtol=1e-14)
+        checked += 1
+    assert checked > 100
+    L = [O.LossLayer(4, -1, cm_row=0.25, cr_row=1, row_bytes=1),
+         O.LossLayer(4, 0, residual_from=-1, cm_row=0.25, cr_row=1, row_bytes=1)]
+    sched = [((0, 4), (0, 0)), ((0, 0), (0, 4))]
+    assert lop.lop_loss_eval(L, 4, 1.0, 1.0, 0.0, sched, lop.LOP_LINK_QUEUED)[0] == 16.0   # hand-worked
+    assert lop.lop_loss_eval(L, 4, 1.0, 1.0, 0.0, sched, lop.LOP_LINK_INDEPENDENT)[0] == 13.0
+    with pytest.raises(lop.LopError):
+        lop.lop_loss_eval(L, 4, 1.0, 1.0, 0.0, sched, 7)
+
+
+def test_solver_with_the_queued_link_never_loses_to_one_device():
+    layers, in_rows, in_bytes = chain_problem(workloads.resnet18_chain())
+    for bw_mb in (2, 10, 50):
+        bw = bw_mb * 1e6
+        t_m = O.evaluate_queued(layers, in_rows, in_bytes, bw, 1e-3, O.all_on(layers, "M"))[0]
+        t_r, _, _, v_r = O.evaluate_queued(layers, in_rows, in_bytes, bw, 1e-3, O.all_on(layers, "R"))
+        sched, T, viol = lop.lop_loss_solve(layers, in_rows, in_bytes, bw, 1e-3, generations=100, seed=5,
+                                            link_model=lop.LOP_LINK_QUEUED)
+        assert viol == 0 and T <= t_m * (1 + 1e-12)
+        if v_r == 0:
+            assert T <= t_r * (1 + 1e-12)
+        want = O.evaluate_queued(layers, in_rows, in_bytes, bw, 1e-3, [O.Alloc(m, r) for m, r in sched])
+        assert want[0] == pytest.approx(T, rel=1e-14)
+
+
 def test_errors():
     L = unit_chain()
     with pytest.raises(lop.LopError) as e:
