@@ -214,15 +214,16 @@ __device__ __forceinline__ TileId xcd_tile(int mx, int ny, int nz) {
 // never straddles two taps. blockIdx.z selects a slice of the reduction (split-K): the
 // slices' fp32 partial tiles go to p.ws and splitk_finish_kernel adds them in slice order.
 template <typename T, int BM, int BN, int WM, int WN, int BKB, int NS, bool VEC_A>
-__global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
+__global__ __launch_bounds__(64 * WM * WN) void conv_igemm_kernel(const ConvParams p) {
   constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
   constexpr int CH = BKB / 16;             // vectors per row and step
   constexpr int BKE = CH * KE;             // reduction elements per step
   constexpr int ROWB = BKB + 16;           // LDS row pitch (16 pad bytes: conflict-free b128)
-  constexpr int RPP = 256 / CH;            // rows filled per pass of the 256 threads
+  constexpr int NW = WM * WN;              // wavefronts
+  constexpr int RPP = 64 * NW / CH;        // rows filled per pass of all threads
   constexpr int TM = BM / (WM * 32), TN = BN / (WN * 32);
   constexpr int A_IT = (BM + RPP - 1) / RPP, B_IT = (BN + RPP - 1) / RPP;
-  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
+  static_assert((NW == 4 || NW == 8) && TM >= 1 && TN >= 1, "tile shape");
 
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (BM + BN) * ROWB];
   unsigned char* const As = smem;
@@ -354,9 +355,9 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  // Software pipeline: the global loads of NS steps are in flight in registers; each
-  // step moves the oldest one into the LDS buffer the previous step is not reading,
-  // refills its registers with the step NS ahead and multiplies. One barrier per step.
+  // Software pipeline: the global loads of NS steps are in flight in registers and one more
+  // step sits in LDS; each step moves the oldest stage into the LDS buffer that is not being
+  // read, refills its registers and multiplies. One barrier per step.
   // (every stage is a variable of its own and the step body is written out once per
   // stage: indexed through an array of stages they end up in private memory)
   static_assert(NS == 3, "the pipeline below is written out for three stages");
@@ -381,46 +382,60 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
       if (ks & 1) __builtin_amdgcn_sched_barrier(0);
     }
   };
+  // One step: after the barrier the tile of this step is complete in LDS and nobody reads the
+  // other buffer any more, so the next step's stage (RA, RB: loaded two steps ago) goes into
+  // that buffer, its registers are refilled with the step NS further on, and the multiply of
+  // this step runs over both: the LDS writes and the global loads sit in the shadow of the
+  // MFMAs instead of in front of the barrier.
 #define LOP_CONV_STEP(ST, RA, RB, OK)                               \
   if (kc + ST < kc1) {                                              \
     const int buf = (kc - kc0 + ST) & 1;                            \
-    stash(buf, RA, RB, OK);                                         \
     __syncthreads();                                                \
-    if (kc + ST + NS < kc1) gather(kc + ST + NS, RA, RB, OK);       \
+    if (kc + ST + 1 < kc1) {                                        \
+      stash(buf ^ 1, RA, RB, OK);                                   \
+      if (kc + ST + 1 + NS < kc1) gather(kc + ST + 1 + NS, RA, RB, OK); \
+    }                                                               \
     multiply(buf);                                                  \
   }
 #define LOP_CONV_STEP_FULL(ST, RA, RB, OK)                          \
   {                                                                 \
     const int buf = (kc - kc0 + ST) & 1;                            \
-    stash(buf, RA, RB, OK);                                         \
     __syncthreads();                                                \
-    gather(kc + ST + NS, RA, RB, OK);                               \
+    stash(buf ^ 1, RA, RB, OK);                                     \
+    gather(kc + ST + 1 + NS, RA, RB, OK);                           \
     multiply(buf);                                                  \
   }
   int kc = kc0;
-  if (VEC_A && kc0 + 2 * NS <= kc1) {
+  if (VEC_A && kc0 + 2 * NS + 1 <= kc1) {
     // Steady state (vector gathers only; the element-wise gather of a narrow first layer has
-    // one or two steps and its loads are conditional anyway): every step exists and so does the step NS ahead of it. Nothing about the
-    // loads is conditional here, neither in the loop nor on the way into it, which is what
-    // lets the wait in front of a stage leave the two younger stages in flight.
+    // one or two steps and its loads are conditional anyway): every step, its successor and
+    // the refill NS beyond that exist. Nothing about the loads is conditional here, neither in
+    // the loop nor on the way into it, which is what lets the wait in front of a stage leave
+    // the two younger stages in flight.
     gather(kc0 + 0, ra0, rb0, ok0);
     gather(kc0 + 1, ra1, rb1, ok1);
     gather(kc0 + 2, ra2, rb2, ok2);
-    for (; kc + 2 * NS <= kc1; kc += NS) {
-      LOP_CONV_STEP_FULL(0, ra0, rb0, ok0)
-      LOP_CONV_STEP_FULL(1, ra1, rb1, ok1)
-      LOP_CONV_STEP_FULL(2, ra2, rb2, ok2)
+    stash(0, ra0, rb0, ok0);
+    gather(kc0 + NS, ra0, rb0, ok0);
+    for (; kc + 2 * NS + 1 <= kc1; kc += NS) {
+      LOP_CONV_STEP_FULL(0, ra1, rb1, ok1)
+      LOP_CONV_STEP_FULL(1, ra2, rb2, ok2)
+      LOP_CONV_STEP_FULL(2, ra0, rb0, ok0)
     }
   } else {
     if (kc0 + 0 < kc1) gather(kc0 + 0, ra0, rb0, ok0);
     if (kc0 + 1 < kc1) gather(kc0 + 1, ra1, rb1, ok1);
     if (kc0 + 2 < kc1) gather(kc0 + 2, ra2, rb2, ok2);
+    if (kc0 < kc1) {
+      stash(0, ra0, rb0, ok0);
+      if (kc0 + NS < kc1) gather(kc0 + NS, ra0, rb0, ok0);
+    }
   }
-  // the last steps (fewer than 2 * NS), each guarded
+  // the last steps (at most 2 * NS), each guarded; the stage named is the next step's
   for (; kc < kc1; kc += NS) {
-    LOP_CONV_STEP(0, ra0, rb0, ok0)
-    LOP_CONV_STEP(1, ra1, rb1, ok1)
-    LOP_CONV_STEP(2, ra2, rb2, ok2)
+    LOP_CONV_STEP(0, ra1, rb1, ok1)
+    LOP_CONV_STEP(1, ra2, rb2, ok2)
+    LOP_CONV_STEP(2, ra0, rb0, ok0)
   }
 #undef LOP_CONV_STEP_FULL
 #undef LOP_CONV_STEP
@@ -435,7 +450,7 @@ __global__ __launch_bounds__(256) void conv_igemm_kernel(const ConvParams p) {
     // one wavefront stages one of its 32-pixel tiles at a time in a slot of its own: no
     // workgroup barrier beyond the first, and the slots need far less LDS than the K loop
     constexpr int CPW = TN * 32 + 4;  // fp32 pitch: conflict-free float4 rows
-    static_assert(4 * 32 * CPW * 4 <= 2 * (BM + BN) * ROWB, "staging slots must fit the K-loop LDS");
+    static_assert(NW * 32 * CPW * 4 <= 2 * (BM + BN) * ROWB, "staging slots must fit the K-loop LDS");
     float* const Cw = (float*)smem + wave * (32 * CPW);
     __syncthreads();  // every wavefront is done reading the operand tiles
     constexpr int CPR = TN * 32 / VE;  // 16-byte pieces per pixel of the wavefront's tile
@@ -951,7 +966,7 @@ hipError_t launch_direct_any(const ConvParams& p, const DirectChoice& d, hipStre
   return launch_direct<T, 16, 1>(p, s, ev);
 }
 
-enum Shape { S128x128, S128x64, S64x64, S128x32 };
+enum Shape { S128x128, S128x64, S64x64, S128x32, S256x256 };
 struct Choice {
   Shape shape;
   int bm, bn;
@@ -959,7 +974,20 @@ struct Choice {
 };
 
 constexpr int kBKB = 128;       // bytes of the reduction axis per row and step
+constexpr int kBigBKB = 64;     // ... of the 256 x 256 tile (its registers and LDS allow no more)
 constexpr int kStages = 3;      // steps of global loads kept in flight
+
+// The 256 x 256 tile (eight wavefronts of 128 x 64, one workgroup per compute unit) moves half
+// the operand bytes per multiply-add of the 128 x 128 tile and reads LDS three times for every
+// four MFMAs instead of four times: measured a fifth faster per unit of tile area. But the chip
+// holds 256 of them at a time against 512 of the smaller tile, so the last, partly filled round
+// of workgroups weighs more. With t the time a compute unit needs for its two concurrent
+// 128 x 128 tiles, a round of the big tile (four tile areas) takes 4 / 2 / 1.2 = 5/3 t.
+bool big_tile_pays(long blocks256, long blocks128) {
+  const long rounds256 = (blocks256 + kComputeUnits - 1) / kComputeUnits;
+  const long rounds128 = (blocks128 + 2 * kComputeUnits - 1) / (2 * kComputeUnits);
+  return rounds256 * 5 < rounds128 * 3;
+}
 
 // Largest tile that still gives every compute unit a workgroup; layers too small for
 // that take the smallest tile and cut the reduction axis into slices until the grid
@@ -969,6 +997,12 @@ Choice choose(const ConvParams& p, int dtype) {
     return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn);
   };
   Choice c;
+  constexpr int kKE16 = 8;  // bf16 elements per 16-byte vector
+  if (dtype == LOP_BF16 && p.C_in % kKE16 == 0 && p.C_out % kKE16 == 0 && blocks(256, 256) >= kComputeUnits &&
+      big_tile_pays(blocks(256, 256), blocks(128, 128))) {
+    c = {S256x256, 256, 256, 1, p.k_pad / (kBigBKB / 2)};
+    return c;
+  }
   if (p.C_out > 64 && blocks(128, 128) >= kComputeUnits) c = {S128x128, 128, 128, 1, 0};
   else if (p.C_out > 32 && blocks(128, 64) >= kComputeUnits) c = {S128x64, 128, 64, 1, 0};
   else if (p.C_out > 32) c = {S64x64, 64, 64, 1, 0};
@@ -996,9 +1030,10 @@ hipError_t launch_finish(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
 template <typename T, int BM, int BN, int WM, int WN>
 hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, KernelEvents* ev) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
+  const dim3 block(64 * WM * WN);
   const hipError_t e =
-      vec_a ? launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>, grid, dim3(256), s, ev, p)
-            : launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>, grid, dim3(256), s, ev, p);
+      vec_a ? launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>, grid, block, s, ev, p)
+            : launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>, grid, block, s, ev, p);
   if (e != hipSuccess || !p.ws) return e;
   return launch_finish<T>(p, s, ev);
 }
@@ -1024,6 +1059,13 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
   p.kc_per_split = c.kc_per_split;
   if (c.splits > 1 && !ws) return hipErrorInvalidValue;
   p.ws = c.splits > 1 ? ws : nullptr;
+  if (c.shape == S256x256) {
+    if constexpr (sizeof(T) == 2) {
+      dim3 grid((p.M + 255) / 256, (p.C_out + 255) / 256, 1);
+      return launch_kernel(conv_igemm_kernel<T, 256, 256, 2, 4, kBigBKB, kStages, true>, grid, dim3(512), s, ev, p);
+    }
+    return hipErrorInvalidValue;
+  }
   switch (c.shape) {
     case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s, ev);
     case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s, ev);
@@ -1080,7 +1122,7 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const bool bf = L.dtype == LOP_BF16;
   const bool vec = p.C_in % (bf ? 8 : 4) == 0;
   const Choice c = choose(p, L.dtype);
-  static const int wm[] = {2, 2, 2, 4}, wn[] = {2, 2, 2, 1};
+  static const int wm[] = {2, 2, 2, 4, 2}, wn[] = {2, 2, 2, 1, 4};
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
   if (d.wk) {
     if (name && size) {
@@ -1091,7 +1133,8 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   }
   if (name && size)
     snprintf(name, size, "conv_igemm_kernel<%s, %d, %d, %d, %d, %d, %d, %s>", bf ? "__bf16" : "float",
-             c.bm, c.bn, wm[c.shape], wn[c.shape], kBKB, kStages, vec ? "true" : "false");
+             c.bm, c.bn, wm[c.shape], wn[c.shape], c.shape == S256x256 ? kBigBKB : kBKB, kStages,
+             vec ? "true" : "false");
   return c.splits;
 }
 

@@ -745,3 +745,48 @@ def test_two_party_time_follows_the_queued_link_model_on_random_schedules(oracle
         got, st = _run_two_party(chain, t, sched, bandwidth, latency, layers)
         assert rel_err(got, want) <= TOL["f32"]
         assert T * 1e3 * 0.999 <= st.total_ms <= T * 1e3 * 1.05 + 2.0, (seed, T, st.total_ms)
+
+
+# ---- the 256 x 256 tile of the tiled conv kernel (large layers, bf16) ----
+def test_big_tile_rowwise_ragged(oracle):
+    """A matrix product large enough for the 256 x 256 tile, with a ragged last tile in both
+    directions and a short reduction, every element against the oracle; then small integers
+    bit for bit."""
+    m, k, n = 15 * 256 + 37, 96, 16 * 256 - 8      # 16 x 16 tiles: one round of workgroups
+    chain = workloads.RowChain("big", m, k, "bf16", 1)
+    chain.add(n, "relu")
+    t = workloads.make_row_tensors(chain, zero_bias=False, seed=31)
+    want = oracle.run_row_chain(chain, t)
+    dev, host, names = _run_rows(chain, t)
+    assert any(nm.startswith("conv_igemm_kernel<__bf16, 256, 256, 2, 4, 64") for nm in names), names
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL["bf16"]
+    rng = np.random.Generator(np.random.PCG64(12))
+    ti = workloads.Tensors(rng.integers(-2, 3, (m, k)).astype(np.float32),
+                           [rng.integers(-1, 2, (n, k)).astype(np.float32)],
+                           [rng.integers(-3, 4, n).astype(np.float32)])
+    want = oracle.run_row_chain(chain, ti)
+    assert np.abs(want).max() <= 256
+    dev, _, _ = _run_rows(chain, ti)
+    np.testing.assert_array_equal(dev, want)
+
+
+def test_big_tile_conv3x3_with_residual(oracle):
+    """The same tile on the gather path: a 3 x 3 convolution with padding whose reduction
+    (12 steps) takes the steady-state loop and its tail, adding the output of a 1 x 1
+    convolution (2 steps: tail only) as residual; one band."""
+    chain = workloads.Chain("bigconv", (2, 40, 62, 66), "bf16", 1)   # 8184 pixels x 2032 channels: 32 x 8 tiles
+    a = chain.add(workloads.CONV, 40, 2048 - 16, 1, 1, 0, act="relu")
+    chain.add(workloads.CONV, 40, 2048 - 16, 3, 1, 1, act="relu", input_from=workloads.CHAIN_INPUT,
+              residual_from=a)
+    t = workloads.make_tensors(chain, zero_bias=False, seed=8)
+    plan = lop.Plan(chain, t)
+    try:
+        names = [plan.layer_kernel(0, l)[0] for l in range(2)]
+    finally:
+        plan.destroy()
+    assert all(nm.startswith("conv_igemm_kernel<__bf16, 256, 256, 2, 4, 64") for nm in names), names
+    want = oracle.run_chain(chain, t)
+    dev, host = run_gpu(chain, t)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL["bf16"]
