@@ -18,7 +18,7 @@ paper's definitions:
 * transmission-efficiency constraint: edges out of a vertex whose output is larger than the raw
   input must carry nothing.
 
-Readings where the paper is silent (listed in the design notes): several parent edges of one
+Readings where the paper is silent: several parent edges of one
 vertex combine by max; a device runs its operators one after another in chain order (one launch
 per operator), so s_D(v) >= s_D(v - 1) + C_D(v - 1) also when v - 1 is not a parent; transfers
 do not queue behind each other on the link (the recurrence has no such term); the volume of an

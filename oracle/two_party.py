@@ -15,7 +15,7 @@ per-layer functions (reference.run_layer), written from the paper's description:
   the result must equal the unpartitioned chain.
 
 Every buffer starts as NaN, so an operation that reads a row its party never computed nor
-received poisons the result. Reading where the paper is silent (listed in the design notes):
+received poisons the result. Reading where the paper is silent:
 a party keeps what it has received, so rows already received for an earlier consumer of the
 same tensor are not sent again.
 """

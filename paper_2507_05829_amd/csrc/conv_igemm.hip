@@ -4,11 +4,12 @@
 // pixels (n, oh, ow) with oh in the band's interval, columns are output channels, the
 // reduction runs over k = (a*kw + b)*c_in + ci. Activations are NHWC so a run of
 // channels of one tap is contiguous; the im2col matrix is never materialised: each
-// workgroup gathers its 64-byte K-slices of BM pixels straight from the input slab into
-// LDS (zero where a tap falls outside the image; rows outside the slab are never needed
-// by construction and are also read as zero, so no access can leave the slab).
+// workgroup gathers its K-slices (128 or 64 bytes per pixel and step) of BM pixels from the
+// input slab through registers into LDS (zero where a tap falls outside the image; rows
+// outside the slab are never needed by construction and are also taken as zero, and the
+// load that stands in for them reads the slab's first bytes, so no access can leave the slab).
 //
-// Wave tiling: 256 threads = 4 wavefronts of 64 lanes, each owning TM x TN tiles of
+// Wave tiling: 4 wavefronts of 64 lanes (8 for the 256 x 256 tile), each owning TM x TN tiles of
 // 32x32 (v_mfma_f32_32x32x16_bf16, or 4 x v_mfma_f32_32x32x2_f32 for fp32). The weight
 // tile is the MFMA A operand and the pixel tile the B operand, so in the accumulator a
 // lane holds 4 consecutive output channels of one pixel: bias, residual, activation and
@@ -18,7 +19,6 @@
 
 #include <algorithm>
 #include <cstdio>
-#include <type_traits>
 
 #include "act.hpp"
 #include "kernels.hpp"
@@ -66,14 +66,6 @@ __device__ __forceinline__ float to_f32(__bf16 v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ __bf16 from_f32<__bf16>(float v) { return (__bf16)v; }
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
 
 template <typename T>
 __device__ __forceinline__ void mma(const u32x4& wa, const u32x4& px, f32x16& acc);
