@@ -40,6 +40,8 @@ def parse():
                     help="also run a plain 256 MiB device-to-device copy (torch) a few times so "
                          "that a counter run can be scaled by a kernel of known traffic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-reference-points", action="store_true",
+                    help="skip the one-band run and the measured HBM / MFMA ceilings")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--profile-iters", type=int, default=10)
     return ap.parse_args()
@@ -203,6 +205,8 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
         d2h_hidden_steady=round(hidden_steady, 4), d2h_hidden_single=round(hidden_single, 4),
         d2h_hidden_single_bound=round((plan.n_bands - 1) / plan.n_bands, 4),
         latency_ms_single=round(med(lat), 4), latency_ms_single_no_d2h=round(med(lat_nc), 4),
+        latency_ms_single_p10=round(lat[len(lat) // 10], 4),
+        latency_ms_single_p90=round(lat[min(len(lat) - 1, len(lat) * 9 // 10)], 4),
         useful_gflop=round(useful / 1e9, 4), executed_over_useful=round(executed / useful, 4),
         useful_tflops=round(useful * steps / t_c / 1e12, 3),
         executed_tflops=round(executed * steps / t_c / 1e12, 3),
@@ -265,6 +269,20 @@ def main():
         del src, dst
     chain, tensors, res, roof = run_workload(torch, lop, workloads, a.workload, a.steps, a.warmup,
                                              a.bands, a.profile_iters, a.lanes, a.graph, a.dma_copy, a.replicas, a.mode)
+    if not a.no_reference_points:
+        # the same chain as one band (no partition): what splitting into bands costs or gains
+        _, _, whole, _ = run_workload(torch, lop, workloads, a.workload, max(a.steps // 4, 10), 5, 1,
+                                      1, a.lanes, a.graph, a.dma_copy, a.replicas, a.mode)
+        res["unbanded_images_per_s"] = round(whole["images_per_s"], 2)
+        res["unbanded_latency_ms_single"] = whole["latency_ms_single"]
+        # what the chip sustains on the roofline's two resources, beside the published peaks
+        c = lop.lop_measure_ceilings()
+        measured = {"hbm": c.hbm_copy_gbs, "mfma": c.mfma_bf16_tflops if chain.dtype == "bf16" else c.mfma_f32_tflops}
+        roof["measured_peak"] = round(measured[roof["bound"]], 1)
+        roof["frac_of_measured"] = round(roof["achieved"] / measured[roof["bound"]], 4)
+        res["measured_ceilings"] = {"hbm_copy_GBps": round(c.hbm_copy_gbs, 1),
+                                    "mfma_bf16_TFLOPps": round(c.mfma_bf16_tflops, 1),
+                                    "mfma_f32_TFLOPps": round(c.mfma_f32_tflops, 1)}
     also = []
     for entry in [e for e in a.also.split(",") if e]:
         name, _, mode = entry.partition(":")

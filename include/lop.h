@@ -276,6 +276,16 @@ LOP_API int lop_run_two_party(lop_plan_t* plan, const void* d_in, void* d_out, c
                               int n_sched, const lop_loss_layer_t* costs, double bandwidth, double latency,
                               lop_two_party_stats_t* stats);
 
+/* What this GPU sustains, measured: hbm_copy_gbs = bytes read + bytes written per second of a
+ * plain 16-byte-vector copy between two 1 GiB device buffers; mfma_bf16_tflops / mfma_f32_tflops
+ * = rate of a loop of nothing but independent 32x32x16 bf16 (32x32x2 fp32) MFMAs with two
+ * wavefronts on every SIMD and operand bits that differ per lane (all-zero operands clock
+ * higher than real data). Best of five launches each. Allocates and frees 2 GiB of device
+ * memory inside the call; synchronous; uses the null stream. Measurement aid: the roofline's
+ * denominators stay the published peaks, these say how close any kernel can get here. */
+typedef struct { double hbm_copy_gbs, mfma_bf16_tflops, mfma_f32_tflops; } lop_ceilings_t;
+LOP_API int lop_measure_ceilings(lop_ceilings_t* out /* host */);
+
 /* Time one layer's kernel of one band in isolation: `iters` launches on the plan's
  * compute stream between two events, on the plan's own scratch (contents are whatever
  * the last run left). Writes the mean milliseconds per launch. Measurement aid. */

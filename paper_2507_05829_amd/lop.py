@@ -48,7 +48,7 @@ EXPORTS = [
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
     "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
     "lop_plan_band_compute_rows", "lop_plan_rowwise", "lop_loss_eval", "lop_loss_solve",
-    "lop_run_two_party",
+    "lop_run_two_party", "lop_measure_ceilings",
 ]
 
 
@@ -79,6 +79,10 @@ class lop_loss_alloc_t(Structure):
 class lop_two_party_stats_t(Structure):
     _fields_ = [("total_ms", c_float), ("bytes_to_m", c_double), ("bytes_to_r", c_double),
                 ("transfers", c_int)]
+
+
+class lop_ceilings_t(Structure):
+    _fields_ = [("hbm_copy_gbs", c_double), ("mfma_bf16_tflops", c_double), ("mfma_f32_tflops", c_double)]
 
 
 class lop_tensor_desc_t(Structure):
@@ -134,6 +138,7 @@ def _load() -> ctypes.CDLL:
         "lop_run_two_party": (c_int, [P, c_void_p, c_void_p, POINTER(lop_loss_alloc_t), c_int,
                                       POINTER(lop_loss_layer_t), c_double, c_double,
                                       POINTER(lop_two_party_stats_t)]),
+        "lop_measure_ceilings": (c_int, [POINTER(lop_ceilings_t)]),
         "lop_strerror": (c_char_p, [c_int]),
         "lop_last_hip_error": (c_int, []),
     }
@@ -345,6 +350,12 @@ def lop_run_two_party(plan, d_in, d_out, sched, bandwidth: float, latency: float
                                   _loss_layers(costs) if costs is not None else None,
                                   bandwidth, latency, byref(st)), "lop_run_two_party")
     return st
+
+
+def lop_measure_ceilings() -> lop_ceilings_t:
+    c = lop_ceilings_t()
+    _check(_lib.lop_measure_ceilings(byref(c)), "lop_measure_ceilings")
+    return c
 
 
 def lop_strerror(code: int) -> str:

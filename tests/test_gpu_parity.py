@@ -790,3 +790,13 @@ def test_big_tile_conv3x3_with_residual(oracle):
     dev, host = run_gpu(chain, t)
     np.testing.assert_array_equal(dev, host)
     assert rel_err(dev, want) <= TOL["bf16"]
+
+
+def test_measured_ceilings_are_below_the_published_peaks():
+    """The copy and the MFMA-only loops behind the bench's `measured_peak`: each lands between a
+    fraction of the published peak and the peak itself (8 TB/s, 2.5 PFLOP/s bf16, 157.3 TFLOP/s
+    fp32); anything else means the loop does not measure what it says."""
+    c = lop.lop_measure_ceilings()
+    assert 2000.0 < c.hbm_copy_gbs <= 8000.0
+    assert 800.0 < c.mfma_bf16_tflops <= 2520.0
+    assert 60.0 < c.mfma_f32_tflops <= 158.5
