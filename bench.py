@@ -184,14 +184,16 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
     hidden_steady = 1.0 - max(0.0, t_c - t_a) / t_b
 
     # single request: one chain at a time, host clock around launch .. last byte
-    lat, lat_nc, cp = [], [], []
+    lat, lat_nc, cp, first, last = [], [], [], [], []
     for i in range(min(steps, 30)):
         tm = plan.run_chain(d_in, d_out[0], h_out[0], timing=True)
         lat.append(tm.wall_ms)
         cp.append(tm.copy_ms)
+        ready = [tm.band_ready_ms[b] for b in range(plan.n_bands) if tm.band_ready_ms[b] > 0]
+        first.append(min(ready)); last.append(max(ready))
         tm = plan.run_chain(d_in, d_out[0], None, timing=True)
         lat_nc.append(tm.wall_ms)
-    lat.sort(); lat_nc.sort(); cp.sort()
+    lat.sort(); lat_nc.sort(); cp.sort(); first.sort(); last.sort()
     med = lambda v: v[len(v) // 2]
     # (bands whose rows leave through the last kernel's own stores have no copy to time)
     hidden_single = (1.0 if med(cp) < 1e-3 else
@@ -205,6 +207,8 @@ def run_workload(torch, lop, workloads, name, steps, warmup, bands, profile_iter
         d2h_hidden_steady=round(hidden_steady, 4), d2h_hidden_single=round(hidden_single, 4),
         d2h_hidden_single_bound=round((plan.n_bands - 1) / plan.n_bands, 4),
         latency_ms_single=round(med(lat), 4), latency_ms_single_no_d2h=round(med(lat_nc), 4),
+        # device-timeline view of one request: when the first and the last band are on the host
+        first_band_ready_ms=round(med(first), 4), last_band_ready_ms=round(med(last), 4),
         latency_ms_single_p10=round(lat[len(lat) // 10], 4),
         latency_ms_single_p90=round(lat[min(len(lat) - 1, len(lat) * 9 // 10)], 4),
         useful_gflop=round(useful / 1e9, 4), executed_over_useful=round(executed / useful, 4),

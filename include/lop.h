@@ -80,6 +80,9 @@ typedef struct {
   float copy_ms;    /* sum of the bands' device-to-host copy durations               */
   float band_compute_ms[LOP_MAX_BANDS];
   float band_copy_ms[LOP_MAX_BANDS];
+  float band_ready_ms[LOP_MAX_BANDS]; /* from the start of the chain until the band's final rows
+                                         are complete (on the host if copied, else on the device):
+                                         when a consumer of that band could start (Sec. IV-B)   */
 } lop_timing_t;
 
 /* lop_plan flags */

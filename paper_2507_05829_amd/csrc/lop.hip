@@ -837,6 +837,7 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
       LOP_HIP(hipEventElapsedTime(&timing->band_copy_ms[b], P->ev_d0[b], P->ev_d1[b]));
       timing->copy_ms += timing->band_copy_ms[b];
     }
+    LOP_HIP(hipEventElapsedTime(&timing->band_ready_ms[b], P->ev_t0, copy ? P->ev_d1[b] : P->ev_c1[b]));
   }
   LOP_HIP(hipEventElapsedTime(&timing->compute_ms, P->ev_t0, P->ev_t1));
   return LOP_OK;

@@ -96,7 +96,8 @@ class lop_rows_t(Structure):
 class lop_timing_t(Structure):
     _fields_ = [("n_bands", c_int), ("wall_ms", c_float), ("compute_ms", c_float),
                 ("copy_ms", c_float), ("band_compute_ms", c_float * LOP_MAX_BANDS),
-                ("band_copy_ms", c_float * LOP_MAX_BANDS)]
+                ("band_copy_ms", c_float * LOP_MAX_BANDS),
+                ("band_ready_ms", c_float * LOP_MAX_BANDS)]
 
 
 def _load() -> ctypes.CDLL:

@@ -336,7 +336,14 @@ def test_timing_struct_is_filled():
     tm = plan.run_chain(d_in, d_out, h_out, timing=True)
     assert tm.n_bands == 4 and tm.wall_ms > 0 and tm.compute_ms > 0 and tm.copy_ms > 0
     assert all(tm.band_compute_ms[b] > 0 for b in range(4))
+    assert all(0 < tm.band_ready_ms[b] <= tm.wall_ms * 1.05 + 0.05 for b in range(4))
     assert not torch.isnan(h_out).any()
+    plan.destroy()
+    # bands in order on one lane: each band is ready after the one before it
+    plan = lop.Plan(chain, t, flags=lop.LOP_FLAG_REUSE)
+    tm = plan.run_chain(d_in, d_out, h_out, timing=True)
+    ready = [tm.band_ready_ms[b] for b in range(4)]
+    assert ready == sorted(ready) and ready[0] > 0
     ms = plan.time_layer(1, 0, d_in, d_out, iters=5)
     assert ms > 0
     plan.destroy()
