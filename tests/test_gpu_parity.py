@@ -807,3 +807,39 @@ def test_measured_ceilings_are_below_the_published_peaks():
     assert 2000.0 < c.hbm_copy_gbs <= 8000.0
     assert 800.0 < c.mfma_bf16_tflops <= 2520.0
     assert 60.0 < c.mfma_f32_tflops <= 158.5
+
+
+def test_two_party_searched_schedule_full_size(oracle):
+    """The whole loop at the bench's size: the library searches a schedule for the 224 x 224
+    backbone (queued link model, a slow client and a fast server), predicts its completion
+    time, runs it with both parties slowed to the modelled speeds, and the result is the
+    unpartitioned chain's while the measured time is the predicted one."""
+    from oracle import loss
+    chain = workloads.resnet18_chain()
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    shapes = planner.infer_shapes(chain)
+    layers = []
+    for i, L in enumerate(chain.layers):
+        n, c, h, w = shapes[i]
+        flop_row = planner.conv_flop(chain, shapes, i, 1) if L.op != "maxpool" else 40.0 * n * c * w
+        layers.append(loss.LossLayer(n_ops=h, input_from=L.input_from, residual_from=L.residual_from,
+                                     k=L.k[0], s=L.s[0], p=L.p[0], d=L.d[0],
+                                     cm_fixed=5e-5, cm_row=flop_row / 5e10, cr_fixed=1e-5, cr_row=flop_row / 2e12,
+                                     row_bytes=float(n * c * w * 4)))
+    n, c, h, w = chain.in_shape
+    in_row_bytes = float(n * c * w * 4)
+    for bw in (4e6, 40e6):
+        sched, T, viol = lop.lop_loss_solve(layers, h, in_row_bytes, bw, 1e-3, generations=60, seed=3,
+                                            link_model=lop.LOP_LINK_QUEUED)
+        assert viol == 0
+        plan = lop.Plan(chain, t, 1)
+        try:
+            d_in = to_device_nhwc(t.x, chain.dtype)
+            d_out = empty_out(plan.out_shape(), chain.dtype)
+            st = plan.run_two_party(d_in, d_out, sched, bw, 1e-3, layers)
+            got = to_nchw(d_out)
+        finally:
+            plan.destroy()
+        assert rel_err(got, want) <= TOL["f32"]
+        assert T * 1e3 * 0.999 <= st.total_ms <= T * 1e3 * 1.05 + 2.0, (bw, T, st.total_ms)
