@@ -74,15 +74,13 @@ int upload_weights(lop_plan_t* P) {
   P->d_wd.assign(nl, nullptr);
   P->d_wd16.assign(nl, nullptr);
   P->d_bias.assign(nl, nullptr);
-  P->k_pad.assign(nl, 0);
   for (int l = 0; l < nl; ++l) {
     const lop::LayerInfo& L = t.layers[l];
     const lop_layer_t& d = L.d;
     if (d.op == LOP_CONV2D) {
       if (!d.weight) return LOP_ERR_INVALID_ARG;
-      const int kp = lop::conv_k_pad(d.c_in, d.kh, d.kw, t.in.dtype);
+      const int kp = P->k_pad[l];
       const int cp = lop::conv_cout_pad(d.c_out);
-      P->k_pad[l] = kp;
       const size_t esz = t.esz();
       std::vector<unsigned char> host((size_t)cp * kp * esz, 0);
       // OIHW -> [co][ (a*kw + b)*c_in + ci ]
@@ -216,16 +214,18 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
   o.x = slab_of(P, band, L.d.input_from, d_in, d_out);
   o.y = slab_of(P, band, l, d_in, d_out);
   if (L.d.residual_from != LOP_NO_RESIDUAL) o.res = slab_of(P, band, L.d.residual_from, d_in, d_out);
-  o.w = P->d_w[l];
-  o.wd = P->d_wd[l];
-  o.wd16 = P->d_wd16[l];
-  o.bias = P->d_bias[l];
+  if (!P->d_w.empty()) {  // uploaded (a plan-only plan has tables but no device arrays)
+    o.w = P->d_w[l];
+    o.wd = P->d_wd[l];
+    o.wd16 = P->d_wd16[l];
+    o.bias = P->d_bias[l];
+  }
+  o.k_pad = P->k_pad[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
   o.ph = L.d.ph; o.pw = L.d.pw; o.dh = L.d.dh; o.dw = L.d.dw;
   o.act = L.d.act;
   o.out_lo = t.bands[band].compute[l].lo;
   o.out_hi = t.bands[band].compute[l].hi;
-  o.k_pad = P->k_pad[l];
   o.ws = P->ws_of(band);
   return o;
 }
@@ -243,8 +243,8 @@ OpLaunch describe_layer(const lop_plan_s* P, int l) {
   if (L.d.residual_from != LOP_NO_RESIDUAL) o.res.ptr = const_cast<lop_plan_t*>(P);
   if (!P->d_w.empty()) {  // uploaded (not a plan-only plan)
     o.w = P->d_w[l]; o.wd = P->d_wd[l]; o.wd16 = P->d_wd16[l]; o.bias = P->d_bias[l];
-    o.k_pad = P->k_pad[l];
   }
+  o.k_pad = P->k_pad[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
   o.ph = L.d.ph; o.pw = L.d.pw; o.dh = L.d.dh; o.dw = L.d.dw;
   o.act = L.d.act;
@@ -620,6 +620,11 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
   int rc = lop::build_tables(layers, n_layers, in, n_bands, (flags & LOP_FLAG_REUSE) != 0, P->t);
   if (rc != LOP_OK) { delete P; return rc; }
   P->flags = flags;
+  P->k_pad.assign((size_t)n_layers, 0);  // padded reduction length of every dense conv
+  for (int l = 0; l < n_layers; ++l) {
+    const lop_layer_t& d = P->t.layers[l].d;
+    if (d.op == LOP_CONV2D) P->k_pad[l] = lop::conv_k_pad(d.c_in, d.kh, d.kw, in->dtype);
+  }
   find_fused_groups(P);
   size_scratch(P);
   if (!(flags & LOP_FLAG_PLAN_ONLY)) {

@@ -231,3 +231,17 @@ def test_two_party_schedule_is_checked_on_the_host():
         assert code([((2, 8), (0, 3)), ((0, 0), (0, 8))]) == lop.LOP_ERR_NOT_READY    # overlap is fine
     finally:
         lop.lop_plan_destroy(h)
+
+
+def test_kernel_query_on_a_plan_without_device_state():
+    """A plan-only plan has tables but no uploaded weights; the kernel-name query must still
+    answer from the shapes alone (it used to read the missing device arrays)."""
+    h = lop.lop_plan([_layer(c_in=4, c_out=64), _layer(c_in=64, c_out=64, src=0)],
+                     _desc(c=4, h=32, w=32), 2, lop.LOP_FLAG_PLAN_ONLY)
+    try:
+        for band in range(2):
+            for layer in range(2):
+                name, slices = lop.lop_plan_layer_kernel(h, band, layer)
+                assert name.startswith("conv_") and slices >= 1
+    finally:
+        lop.lop_plan_destroy(h)
