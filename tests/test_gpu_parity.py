@@ -848,3 +848,27 @@ def test_two_party_searched_schedule_full_size(oracle):
             plan.destroy()
         assert rel_err(got, want) <= TOL["f32"]
         assert T * 1e3 * 0.998 <= st.total_ms <= T * 1e3 * 1.10 + 5.0, (bw, T, st.total_ms)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_two_party_random_chains(oracle, dtype):
+    """Seeded random chains (odd channel counts, dilation, pools, depthwise, residuals) under
+    random schedules: every kernel choice on arbitrary row intervals of full-height buffers,
+    against the unpartitioned oracle; bytes and messages against the oracle's runtime."""
+    from oracle import two_party
+    rng = np.random.Generator(np.random.PCG64(4321 + (dtype == "bf16")))
+    done = 0
+    while done < 10:
+        chain = _random_conv_chain(rng, dtype)
+        if chain is None:
+            continue
+        t = workloads.make_tensors(chain, zero_bias=False, seed=int(rng.integers(1, 1 << 30)))
+        want = oracle.run_chain(chain, t)
+        sched = workloads.random_schedule(_heights(chain), seed=int(rng.integers(1, 1 << 30)), overlap=2)
+        _, ost = two_party.run(chain, t, sched)
+        got, st = _run_two_party(chain, t, sched)
+        desc = [(L.op, L.c_in, L.c_out, L.k, L.s, L.p, L.d, L.act, L.residual_from) for L in chain.layers]
+        assert rel_err(got, want) <= TOL[dtype], (chain.in_shape, desc, sched)
+        assert st.bytes_to_m == ost.bytes_to("M") and st.bytes_to_r == ost.bytes_to("R"), (desc, sched)
+        assert st.transfers == len(ost.transfers)
+        done += 1
