@@ -90,8 +90,9 @@ typedef struct {
 #define LOP_FLAG_PLAN_ONLY 2u /* integer planning only: touches no GPU, needs no weights;
                                  lop_run_* return LOP_ERR_NOT_READY                      */
 #define LOP_FLAG_DMA_COPY 8u  /* always use hipMemcpyAsync for the band copies; by default a
-                                 mapped pinned host buffer is written by a copy kernel on
-                                 the copy stream                                         */
+                                 mapped pinned host buffer is written by the kernel of the
+                                 band's last layer itself (band outputs up to 256 KiB) or by
+                                 a small copy kernel                                     */
 #define LOP_FLAG_REUSE 16u    /* bands run in order and share per-layer buffers: a band computes,
                                  of every layer, only the rows no earlier band has produced
                                  (no halo recompute; data already on the device is reused,
