@@ -146,15 +146,25 @@ def roofline_of(k, dtype):
                 avg_us=k["avg_us"], launches_per_step=k["launches"])
 
 
+def source_hash():
+    """Hash of the kernel sources: counters taken for other kernels must not be reported."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2507_05829_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        if f.endswith((".hip", ".hpp", ".cpp")):
+            h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(workload, kernel_name):
     """HBM bytes per launch of a kernel from the committed counter summary, or None when
     there is none for this workload or the kernel sources changed since it was taken."""
     path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
     if not os.path.exists(path):
         return None
-    from paper_2507_05829_amd import pmc_traffic
     doc = json.load(open(path))
-    if doc.get("source_hash") != pmc_traffic.source_hash():
+    if doc.get("source_hash") != source_hash():
         return None
     k = doc["kernels"].get(kernel_name)
     if not k or k["fetch_bytes_per_launch"] is None or k["write_bytes_per_launch"] is None:

@@ -86,6 +86,9 @@ typedef struct {
 } lop_timing_t;
 
 /* lop_plan flags */
+#define LOP_FLAG_INDEPENDENT 0u /* the default mode, named: every band recomputes its halo rows
+                                 (local-operation replication, Sec. IV-C), so bands are
+                                 independent of one another and run in any order            */
 #define LOP_FLAG_NO_D2H 1u    /* never copy to the host even if a host pointer is given  */
 #define LOP_FLAG_PLAN_ONLY 2u /* integer planning only: touches no GPU, needs no weights;
                                  lop_run_* return LOP_ERR_NOT_READY                      */
@@ -156,7 +159,10 @@ LOP_API int lop_plan_layer_work(const lop_plan_t* plan, int band, int layer, dou
  * to h_out once the kernels are done. Asynchronous.
  *   d_in   device, whole chain input N x H x W x C; only band_in_rows(band) are read
  *   d_out  device, whole chain output; only band_out_rows(band) are written
- *   h_out  pinned host, whole chain output, or NULL
+ *   h_out  pinned host, whole chain output, or NULL. What kind of memory h_out is (mapped
+ *          pinned, or anything else) is looked up once per address and plan and kept, and a
+ *          captured graph (LOP_FLAG_GRAPH) holds the addresses it was captured with: a buffer
+ *          passed here must stay allocated, and of the same kind, for as long as the plan lives.
  *   compute_stream, copy_stream  hipStream_t or NULL (= the plan's own streams)
  * Bands b and b' with b = b' (mod lanes) share scratch memory: give them the same
  * compute stream (or NULL). Bands of different lanes may run concurrently. */

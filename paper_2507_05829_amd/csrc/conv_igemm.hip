@@ -938,6 +938,7 @@ DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
 template <typename T, int WK, int NT>
 hipError_t launch_direct(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
   dim3 grid((p.M + 31) / 32, (p.C_out + 32 * NT - 1) / (32 * NT), p.splits);
+  if ((int)grid.y * 32 * NT > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;  // unguarded weight loads
   return launch_kernel(conv_direct_kernel<T, WK, NT>, grid, dim3(64 * WK), s, ev, p);
 }
 
@@ -946,6 +947,7 @@ hipError_t launch_direct_any(const ConvParams& p, const DirectChoice& d, hipStre
                              KernelEvents* ev) {
   if (d.narrow) {
     dim3 grid((p.M + 15) / 16, (p.C_out + 15) / 16);
+    if ((int)grid.y * 16 > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
     return launch_kernel(conv_narrow_kernel<T>, grid, dim3(64 * kNarrowWaves), s, ev, p);
   }
   if (d.nt == 2) {
@@ -990,7 +992,8 @@ Choice choose(const ConvParams& p, int dtype) {
   };
   Choice c;
   constexpr int kKE16 = 8;  // bf16 elements per 16-byte vector
-  if (dtype == LOP_BF16 && p.C_in % kKE16 == 0 && p.C_out % kKE16 == 0 && blocks(256, 256) >= kComputeUnits &&
+  if (dtype == LOP_BF16 && p.C_out > kConvCoutPad && p.C_in % kKE16 == 0 && p.C_out % kKE16 == 0 &&
+      blocks(256, 256) >= kComputeUnits &&
       big_tile_pays(blocks(256, 256), blocks(128, 128))) {
     c = {S256x256, 256, 256, 1, p.k_pad / (kBigBKB / 2)};
     return c;
@@ -1023,6 +1026,8 @@ template <typename T, int BM, int BN, int WM, int WN>
 hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, KernelEvents* ev) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
   const dim3 block(64 * WM * WN);
+  // weight loads are unguarded: the channel tiles must end inside the padded packing
+  if ((int)grid.y * BN > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
   const hipError_t e =
       vec_a ? launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>, grid, block, s, ev, p)
             : launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>, grid, block, s, ev, p);
@@ -1054,6 +1059,7 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
   if (c.shape == S256x256) {
     if constexpr (sizeof(T) == 2) {
       dim3 grid((p.M + 255) / 256, (p.C_out + 255) / 256, 1);
+      if ((int)grid.y * 256 > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
       return launch_kernel(conv_igemm_kernel<T, 256, 256, 2, 4, kBigBKB, kStages, true>, grid, dim3(512), s, ev, p);
     }
     return hipErrorInvalidValue;

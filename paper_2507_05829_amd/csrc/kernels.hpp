@@ -34,16 +34,23 @@ struct OpLaunch {
 };
 
 // Dense conv weights are packed as [c_out_pad][k_pad], k = (a*kw + b)*c_in + ci, zero
-// padded so the kernel never guards weight loads.
+// padded so the kernel never guards weight loads (every launch checks on the host that its
+// channel tiles end inside c_out_pad).
 // Layers whose c_in and c_out are multiples of the 16-byte vector get a second packing in
 // MFMA operand order for the small-layer kernel: [c_out_pad / 32][k_pad / MK][64 lanes] x 16
 // bytes, MK = 2 vectors of elements; lane = half*32 + (co % 32) holds
 // w[co][step*MK + half*KE ... + KE) of the first packing. A third one serves 16 x 16 tiles:
 // [c_out_pad / 16][k_pad / MK16][64 lanes] x 16 bytes, MK16 = 4 vectors, lane = quarter*16 +
 // (co % 16) holds w[co][step*MK16 + quarter*KE ... + KE).
+// The row count is padded to the widest channel tile that can take the layer: 128, and 256 once
+// there are more than 128 channels (the 256-wide tile is never chosen below that), so the last
+// channel tile of any kernel reads rows that exist.
 constexpr int kConvCoutPad = 128;
 int conv_k_pad(int c_in, int kh, int kw, int dtype);
-inline int conv_cout_pad(int c_out) { return (c_out + kConvCoutPad - 1) / kConvCoutPad * kConvCoutPad; }
+inline int conv_cout_pad(int c_out) {
+  const int unit = c_out > kConvCoutPad ? 2 * kConvCoutPad : kConvCoutPad;
+  return (c_out + unit - 1) / unit * unit;
+}
 
 // Bytes of split-K scratch the dense conv launch needs (0: none).
 size_t conv_workspace_bytes(const OpLaunch& L);

@@ -193,7 +193,9 @@ lop::Slab slab_of(const lop_plan_t* P, int band, int tensor, const void* d_in, v
     if (tensor == nl - 1) {
       s.ptr = d_out; s.row0 = 0; s.rows = s.h;
     } else {
-      s.ptr = (char*)P->arena_of(band) + P->slab_off[band][tensor];
+      // (no arena yet while the plan is being sized, and none at all in a plan-only plan)
+      char* const arena = (char*)P->arena_of(band);
+      s.ptr = arena ? arena + P->slab_off[band][tensor] : nullptr;
       if (t.reuse) {
         s.row0 = 0; s.rows = s.h;
       } else {
@@ -572,16 +574,17 @@ int enqueue_chain_reuse(lop_plan_t* P, const void* d_in, void* d_out, void* h_ou
 
 int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms) {
   const int lane = P->t.reuse ? P->cur_lane : -1;
-  for (const auto& g : P->graphs)
-    if (g.d_in == d_in && g.d_out == d_out && g.h_out == h_out && g.lane == lane) {
-      LOP_HIP(hipGraphLaunch(g.exec, ms));
-      return LOP_OK;
-    }
-  // an eager run may still have copies in flight that later eager calls would wait for
+  // an eager run may still have copies of the output rows in flight (on a copy stream that the
+  // graph's stream is not ordered behind): a replay, and the first capture, wait for them
   for (int b = 0; b < P->t.n_bands; ++b)
     if (P->copied_valid[b]) {
       LOP_HIP(hipStreamWaitEvent(ms, P->ev_copied[b], 0));
       P->copied_valid[b] = 0;
+    }
+  for (const auto& g : P->graphs)
+    if (g.d_in == d_in && g.d_out == d_out && g.h_out == h_out && g.lane == lane) {
+      LOP_HIP(hipGraphLaunch(g.exec, ms));
+      return LOP_OK;
     }
   if (h_out) (void)device_view_of_host(P, h_out);  // query before capture starts
   hipGraph_t graph = nullptr;
@@ -662,12 +665,14 @@ int lop_plan_rowwise(const lop_rowwise_t* layers, int n_layers, int m, int k, in
 
 void lop_plan_destroy(lop_plan_t* P) {
   if (!P) return;
-  for (Lane& L : P->lanes) {
-    if (L.stream) (void)hipStreamSynchronize(L.stream);
-    if (L.copy) (void)hipStreamSynchronize(L.copy);
+  if (P->ready || P->device >= 0) {
+    // Everything below belongs to the plan's device, and work that uses the plan's memory may
+    // sit on streams the plan does not own (a caller's compute or copy stream, which may not
+    // exist any more, so it is not touched through its handle): wait for the whole device.
+    int cur = -1;
+    if (hipGetDevice(&cur) == hipSuccess && cur != P->device && P->device >= 0) (void)hipSetDevice(P->device);
+    (void)hipDeviceSynchronize();
   }
-  if (P->s_main) (void)hipStreamSynchronize(P->s_main);
-  if (P->s_copy) (void)hipStreamSynchronize(P->s_copy);
   for (void* w : P->d_w) if (w) (void)hipFree(w);
   for (void* w : P->d_wd) if (w) (void)hipFree(w);
   for (void* w : P->d_wd16) if (w) (void)hipFree(w);
@@ -742,7 +747,7 @@ int lop_plan_stats(const lop_plan_t* P, double* useful, double* executed, size_t
     u += P->t.layer_flop(l, P->t.layers[l].h_out);
     for (int b = 0; b < P->t.n_bands; ++b) {
       double f = 0.0, by = 0.0;
-      if (P->fuse_head.empty()) {  // plan-only: no kernels are chosen
+      if (P->flags & LOP_FLAG_PLAN_ONLY) {  // no kernels are chosen, so no launches are fused
         const lop_rows_t r = P->t.bands[b].compute[l];
         if (r.hi > r.lo) f = P->t.layer_flop(l, r.hi - r.lo);
       } else {
@@ -762,7 +767,7 @@ int lop_plan_layer_work(const lop_plan_t* P, int band, int layer, double* flop, 
   if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
     return LOP_ERR_BAND_RANGE;
   double f = 0.0, by = 0.0;
-  if (P->fuse_head.empty()) {  // plan-only: no kernels are chosen
+  if (P->flags & LOP_FLAG_PLAN_ONLY) {  // no kernels are chosen, so no launches are fused
     const lop_rows_t r = P->t.bands[band].compute[layer];
     f = r.hi > r.lo ? P->t.layer_flop(layer, r.hi - r.lo) : 0.0;
     by = P->t.layer_bytes(band, layer);
@@ -891,7 +896,9 @@ int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, 
     return LOP_ERR_BAND_RANGE;
   name[0] = 0;
   int slices = 0;
-  if (!P->fuse_head.empty()) slices = describe_layer_launch(P, band, layer, name, size);
+  // (a plan-only plan has uploaded no weights, and which kernel takes a layer depends on the
+  // packings that exist: it names none rather than a kernel the ready plan would not launch)
+  if (!(P->flags & LOP_FLAG_PLAN_ONLY)) slices = describe_layer_launch(P, band, layer, name, size);
   if (k_slices) *k_slices = slices;
   return LOP_OK;
 }

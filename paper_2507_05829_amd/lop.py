@@ -33,6 +33,7 @@ LOP_INPUT, LOP_NO_RESIDUAL = -1, -2
 LOP_MAX_BANDS = 64
 LOP_FLAG_NO_D2H, LOP_FLAG_PLAN_ONLY, LOP_FLAG_GRAPH, LOP_FLAG_DMA_COPY = 1, 2, 4, 8
 LOP_FLAG_REUSE = 16
+LOP_FLAG_INDEPENDENT = 0
 LOP_FLAG_NO_FUSE = 32
 LOP_LINK_INDEPENDENT, LOP_LINK_QUEUED = 0, 1
 

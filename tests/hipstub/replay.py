@@ -1,0 +1,150 @@
+"""Replays the library's host code paths against the stand-in HIP runtime under the sanitizers
+(see build_stub.py). Run as `python replay.py <stub dir>` with the AddressSanitizer runtime
+preloaded; exits non-zero on any sanitizer report, stub misuse report or leaked HIP object.
+
+What runs: the create / run / destroy sequences of the GPU parity suite (the same seeded
+random chains, all four (mode, type) sets, and the named workloads at reduced size), with
+"device" buffers that are plain host arrays and kernels that do nothing, so only the host code
+is exercised: planning, weight packing and upload, lanes, events, graph capture and replay,
+the copy paths (mapped pinned, pageable, DMA flag), timing, the measurement aids, the
+two-party runtime, the entry point that allocates nothing, and the teardown.
+"""
+import ctypes
+import os
+import sys
+import types
+
+stub_dir = sys.argv[1]
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
+sys.path[:0] = [stub_dir, ROOT, os.path.dirname(HERE)]
+sys.modules["torch"] = types.ModuleType("torch")   # the binding imports it only for its runtime
+
+import numpy as np  # noqa: E402
+
+import workloads  # noqa: E402
+from paper_2507_05829_amd import lop  # noqa: E402
+from random_chains import random_conv_chain  # noqa: E402
+
+assert lop.LIB_PATH.startswith(stub_dir), lop.LIB_PATH
+stub = ctypes.CDLL(os.path.join(stub_dir, "paper_2507_05829_amd", "libhipstub.so"))
+stub.hipstub_live.restype = ctypes.c_long
+stub.hipstub_launches.restype = ctypes.c_long
+stub.hipstub_pin.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+stub.hipstub_unpin.argtypes = [ctypes.c_void_p]
+KINDS = ["stream", "event", "graph", "graph exec", "allocation"]
+
+
+def buffers(chain, plan, pinned=True):
+    n, c, h, w = chain.in_shape
+    esz = 2 if chain.dtype == "bf16" else 4
+    d_in = np.zeros(n * c * h * w * esz, np.uint8)
+    on, oc, oh, ow = plan.out_shape()
+    d_out = np.zeros(on * oc * oh * ow * esz, np.uint8)
+    h_out = np.zeros(on * oc * oh * ow * esz, np.uint8)
+    if pinned:
+        stub.hipstub_pin(h_out.ctypes.data, h_out.nbytes)
+    return d_in, d_out, h_out
+
+
+def release(h_out):
+    stub.hipstub_unpin(h_out.ctypes.data)
+
+
+def run_like_the_parity_suite(chain, t, flags):
+    plan = lop.Plan(chain, t, None, flags)
+    try:
+        d_in, d_out, h_out = buffers(chain, plan)
+        plan.run_chain(d_in, d_out, h_out)
+        plan.synchronize()
+        release(h_out)
+    finally:
+        plan.destroy()
+
+
+def random_chain_sets():
+    n = 0
+    for dtype in ("f32", "bf16"):
+        for reuse in (0, 1):
+            rng = np.random.Generator(np.random.PCG64(1234 + 17 * reuse + (dtype == "bf16")))
+            done = 0
+            while done < 24:
+                chain = random_conv_chain(rng, dtype)
+                if chain is None:
+                    continue
+                t = workloads.make_tensors(chain, zero_bias=False, seed=int(rng.integers(1, 1 << 30)))
+                run_like_the_parity_suite(chain, t, lop.LOP_FLAG_REUSE if reuse else 0)
+                done += 1
+                n += 1
+    return n
+
+
+def named_workloads():
+    n = 0
+    scaled = [workloads.tiny_chain(), workloads.resnet18_chain(h=64, w=48), workloads.vgg16_chain(h=64, w=64),
+              workloads.detector_chain(h=96, w=64), workloads.mbv2_chain(h=32, w=32, n=2, n_bands=4)]
+    for chain in scaled:
+        t = workloads.make_tensors(chain, zero_bias=False)
+        for flags in (0, lop.LOP_FLAG_REUSE, lop.LOP_FLAG_GRAPH, lop.LOP_FLAG_GRAPH | lop.LOP_FLAG_REUSE,
+                      lop.LOP_FLAG_DMA_COPY, lop.LOP_FLAG_NO_D2H, lop.LOP_FLAG_NO_FUSE, lop.LOP_FLAG_LANES(1),
+                      lop.LOP_FLAG_LANES(1) | lop.LOP_FLAG_GRAPH, lop.LOP_FLAG_LANES(7) | lop.LOP_FLAG_REUSE):
+            plan = lop.Plan(chain, t, None, flags)
+            d_in, d_out, h_out = buffers(chain, plan)
+            pageable = np.zeros_like(h_out)
+            for rep in range(3):                      # graph: capture once, replay twice
+                plan.run_chain(d_in, d_out, h_out)
+                plan.synchronize()
+            plan.run_chain(d_in, d_out, pageable)     # copy engines
+            plan.run_chain(d_in, d_out, None)
+            tm = plan.run_chain(d_in, d_out, h_out, timing=True)
+            assert tm.n_bands == plan.n_bands
+            order = range(plan.n_bands) if flags & lop.LOP_FLAG_REUSE else reversed(range(plan.n_bands))
+            for b in order:
+                plan.run_band(b, d_in, d_out, h_out)
+            plan.synchronize()
+            plan.profile_chain(d_in, d_out, 2)
+            plan.copy_chain(d_out, h_out)
+            plan.time_layer(0, plan.n_layers - 1, d_in, d_out, 2)
+            for b in range(plan.n_bands):
+                for l in range(plan.n_layers):
+                    plan.layer_kernel(b, l)
+                    plan.layer_work(b, l)
+            plan.stats()
+            if hasattr(lop, "lop_run_chain_static") and not flags & lop.LOP_FLAG_REUSE:
+                lop.lop_run_chain_static(plan.handle, d_in, d_out, None)
+                plan.synchronize()
+            if not flags:
+                heights = [plan.layer_shape(l)[2] for l in range(plan.n_layers)]
+                sched = workloads.random_schedule(heights, seed=5)
+                plan.run_two_party(d_in, d_out, [(a["M"], a["R"]) for a in sched], 1e12, 0.0)
+            release(h_out)
+            plan.destroy()
+            n += 1
+    # row-wise chain (Eq. 1)
+    rc = workloads.mlp_chain(m=300, k=64, hidden=128)
+    rt = workloads.make_row_tensors(rc)
+    plan = lop.Plan.rowwise(rc, rt)
+    esz = 2 if rc.dtype == "bf16" else 4
+    d_in = np.zeros(rc.m * rc.k * esz, np.uint8)
+    on, oc, oh, ow = plan.out_shape()
+    d_out = np.zeros(on * oc * oh * ow * esz, np.uint8)
+    plan.run_chain(d_in, d_out, None)
+    plan.synchronize()
+    plan.destroy()
+    return n + 1
+
+
+def main():
+    total = random_chain_sets()
+    print("random chains replayed:", total, flush=True)
+    total += named_workloads()
+    print("plans replayed:", total, "kernel launches:", stub.hipstub_launches(), flush=True)
+    leaks = {k: stub.hipstub_live(i) for i, k in enumerate(KINDS) if stub.hipstub_live(i)}
+    if leaks:
+        print("LEAKED HIP objects after every plan was destroyed:", leaks, flush=True)
+        sys.exit(1)
+    print("REPLAY OK", flush=True)
+
+
+if __name__ == "__main__":
+    main()

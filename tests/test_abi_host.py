@@ -234,14 +234,19 @@ def test_two_party_schedule_is_checked_on_the_host():
 
 
 def test_kernel_query_on_a_plan_without_device_state():
-    """A plan-only plan has tables but no uploaded weights; the kernel-name query must still
-    answer from the shapes alone (it used to read the missing device arrays)."""
+    """A plan-only plan has tables but no uploaded weights. Which kernel takes a layer depends
+    on the weight packings that exist, so such a plan names no kernel (rather than one that the
+    same chain's ready plan would not launch), and its work counts are those of the layers."""
     h = lop.lop_plan([_layer(c_in=4, c_out=64), _layer(c_in=64, c_out=64, src=0)],
                      _desc(c=4, h=32, w=32), 2, lop.LOP_FLAG_PLAN_ONLY)
     try:
         for band in range(2):
             for layer in range(2):
                 name, slices = lop.lop_plan_layer_kernel(h, band, layer)
-                assert name.startswith("conv_") and slices >= 1
+                assert name == "" and slices == 0
+                flop, byts = lop.lop_plan_layer_work(h, band, layer)
+                lo, hi = lop.lop_plan_band_compute_rows(h, band, layer)
+                c_in = 4 if layer == 0 else 64
+                assert flop == 2.0 * (hi - lo) * 32 * 64 * c_in * 9 and byts > 0
     finally:
         lop.lop_plan_destroy(h)

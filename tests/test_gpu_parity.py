@@ -8,6 +8,7 @@ import torch
 import workloads
 from oracle import planner
 from gpu_util import TOL, empty_out, rel_err, run_gpu, to_device_nhwc, to_nchw
+from random_chains import random_conv_chain as _random_conv_chain
 from paper_2507_05829_amd import lop
 
 pytestmark = pytest.mark.gpu
@@ -551,54 +552,6 @@ def test_rowwise_full_size_sampled_rows(oracle):
 
 # ---- seeded random shapes: every kernel choice the library can make, against the oracle ----
 
-def _random_conv_chain(rng, dtype):
-    """Two to four layers with random (valid) hyper-parameters, channel counts that are and are
-    not multiples of the vector width, an optional residual and pool, random band count."""
-    vec = 8 if dtype == "bf16" else 4
-    n = int(rng.choice([1, 1, 2, 3]))
-    h, w = int(rng.integers(9, 40)), int(rng.integers(5, 33))
-    c = int(rng.choice([3, vec, 2 * vec, 24, 5 * vec, 64, 96]))
-    chain = workloads.Chain("rand", (n, c, h, w), dtype, int(rng.integers(1, 7)))
-    for _ in range(int(rng.integers(2, 5))):
-        kind = rng.choice(["conv", "conv", "conv", "dw", "pool", "pw"])
-        hh = workloads_h(chain)
-        if kind == "conv":
-            k = int(rng.choice([1, 2, 3, 3, 5])); d = int(rng.choice([1, 1, 2]))
-            p = int(rng.integers(0, d * (k - 1) // 2 + 1)); s_ = int(rng.choice([1, 1, 2]))
-            if hh + 2 * p - d * (k - 1) < 2 or min_w(chain) + 2 * p - d * (k - 1) < 2:
-                continue
-            c_out = int(rng.choice([vec, 2 * vec, 6, 40, 64, 72, 128]))
-            same = (c_out == c and s_ == 1 and 2 * p == d * (k - 1))
-            res = len(chain.layers) - 1 if (same and rng.random() < 0.5) else workloads.NO_RESIDUAL
-            chain.add(workloads.CONV, c, c_out, k, s_, p, d, str(rng.choice(["none", "relu", "relu6"])),
-                      residual_from=res)
-            c = c_out
-        elif kind == "pw":
-            c_out = int(rng.choice([32, 64, 96, 192])) if dtype == "bf16" else int(rng.choice([vec, 48]))
-            chain.add(workloads.CONV, c, c_out, 1, 1, 0, 1, str(rng.choice(["none", "relu6"])))
-            c = c_out
-        elif kind == "dw":
-            s_ = int(rng.choice([1, 2]))
-            if hh < 3 or min_w(chain) < 3:
-                continue
-            chain.add(workloads.DWCONV, c, c, 3, s_, 1, 1, str(rng.choice(["relu6", "none"])))
-        else:
-            if hh < 4 or min_w(chain) < 4:
-                continue
-            chain.add(workloads.MAXPOOL, c, c, 2, 2, 0, 1, "none", has_bias=False)
-    return chain if chain.layers else None
-
-
-def workloads_h(chain):
-    from oracle import planner
-    return planner.infer_shapes(chain)[-1][2] if chain.layers else chain.in_shape[2]
-
-
-def min_w(chain):
-    from oracle import planner
-    return planner.infer_shapes(chain)[-1][3] if chain.layers else chain.in_shape[3]
-
-
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("reuse", [0, 1])
 def test_random_chains(oracle, dtype, reuse):
@@ -774,6 +727,30 @@ def test_big_tile_rowwise_ragged(oracle):
     np.testing.assert_array_equal(dev, host)
     assert rel_err(dev, want) <= TOL["bf16"]
     rng = np.random.Generator(np.random.PCG64(12))
+    ti = workloads.Tensors(rng.integers(-2, 3, (m, k)).astype(np.float32),
+                           [rng.integers(-1, 2, (n, k)).astype(np.float32)],
+                           [rng.integers(-3, 4, n).astype(np.float32)])
+    want = oracle.run_row_chain(chain, ti)
+    assert np.abs(want).max() <= 256
+    dev, _, _ = _run_rows(chain, ti)
+    np.testing.assert_array_equal(dev, want)
+
+
+def test_big_tile_last_channel_tile_past_the_channels(oracle):
+    """384 output channels: the second 256-wide channel tile covers channels 256..511, so the
+    packed weights must hold rows up to 512 (regression: they were padded to 384 and that tile
+    read past the allocation). Ragged in both directions; random values, then small integers
+    bit for bit."""
+    m, k, n = 128 * 256 - 37, 96, 384
+    chain = workloads.RowChain("big384", m, k, "bf16", 1)
+    chain.add(n, "relu")
+    t = workloads.make_row_tensors(chain, zero_bias=False, seed=32)
+    want = oracle.run_row_chain(chain, t)
+    dev, host, names = _run_rows(chain, t)
+    assert any(nm.startswith("conv_igemm_kernel<__bf16, 256, 256, 2, 4, 64") for nm in names), names
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL["bf16"]
+    rng = np.random.Generator(np.random.PCG64(13))
     ti = workloads.Tensors(rng.integers(-2, 3, (m, k)).astype(np.float32),
                            [rng.integers(-1, 2, (n, k)).astype(np.float32)],
                            [rng.integers(-3, 4, n).astype(np.float32)])

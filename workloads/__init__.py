@@ -171,10 +171,10 @@ CONFIGS = {
 # --------------------------------------------------------------------------- tensors
 
 def to_bf16_values(a: np.ndarray) -> np.ndarray:
-    """Round float32 values to the nearest bfloat16 (ties to even), keep float32."""
-    import torch
-    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
-    return t.to(torch.bfloat16).to(torch.float32).numpy()
+    """Round finite float32 values to the nearest bfloat16 (ties to even), keep float32."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(a))
 
 
 def bf16_bits(a: np.ndarray) -> np.ndarray:
