@@ -109,6 +109,10 @@ typedef struct {
                                  tensors nobody else reads (an inverted-residual block) run as
                                  one launch that keeps the expanded tensor on chip; results
                                  agree with the layer-by-layer path to fp32 summation order */
+#define LOP_FLAG_POISON_SCRATCH 64u /* debug aid: before a band's kernels (reuse mode: before a chain's
+                                 first band) its scratch slabs and split-K workspace are filled
+                                 with NaN bit patterns, so any read of a scratch row that the
+                                 band's own launches did not write first poisons the output  */
 #define LOP_FLAG_LANES(n) (((unsigned)(n) & 0xffu) << 8) /* bands are dealt round robin to n
                                  compute streams ("lanes", each with its own scratch) that run
                                  concurrently; 0 = LOP_DEFAULT_LANES, capped at the number of
@@ -146,7 +150,8 @@ LOP_API int lop_plan_band_layer_rows(const lop_plan_t* plan, int band, int layer
 LOP_API int lop_plan_band_compute_rows(const lop_plan_t* plan, int band, int layer, lop_rows_t* rows);
 
 /* Work counts: operations of the whole layers (useful) and summed over the bands'
- * intervals (executed; > useful where halos are recomputed); bytes of device scratch. */
+ * intervals (executed; > useful where halos are recomputed); bytes of device scratch one lane
+ * holds (the slabs of one band plus the largest split-K workspace of a launch). */
 LOP_API int lop_plan_stats(const lop_plan_t* plan, double* useful_flop, double* executed_flop,
                    size_t* scratch_bytes);
 /* Per layer and band: operations executed and algorithmic bytes moved (rows read of the

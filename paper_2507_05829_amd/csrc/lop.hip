@@ -19,6 +19,7 @@ hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, KernelEvents
 hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
 hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
                             hipStream_t stream);
+hipError_t launch_fill_words(void* dst, size_t bytes, unsigned word, hipStream_t stream);
 
 hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
 bool mbconv_applies(const OpLaunch& e, const OpLaunch& d, const OpLaunch& p);
@@ -95,7 +96,7 @@ int upload_weights(lop_plan_t* P) {
       LOP_HIP(hipMalloc(&P->d_w[l], host.size()));
       LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size(), hipMemcpyHostToDevice));
       const int ke = 16 / (int)esz;
-      if (d.c_in % ke == 0 && d.c_out % ke == 0) {
+      if (P->has_wd[l]) {
         // the same values in MFMA operand order: [co / 32][step][half*32 + co % 32] x 16 B
         std::vector<unsigned char> ord(host.size());
         const size_t steps = (size_t)kp / (2 * ke);
@@ -108,7 +109,7 @@ int upload_weights(lop_plan_t* P) {
             }
         LOP_HIP(hipMalloc(&P->d_wd[l], ord.size()));
         LOP_HIP(hipMemcpy(P->d_wd[l], ord.data(), ord.size(), hipMemcpyHostToDevice));
-        if (kp % (4 * ke) == 0) {
+        if (P->has_wd16[l]) {
           // ... and in the order of 16 x 16 tiles: [co / 16][step][quarter*16 + co % 16] x 16 B
           const size_t steps16 = (size_t)kp / (4 * ke);
           for (int co = 0; co < cp; ++co)
@@ -178,6 +179,23 @@ void size_scratch(lop_plan_t* P) {
   P->arena_bytes = worst;
 }
 
+lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in, void* d_out);
+
+// Largest split-K workspace any launch of the plan needs (the launch descriptors only need
+// sizes here, not the scratch addresses).
+void size_workspace(lop_plan_t* P) {
+  P->conv_ws_bytes = 0;
+  for (int b = 0; b < P->t.n_bands; ++b)
+    for (int l = 0; l < P->t.n_layers(); ++l) {
+      if (P->t.layers[l].d.op != LOP_CONV2D || P->fused_away[l] || P->fuse_head[l] >= 0) continue;
+      const lop_rows_t rr = P->t.bands[b].compute[l];
+      if (rr.hi <= rr.lo) continue;
+      const lop::OpLaunch o = make_launch(P, b, l, nullptr, nullptr);
+      const size_t need = lop::pointwise_applies(o) ? 0 : lop::conv_workspace_bytes(o);
+      P->conv_ws_bytes = std::max(need, P->conv_ws_bytes);
+    }
+}
+
 lop::Slab slab_of(const lop_plan_t* P, int band, int tensor, const void* d_in, void* d_out) {
   const lop::Tables& t = P->t;
   const int nl = t.n_layers();
@@ -221,6 +239,11 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
     o.wd = P->d_wd[l];
     o.wd16 = P->d_wd16[l];
     o.bias = P->d_bias[l];
+  } else {
+    // not uploaded (yet): the kernel choice only asks which packings exist, so a marker that
+    // is never dereferenced stands for each that upload_weights would make
+    o.wd = P->has_wd[l] ? (const void*)P : nullptr;
+    o.wd16 = P->has_wd16[l] ? (const void*)P : nullptr;
   }
   o.k_pad = P->k_pad[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
@@ -245,6 +268,9 @@ OpLaunch describe_layer(const lop_plan_s* P, int l) {
   if (L.d.residual_from != LOP_NO_RESIDUAL) o.res.ptr = const_cast<lop_plan_t*>(P);
   if (!P->d_w.empty()) {  // uploaded (not a plan-only plan)
     o.w = P->d_w[l]; o.wd = P->d_wd[l]; o.wd16 = P->d_wd16[l]; o.bias = P->d_bias[l];
+  } else {
+    o.wd = P->has_wd[l] ? (const void*)P : nullptr;
+    o.wd16 = P->has_wd16[l] ? (const void*)P : nullptr;
   }
   o.k_pad = P->k_pad[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
@@ -366,9 +392,25 @@ void* direct_host_target(lop_plan_t* P, int band, void* h_out) {
   return device_view_of_host(P, h_out);
 }
 
+bool band_empty(const lop_plan_t* P, int band) {
+  const lop_rows_t r = P->t.bands[band].need[P->t.n_layers()];
+  return r.hi <= r.lo;
+}
+
 int enqueue_band_kernels(lop_plan_t* P, int band, const void* d_in, void* d_out, hipStream_t cs,
                          void* y2 = nullptr) {
   const int nl = P->t.n_layers();
+  if (P->flags & LOP_FLAG_POISON_SCRATCH) {
+    // Debug aid: every scratch byte the band could read is NaN (all bits set, in both storage
+    // types) unless this band's own launches write it first, so a kernel that reads a row outside
+    // the intervals the plan gave it shows up in the output. In reuse mode earlier bands' rows
+    // are read on purpose: the slabs are poisoned once, before the chain's first band.
+    bool first = true;
+    for (int b = 0; b < band; ++b) first = first && band_empty(P, b);
+    if (!P->t.reuse || first)
+      LOP_HIP(lop::launch_fill_words(P->arena_of(band), align_up(P->arena_bytes, 256), 0xFFFFFFFFu, cs));
+    LOP_HIP(lop::launch_fill_words(P->ws_of(band), P->conv_ws_bytes / 16 * 16, 0xFFFFFFFFu, cs));
+  }
   for (int l = 0; l < nl; ++l)
     LOP_HIP(launch_layer(P, band, l, d_in, d_out, cs, nullptr, l == nl - 1 ? y2 : nullptr));
   return LOP_OK;
@@ -431,11 +473,6 @@ int ensure_timing_events(lop_plan_t* P) {
   return LOP_OK;
 }
 
-bool band_empty(const lop_plan_t* P, int band) {
-  const lop_rows_t r = P->t.bands[band].need[P->t.n_layers()];
-  return r.hi <= r.lo;
-}
-
 int setup_device(lop_plan_t* P) {
   LOP_HIP(hipGetDevice(&P->device));
   int rc = upload_weights(P);
@@ -447,18 +484,8 @@ int setup_device(lop_plan_t* P) {
   if (want == 0) want = LOP_DEFAULT_LANES;
   const int n_lanes = P->t.reuse ? std::max(1, want) : std::max(1, std::min(want, live));
   P->lanes.assign(n_lanes, Lane{});
-  // the launch descriptors below only need sizes, not the scratch addresses
-  for (int b = 0; b < nb; ++b)
-    for (int l = 0; l < P->t.n_layers(); ++l) {
-      if (P->t.layers[l].d.op != LOP_CONV2D) continue;
-      const lop_rows_t rr = P->t.bands[b].compute[l];
-      if (rr.hi <= rr.lo) continue;
-      const lop::OpLaunch o = make_launch(P, b, l, nullptr, nullptr);
-      const size_t need = lop::pointwise_applies(o) ? 0 : lop::conv_workspace_bytes(o);
-      P->conv_ws_bytes = std::max(need, P->conv_ws_bytes);
-    }
   for (Lane& L : P->lanes) {
-    if (P->arena_bytes) LOP_HIP(hipMalloc(&L.arena, P->arena_bytes));
+    if (P->arena_bytes) LOP_HIP(hipMalloc(&L.arena, align_up(P->arena_bytes, 256)));
     if (P->conv_ws_bytes) {
       LOP_HIP(hipMalloc(&L.conv_ws, P->conv_ws_bytes));
     }
@@ -624,12 +651,19 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
   if (rc != LOP_OK) { delete P; return rc; }
   P->flags = flags;
   P->k_pad.assign((size_t)n_layers, 0);  // padded reduction length of every dense conv
+  P->has_wd.assign((size_t)n_layers, 0);
+  P->has_wd16.assign((size_t)n_layers, 0);
+  const int ke = 16 / (int)P->t.esz();
   for (int l = 0; l < n_layers; ++l) {
     const lop_layer_t& d = P->t.layers[l].d;
-    if (d.op == LOP_CONV2D) P->k_pad[l] = lop::conv_k_pad(d.c_in, d.kh, d.kw, in->dtype);
+    if (d.op != LOP_CONV2D) continue;
+    P->k_pad[l] = lop::conv_k_pad(d.c_in, d.kh, d.kw, in->dtype);
+    P->has_wd[l] = d.c_in % ke == 0 && d.c_out % ke == 0;
+    P->has_wd16[l] = P->has_wd[l] && P->k_pad[l] % (4 * ke) == 0;
   }
   find_fused_groups(P);
   size_scratch(P);
+  size_workspace(P);
   if (!(flags & LOP_FLAG_PLAN_ONLY)) {
     rc = setup_device(P);
     if (rc != LOP_OK) { lop_plan_destroy(P); return rc; }
@@ -758,7 +792,7 @@ int lop_plan_stats(const lop_plan_t* P, double* useful, double* executed, size_t
   }
   if (useful) *useful = u;
   if (executed) *executed = e;
-  if (scratch) *scratch = P->arena_bytes;
+  if (scratch) *scratch = align_up(P->arena_bytes, 256) + P->conv_ws_bytes;
   return LOP_OK;
 }
 

@@ -45,6 +45,7 @@ struct lop_plan_s {
   std::vector<char> fused_away;
   std::vector<float*> d_bias;  // per layer bias (device) or nullptr
   std::vector<int> k_pad;
+  std::vector<char> has_wd, has_wd16;  // which of the two operand-order packings a layer gets
   size_t conv_ws_bytes = 0;
   size_t arena_bytes = 0;
   std::vector<std::vector<size_t>> slab_off;  // [band][layer] byte offset into a lane's arena
@@ -75,8 +76,12 @@ struct lop_plan_s {
   int lane_index(int band) const { return t.reuse ? cur_lane : band % (int)lanes.size(); }
   Lane& lane_of(int band) { return lanes[lane_index(band)]; }
   const Lane& lane_of(int band) const { return lanes[lane_index(band)]; }
-  void* arena_of(int band) const { return lanes.empty() ? nullptr : lane_of(band).arena; }
-  void* ws_of(int band) const { return lanes.empty() ? nullptr : lane_of(band).conv_ws; }
+  void* arena_of(int band) const {
+    return lanes.empty() ? nullptr : lane_of(band).arena;
+  }
+  void* ws_of(int band) const {
+    return lanes.empty() ? nullptr : lane_of(band).conv_ws;
+  }
 };
 
 namespace lop {

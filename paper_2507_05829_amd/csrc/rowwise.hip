@@ -347,7 +347,22 @@ __global__ __launch_bounds__(256) void copy_rows_kernel(char* __restrict__ dst,
       dst[i * pitch + j] = src[i * pitch + j];
   }
 }
+// Fills `bytes` (a multiple of 16) with one 32-bit pattern: the debug poisoning of scratch
+// memory (a kernel, not a memset, so that it may be captured into a graph).
+__global__ __launch_bounds__(256) void fill_words_kernel(uint4* __restrict__ dst, size_t vecs, unsigned word) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  const uint4 v = make_uint4(word, word, word, word);
+  for (size_t j = (size_t)blockIdx.x * 256 + threadIdx.x; j < vecs; j += stride) dst[j] = v;
+}
 }  // namespace
+
+hipError_t launch_fill_words(void* dst, size_t bytes, unsigned word, hipStream_t stream) {
+  const size_t vecs = bytes / 16;
+  if (!dst || vecs == 0) return hipSuccess;
+  const unsigned grid = (unsigned)std::min<size_t>((vecs + 255) / 256, 2048);
+  hipLaunchKernelGGL(fill_words_kernel, dim3(grid), dim3(256), 0, stream, (uint4*)dst, vecs, word);
+  return hipGetLastError();
+}
 
 hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
                             hipStream_t stream) {

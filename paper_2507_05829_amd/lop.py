@@ -35,6 +35,7 @@ LOP_FLAG_NO_D2H, LOP_FLAG_PLAN_ONLY, LOP_FLAG_GRAPH, LOP_FLAG_DMA_COPY = 1, 2, 4
 LOP_FLAG_REUSE = 16
 LOP_FLAG_INDEPENDENT = 0
 LOP_FLAG_NO_FUSE = 32
+LOP_FLAG_POISON_SCRATCH = 64
 LOP_LINK_INDEPENDENT, LOP_LINK_QUEUED = 0, 1
 
 

@@ -231,35 +231,45 @@ def test_inverted_residual_block_small_integers_bit_exact(oracle):
     np.testing.assert_array_equal(host, want)
 
 
-@pytest.mark.parametrize("name", ["resnet18", "vgg16", "detector720p"])
+_FULL_WANT = {}
+
+
+def _full_size_case(oracle, name):
+    """(chain, tensors, oracle result) of a bench configuration at full size, computed once per
+    test session; the batch-8 640 x 640 chain one image at a time to bound the oracle's memory."""
+    if name not in _FULL_WANT:
+        chain = workloads.CONFIGS[name]()
+        t = workloads.make_tensors(chain)
+        if chain.in_shape[0] == 1:
+            want = oracle.run_chain(chain, t)
+        else:
+            one = workloads.CONFIGS[name](n=1)
+            want = np.concatenate([
+                oracle.run_chain(one, workloads.Tensors(np.ascontiguousarray(t.x[i:i + 1]), t.weights, t.biases))
+                for i in range(chain.in_shape[0])])
+        _FULL_WANT[name] = (chain, t, want)
+    return _FULL_WANT[name]
+
+
+def _check_every_image_and_band(dev, want, plan_rows, dtype):
+    """Every (image, band) slab against the oracle on its own scale, so that no slab can hide
+    behind a larger one."""
+    for img in range(want.shape[0]):
+        for lo, hi in plan_rows:
+            if hi > lo:
+                assert rel_err(dev[img:img + 1, :, lo:hi], want[img:img + 1, :, lo:hi]) <= TOL[dtype], (img, lo, hi)
+
+
+@pytest.mark.parametrize("name", ["resnet18", "vgg16", "detector720p", "mbv2"])
 def test_full_size_chains(oracle, name):
-    """The bench configurations at full size, element by element against the oracle."""
-    chain = workloads.CONFIGS[name]()
-    t = workloads.make_tensors(chain)
-    want = oracle.run_chain(chain, t)
+    """The bench configurations at full size, independent bands, element by element against the
+    oracle (all 8 images x 8 bands of the batch-8 chain too)."""
+    chain, t, want = _full_size_case(oracle, name)
     dev, host = run_gpu(chain, t)
     np.testing.assert_array_equal(dev, host)
     assert rel_err(dev, want) <= TOL[chain.dtype]
-
-
-def test_full_size_mbv2_sampled_bands(oracle):
-    """Batch-8 640x640 chain: the oracle recomputes two whole bands of one image (its own
-    banded path on a single-image copy of the same tensors) and they are compared with the
-    same rows of the GPU result; the other images are checked against image-independent
-    properties (finite, ReLU6-free last layer has both signs)."""
-    chain = workloads.mbv2_chain()
-    t = workloads.make_tensors(chain)
-    dev, host = run_gpu(chain, t)
-    np.testing.assert_array_equal(dev, host)
-    assert np.isfinite(dev).all()
-    from oracle import planner
-    for img, band in ((0, 0), (5, 3), (7, 7)):
-        one = workloads.mbv2_chain(n=1)
-        t1 = workloads.Tensors(np.ascontiguousarray(t.x[img:img + 1]), t.weights, t.biases)
-        need = planner.plan(one)[band]
-        slab = oracle.run_band(one, t1, need)
-        got = dev[img:img + 1, :, slab.row0:slab.row0 + slab.rows]
-        assert rel_err(got, slab.data) <= TOL["bf16"]
+    rows = planner.split_rows(want.shape[2], chain.n_bands)
+    _check_every_image_and_band(dev, want, rows, chain.dtype)
 
 
 def test_bands_in_any_order_and_subsets(oracle):
@@ -418,15 +428,15 @@ def test_reuse_mode_full_size(oracle, name):
     assert rel_err(dev, want) <= TOL[chain.dtype]
 
 
+@pytest.mark.parametrize("mode", ["independent", "reuse"])
 @pytest.mark.parametrize("name", ["resnet18", "vgg16", "detector720p", "mbv2"])
-def test_bench_configuration_full_size(oracle, name):
-    """The launch configuration bench.py times (reuse mode, graph replay, default lanes,
-    fused blocks) at the full sizes: five chains in a row so that every lane's graph is
-    replayed, the last one compared with the oracle. mbv2 (batch 8, 640x640): three sampled
-    (image, band) pairs recomputed by the oracle's banded path, the rest checked finite."""
-    chain = workloads.CONFIGS[name]()
-    t = workloads.make_tensors(chain)
-    plan = lop.Plan(chain, t, flags=lop.LOP_FLAG_REUSE | lop.LOP_FLAG_GRAPH)
+def test_bench_configuration_full_size(oracle, name, mode):
+    """The launch configurations bench.py times (independent bands and reuse mode; graph replay,
+    default lanes, fused blocks) at the full sizes: five chains in a row so that every lane's
+    graph is replayed, the last one compared with the oracle element by element, every image
+    and band."""
+    chain, t, want = _full_size_case(oracle, name)
+    plan = lop.Plan(chain, t, flags=(lop.LOP_FLAG_REUSE if mode == "reuse" else 0) | lop.LOP_FLAG_GRAPH)
     d_in = to_device_nhwc(t.x, chain.dtype)
     d_out = empty_out(plan.out_shape(), chain.dtype)
     h_out = empty_out(plan.out_shape(), chain.dtype, pinned=True)
@@ -434,20 +444,32 @@ def test_bench_configuration_full_size(oracle, name):
         plan.run_chain(d_in, d_out, h_out)
     plan.synchronize()
     dev, host = to_nchw(d_out), to_nchw(h_out)
+    rows = [plan.band_out_rows(b) for b in range(plan.n_bands)]
     plan.destroy()
     np.testing.assert_array_equal(dev, host)
-    if name != "mbv2":
-        want = oracle.run_chain(chain, t)
-        assert rel_err(dev, want) <= TOL[chain.dtype]
-        return
-    assert np.isfinite(dev).all()
-    from oracle import planner
-    for img, band in ((1, 0), (4, 5), (6, 7)):
-        one = workloads.mbv2_chain(n=1)
-        t1 = workloads.Tensors(np.ascontiguousarray(t.x[img:img + 1]), t.weights, t.biases)
-        slab = oracle.run_band(one, t1, planner.plan(one)[band])
-        got = dev[img:img + 1, :, slab.row0:slab.row0 + slab.rows]
-        assert rel_err(got, slab.data) <= TOL["bf16"]
+    assert rel_err(dev, want) <= TOL[chain.dtype]
+    _check_every_image_and_band(dev, want, rows, chain.dtype)
+
+
+@pytest.mark.parametrize("reuse", [0, 1])
+def test_poisoned_scratch_changes_nothing(oracle, reuse):
+    """LOP_FLAG_POISON_SCRATCH fills a band's scratch slabs and split-K workspace with NaN before
+    its kernels run: a kernel that read any scratch row outside the intervals the plan gave it,
+    or a stale row of an earlier band or chain, would carry the NaN into the output. The result
+    must equal the unpoisoned run bit for bit and match the oracle."""
+    mode = lop.LOP_FLAG_REUSE if reuse else 0
+    cases = [(workloads.CONFIGS[name](**kw), None) for name, kw in SCALED] + [
+        (workloads.resnet18_chain(), None), (workloads.vgg16_chain(), None)]
+    for chain, _ in cases:
+        t = workloads.make_tensors(chain, zero_bias=False)
+        for extra in (0, lop.LOP_FLAG_NO_FUSE):
+            plain, _h = run_gpu(chain, t, flags=mode | extra)
+            dev, host = run_gpu(chain, t, flags=mode | extra | lop.LOP_FLAG_POISON_SCRATCH)
+            assert not np.isnan(dev).any(), chain.name
+            np.testing.assert_array_equal(dev, host)
+            np.testing.assert_array_equal(dev, plain)
+        if chain.in_shape[2] < 200:
+            assert rel_err(dev, oracle.run_chain(chain, t)) <= TOL[chain.dtype]
 
 
 def test_reuse_mode_small_integers_bit_exact(oracle):
@@ -552,15 +574,21 @@ def test_rowwise_full_size_sampled_rows(oracle):
 
 # ---- seeded random shapes: every kernel choice the library can make, against the oracle ----
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("reuse", [0, 1])
-def test_random_chains(oracle, dtype, reuse):
-    if reuse == 0 and dtype == "f32":
-        pytest.skip("the test process once died with a segmentation fault inside lop_plan_destroy "
-                    "while this case ran (after many clean runs of the same code); the host code "
-                    "it goes through is clean under a host AddressSanitizer build and by reading, "
-                    "the cause is not known, so the case stays off the GPU until it is")
-    rng = np.random.Generator(np.random.PCG64(1234 + 17 * reuse + (dtype == "bf16")))
+_SKIP_RANDOM_F32 = (
+    "the test process once died with a segmentation fault inside lop_plan_destroy while this "
+    "case ran (after many clean runs of the same code). The whole create / run / destroy "
+    "sequence of this case has since been replayed on the CPU against a stand-in HIP runtime "
+    "under AddressSanitizer and UBSan with every stream, event and allocation tracked "
+    "(tests/test_host_under_stub.py): clean. No cause in this library's code is known, so this "
+    "exact case stays off the GPU; fp32 independent-mode chains are covered by the set with "
+    "base seed 9001 below")
+
+
+@pytest.mark.parametrize("dtype,reuse,base", [
+    pytest.param("f32", 0, 1234, marks=pytest.mark.skip(reason=_SKIP_RANDOM_F32)),
+    ("f32", 0, 9001), ("f32", 1, 1234), ("bf16", 0, 1234), ("bf16", 1, 1234)])
+def test_random_chains(oracle, dtype, reuse, base):
+    rng = np.random.Generator(np.random.PCG64(base + 17 * reuse + (dtype == "bf16")))
     done = 0
     while done < 24:
         chain = _random_conv_chain(rng, dtype)
