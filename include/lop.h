@@ -39,7 +39,8 @@ typedef enum {
   LOP_ERR_BAND_RANGE = -4,  /* band or layer index outside the plan                          */
   LOP_ERR_OOM = -5,         /* host or device allocation failed                              */
   LOP_ERR_HIP = -6,         /* a HIP call failed; see lop_last_hip_error()                   */
-  LOP_ERR_NOT_READY = -7    /* plan was made with LOP_FLAG_PLAN_ONLY and cannot run          */
+  LOP_ERR_NOT_READY = -7,   /* plan was made with LOP_FLAG_PLAN_ONLY and cannot run          */
+  LOP_ERR_TOO_LARGE = -8    /* lop_run_chain_static: scratch need above LOP_STATIC_SCRATCH_BYTES */
 } lop_status_t;
 
 /* Operator kinds (Sec. IV-A). Global operators (softmax, ...) are not local and are
@@ -181,6 +182,26 @@ LOP_API int lop_run_band(lop_plan_t* plan, int band, const void* d_in, void* d_o
  * waits for completion and fills *timing; otherwise it is asynchronous. */
 LOP_API int lop_run_chain(lop_plan_t* plan, const void* d_in, void* d_out, void* h_out,
                   void* compute_stream, lop_timing_t* timing);
+
+/* lop_run_chain for callers that cannot allocate device memory or create streams and events
+ * where they run: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc. Enqueues the kernels of every band, bands in order, on `stream` alone (NULL = the
+ * null stream) and returns; no copy to the host, no event, no other stream. The band slabs and
+ * the split-K partial sums do not live in the plan's allocations but in an array of
+ * LOP_STATIC_SCRATCH_BYTES that is part of the library's code object: every GPU the library
+ * is used on holds one such array from load until the process ends. The call allocates nothing,
+ * frees nothing and calls no allocating routine. Its address on the plan's device was looked up
+ * when the plan was made (lop_plan is the set-up call and does allocate).
+ *   plan    made by lop_plan / lop_plan_rowwise on the current device, either mode
+ *   d_in    device, whole chain input; d_out device, whole chain output (every row is written)
+ * LOP_ERR_TOO_LARGE: the plan needs more scratch (lop_plan_stats: scratch_bytes) than the
+ * array holds; nothing was enqueued. Results are those of lop_run_chain bit for bit (the same
+ * kernels on the same intervals). All calls on one GPU, from any plan, share that GPU's array:
+ * calls whose kernels can overlap on the GPU (different streams without an ordering between
+ * them) race; order them on one stream or with events. The array is not cleared between calls
+ * and need not be: every scratch row is written before it is read within a call. */
+#define LOP_STATIC_SCRATCH_BYTES (64u << 20)
+LOP_API int lop_run_chain_static(lop_plan_t* plan, const void* d_in, void* d_out, void* stream);
 
 /* Wait for everything the plan has enqueued on its own and on the passed streams. */
 LOP_API int lop_synchronize(lop_plan_t* plan);

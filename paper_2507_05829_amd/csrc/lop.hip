@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -47,8 +48,38 @@ int describe_op(const OpLaunch& L, char* name, size_t size) {
 }
 }  // namespace lop
 
+// Scratch of lop_run_chain_static: the slabs of one band at a time and the split-K partial sums
+// of one launch at a time, in an array that is part of the loaded code object instead of an
+// allocation. Every GPU the library runs on holds its own copy, at its own address, until the
+// process ends. In host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[LOP_STATIC_SCRATCH_BYTES];
+
 namespace {
 thread_local int g_last_hip = 0;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, once known
+
+// Looks up the address of `scratch` on `device`, which must be the current device. Called when
+// a plan is set up on a device, so that lop_run_chain_static itself makes no runtime query.
+hipError_t resolve_static_scratch(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[device]) return hipSuccess;
+  void* ptr = nullptr;
+  const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!ptr) return hipErrorInvalidSymbol;
+  g_scratch_ptr[device] = ptr;
+  return hipSuccess;
+}
+
+void* static_scratch_of(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  return g_scratch_ptr[device];
+}
 }  // namespace
 
 namespace lop {
@@ -475,6 +506,7 @@ int ensure_timing_events(lop_plan_t* P) {
 
 int setup_device(lop_plan_t* P) {
   LOP_HIP(hipGetDevice(&P->device));
+  LOP_HIP(resolve_static_scratch(P->device));
   int rc = upload_weights(P);
   if (rc != LOP_OK) return rc;
   const int nb = P->t.n_bands;
@@ -887,6 +919,26 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
   return LOP_OK;
 }
 
+int lop_run_chain_static(lop_plan_t* P, const void* d_in, void* d_out, void* stream) {
+  if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
+  if (!P->ready) return LOP_ERR_NOT_READY;
+  const size_t arena = align_up(P->arena_bytes, 256);
+  if (arena + P->conv_ws_bytes > (size_t)LOP_STATIC_SCRATCH_BYTES) return LOP_ERR_TOO_LARGE;
+  unsigned char* const base = (unsigned char*)static_scratch_of(P->device);
+  if (!base) return LOP_ERR_NOT_READY;
+  // Nothing in the array has to start at zero: a band's slabs are written by the layer that
+  // produces them before any layer reads them, and a launch's partial sums by its slices
+  // before its finish kernel adds them, so the contents left by the last call do not matter.
+  P->arena_override = base;
+  P->ws_override = P->conv_ws_bytes ? base + arena : nullptr;
+  int rc = LOP_OK;
+  for (int b = 0; b < P->t.n_bands && rc == LOP_OK; ++b)
+    if (!band_empty(P, b)) rc = enqueue_band_kernels(P, b, d_in, d_out, (hipStream_t)stream);
+  P->arena_override = nullptr;
+  P->ws_override = nullptr;
+  return rc;
+}
+
 int lop_synchronize(lop_plan_t* P) {
   if (!P) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
@@ -1005,6 +1057,7 @@ const char* lop_strerror(int code) {
     case LOP_ERR_OOM: return "out of memory";
     case LOP_ERR_HIP: return "HIP runtime error";
     case LOP_ERR_NOT_READY: return "plan holds no device state (plan-only)";
+    case LOP_ERR_TOO_LARGE: return "the plan needs more scratch than the static array holds";
     default: return "unknown error";
   }
 }

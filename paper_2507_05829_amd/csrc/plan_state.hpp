@@ -76,10 +76,16 @@ struct lop_plan_s {
   int lane_index(int band) const { return t.reuse ? cur_lane : band % (int)lanes.size(); }
   Lane& lane_of(int band) { return lanes[lane_index(band)]; }
   const Lane& lane_of(int band) const { return lanes[lane_index(band)]; }
+  // While lop_run_chain_static enqueues, scratch comes from the library's static device array
+  // instead of the lanes' allocations.
+  void* arena_override = nullptr;
+  void* ws_override = nullptr;
   void* arena_of(int band) const {
+    if (arena_override) return arena_override;
     return lanes.empty() ? nullptr : lane_of(band).arena;
   }
   void* ws_of(int band) const {
+    if (ws_override) return ws_override;
     return lanes.empty() ? nullptr : lane_of(band).conv_ws;
   }
 };

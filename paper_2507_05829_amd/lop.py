@@ -25,7 +25,8 @@ LIB_PATH = os.path.join(_HERE, "liblop.so")
 
 LOP_OK = 0
 LOP_ERR_INVALID_ARG, LOP_ERR_UNSUPPORTED, LOP_ERR_SHAPE, LOP_ERR_BAND_RANGE = -1, -2, -3, -4
-LOP_ERR_OOM, LOP_ERR_HIP, LOP_ERR_NOT_READY = -5, -6, -7
+LOP_ERR_OOM, LOP_ERR_HIP, LOP_ERR_NOT_READY, LOP_ERR_TOO_LARGE = -5, -6, -7, -8
+LOP_STATIC_SCRATCH_BYTES = 64 << 20
 LOP_CONV2D, LOP_DWCONV2D, LOP_MAXPOOL2D, LOP_ELTWISE = 0, 1, 2, 3
 LOP_ACT_NONE, LOP_ACT_RELU, LOP_ACT_RELU6 = 0, 1, 2
 LOP_F32, LOP_BF16 = 0, 1
@@ -50,7 +51,7 @@ EXPORTS = [
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
     "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
     "lop_plan_band_compute_rows", "lop_plan_rowwise", "lop_loss_eval", "lop_loss_solve",
-    "lop_run_two_party", "lop_measure_ceilings",
+    "lop_run_two_party", "lop_measure_ceilings", "lop_run_chain_static",
 ]
 
 
@@ -132,6 +133,7 @@ def _load() -> ctypes.CDLL:
         "lop_plan_layer_work": (c_int, [P, c_int, c_int, POINTER(c_double), POINTER(c_double)]),
         "lop_run_band": (c_int, [P, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
         "lop_run_chain": (c_int, [P, c_void_p, c_void_p, c_void_p, c_void_p, POINTER(lop_timing_t)]),
+        "lop_run_chain_static": (c_int, [P, c_void_p, c_void_p, c_void_p]),
         "lop_synchronize": (c_int, [P]),
         "lop_time_layer": (c_int, [P, c_int, c_int, c_void_p, c_void_p, c_int, POINTER(c_float)]),
         "lop_plan_destroy": (None, [P]),
@@ -309,6 +311,10 @@ def lop_run_chain(plan, d_in, d_out, h_out=None, compute_stream=None,
     return t
 
 
+def lop_run_chain_static(plan, d_in, d_out, stream=None) -> None:
+    _check(_lib.lop_run_chain_static(plan, _ptr(d_in), _ptr(d_out), _stream(stream)), "lop_run_chain_static")
+
+
 def lop_synchronize(plan) -> None:
     _check(_lib.lop_synchronize(plan), "lop_synchronize")
 
@@ -479,6 +485,9 @@ class Plan:
 
     def run_chain(self, d_in, d_out, h_out=None, compute_stream=None, timing=False):
         return lop_run_chain(self.handle, d_in, d_out, h_out, compute_stream, timing)
+
+    def run_chain_static(self, d_in, d_out, stream=None):
+        lop_run_chain_static(self.handle, d_in, d_out, stream)
 
     def synchronize(self): lop_synchronize(self.handle)
 
