@@ -93,8 +93,8 @@ typedef struct {
 #define LOP_FLAG_NO_D2H 1u    /* never copy to the host even if a host pointer is given  */
 #define LOP_FLAG_PLAN_ONLY 2u /* integer planning only: touches no GPU, needs no weights;
                                  lop_run_* return LOP_ERR_NOT_READY                      */
-#define LOP_FLAG_DMA_COPY 8u  /* always use hipMemcpyAsync for the band copies; by default a
-                                 mapped pinned host buffer is written by the kernel of the
+#define LOP_FLAG_DMA_COPY 8u  /* always use hipMemcpyAsync for the band copies; by default the
+                                 pinned host buffer is written by the kernel of the
                                  band's last layer itself (band outputs up to 256 KiB) or by
                                  a small copy kernel                                     */
 #define LOP_FLAG_REUSE 16u    /* bands run in order and share per-layer buffers: a band computes,
@@ -165,8 +165,10 @@ LOP_API int lop_plan_layer_work(const lop_plan_t* plan, int band, int layer, dou
  * to h_out once the kernels are done. Asynchronous.
  *   d_in   device, whole chain input N x H x W x C; only band_in_rows(band) are read
  *   d_out  device, whole chain output; only band_out_rows(band) are written
- *   h_out  pinned host, whole chain output, or NULL. What kind of memory h_out is (mapped
- *          pinned, or anything else) is looked up once per address and plan and kept, and a
+ *   h_out  pinned host (hipHostMalloc or equivalent: memory the device can address), whole
+ *          chain output, or NULL; host memory that is not pinned is refused with
+ *          LOP_ERR_INVALID_ARG. What kind of memory h_out is is looked up once per address and
+ *          plan and kept, and a
  *          captured graph (LOP_FLAG_GRAPH) holds the addresses it was captured with: a buffer
  *          passed here must stay allocated, and of the same kind, for as long as the plan lives.
  *   compute_stream, copy_stream  hipStream_t or NULL (= the plan's own streams)
@@ -175,11 +177,14 @@ LOP_API int lop_plan_layer_work(const lop_plan_t* plan, int band, int layer, dou
 LOP_API int lop_run_band(lop_plan_t* plan, int band, const void* d_in, void* d_out, void* h_out,
                  void* compute_stream, void* copy_stream);
 
-/* Run every band: the lanes fork from compute_stream (or the plan's own main stream),
- * each runs its bands in order, band b's copy overlaps the kernels of the bands after it
- * (Sec. IV-B), and compute_stream waits for all lanes' kernels (not for the copies: those
- * are complete after lop_synchronize). With timing != NULL the call records events,
- * waits for completion and fills *timing; otherwise it is asynchronous. */
+/* Run every band: the lanes fork from compute_stream, each runs its bands in order, band b's
+ * copy overlaps the kernels of the bands after it (Sec. IV-B), and compute_stream waits for
+ * all lanes' kernels (not for the copies: those are complete after lop_synchronize). With
+ * compute_stream == NULL there is nothing to order against: d_in must be complete when the
+ * call is made, every lane appends its bands to its own stream and the lanes are not joined,
+ * so the chains of consecutive calls overlap (give each chain in flight its own d_out /
+ * h_out); results are complete after lop_synchronize. With timing != NULL the call records
+ * events, waits for completion and fills *timing; otherwise it is asynchronous. */
 LOP_API int lop_run_chain(lop_plan_t* plan, const void* d_in, void* d_out, void* h_out,
                   void* compute_stream, lop_timing_t* timing);
 
@@ -348,6 +353,14 @@ LOP_API int lop_profile_chain(lop_plan_t* plan, const void* d_in, void* d_out, i
 /* Enqueue only the bands' device-to-host copies, back to back on the plan's copy stream
  * (the transmission leg alone, to measure how much of it the pipelined run hides). */
 LOP_API int lop_copy_chain(lop_plan_t* plan, const void* d_out, void* h_out);
+
+/* Debug aid. With the environment variable LOP_GUARD_BYTES=<n> set when the library makes its
+ * first device allocation, every device allocation of the library carries n bytes of a fixed
+ * pattern in front and behind. Waits for the device, compares the guards of all live
+ * allocations and returns the number of allocations (live, or freed since the process
+ * started) whose guard was overwritten, i.e. that some kernel stored outside of; 0 when the
+ * variable is not set; each finding is also reported on stderr. */
+LOP_API int lop_debug_guard_check(void);
 
 LOP_API void lop_plan_destroy(lop_plan_t* plan);
 LOP_API const char* lop_strerror(int code);

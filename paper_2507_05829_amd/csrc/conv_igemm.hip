@@ -896,6 +896,7 @@ __global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const Co
 }
 
 constexpr int kComputeUnits = 256;
+constexpr int kNarrowMaxTiles = 320;
 
 struct DirectChoice {
   int wk, nt;      // wk == 0: not applicable
@@ -919,11 +920,15 @@ DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
     while (d.wk < 16 && (steps + d.wk - 1) / d.wk > 8) d.wk *= 2;
     return d;
   }
-  // few pixels and at most two rounds of loads per wavefront: 16 x 16 tiles finish the layer
-  // in one launch (with more pixels every pixel tile would pull the weights again, with a
-  // longer reduction the tiles' own latency chain and, in fp32, MFMA time exceed the cut's)
+  // at most two rounds of loads per wavefront and about one workgroup per compute unit: 16 x 16
+  // tiles finish the layer in one launch, as fast as the cut and its finish kernel together
+  // (measured 12 against 8 + 4 us on 560 pixels x 128 channels, 7 against 6 + 4 on 196 x 256)
+  // and one launch fewer on the stream; with more tiles than that the workgroups (1024 threads,
+  // one per compute unit) come in rounds, with a longer reduction the tiles' own latency chain
+  // and, in fp32, MFMA time exceed the cut's
   const int steps16 = (p.K + 4 * ke - 1) / (4 * ke);
-  if (p.wd16 && p.M <= 128 && steps16 <= 16 * kNarrowWaves) {
+  const long tiles16 = (long)((p.M + 15) / 16) * ((p.C_out + 15) / 16);
+  if (p.wd16 && tiles16 <= kNarrowMaxTiles && steps16 <= 16 * kNarrowWaves) {
     d.narrow = true;
     d.z = 1;
     return d;

@@ -10,6 +10,7 @@
 #include <utility>
 #include <vector>
 
+#include "devmem.hpp"
 #include "kernels.hpp"
 #include "lop.h"
 #include "plan_state.hpp"
@@ -124,7 +125,7 @@ int upload_weights(lop_plan_t* P) {
               const size_t dst = (size_t)co * kp + (size_t)(a * d.kw + b) * d.c_in + ci;
               std::memcpy(&host[dst * esz], (const unsigned char*)d.weight + src * esz, esz);
             }
-      LOP_HIP(hipMalloc(&P->d_w[l], host.size()));
+      LOP_HIP(lop::dev_alloc(&P->d_w[l], host.size()));
       LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size(), hipMemcpyHostToDevice));
       const int ke = 16 / (int)esz;
       if (P->has_wd[l]) {
@@ -138,7 +139,7 @@ int upload_weights(lop_plan_t* P) {
               const size_t dst = (((size_t)(co / 32) * steps + st) * 64 + half * 32 + co % 32) * ke;
               std::memcpy(&ord[dst * esz], &host[src * esz], 16);
             }
-        LOP_HIP(hipMalloc(&P->d_wd[l], ord.size()));
+        LOP_HIP(lop::dev_alloc(&P->d_wd[l], ord.size()));
         LOP_HIP(hipMemcpy(P->d_wd[l], ord.data(), ord.size(), hipMemcpyHostToDevice));
         if (P->has_wd16[l]) {
           // ... and in the order of 16 x 16 tiles: [co / 16][step][quarter*16 + co % 16] x 16 B
@@ -150,7 +151,7 @@ int upload_weights(lop_plan_t* P) {
                 const size_t dst = (((size_t)(co / 16) * steps16 + st) * 64 + q * 16 + co % 16) * ke;
                 std::memcpy(&ord[dst * esz], &host[src * esz], 16);
               }
-          LOP_HIP(hipMalloc(&P->d_wd16[l], ord.size()));
+          LOP_HIP(lop::dev_alloc(&P->d_wd16[l], ord.size()));
           LOP_HIP(hipMemcpy(P->d_wd16[l], ord.data(), ord.size(), hipMemcpyHostToDevice));
         }
       }
@@ -170,11 +171,11 @@ int upload_weights(lop_plan_t* P) {
           }
           host[(size_t)tap * d.c_in + c] = v;
         }
-      LOP_HIP(hipMalloc(&P->d_w[l], host.size() * 4));
+      LOP_HIP(lop::dev_alloc(&P->d_w[l], host.size() * 4));
       LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size() * 4, hipMemcpyHostToDevice));
     }
     if (d.bias && d.op != LOP_MAXPOOL2D) {
-      LOP_HIP(hipMalloc((void**)&P->d_bias[l], (size_t)d.c_out * 4));
+      LOP_HIP(lop::dev_alloc((void**)&P->d_bias[l], (size_t)d.c_out * 4));
       LOP_HIP(hipMemcpy(P->d_bias[l], d.bias, (size_t)d.c_out * 4, hipMemcpyHostToDevice));
     }
   }
@@ -474,9 +475,13 @@ int enqueue_band_copy(lop_plan_t* P, int band, const void* d_out, void* h_out, h
   const size_t img_b = row_b * L.h_out;
   const size_t off = row_b * r.lo, len = row_b * (r.hi - r.lo);
   // Mapped pinned host memory is written by a small kernel on the copy stream (no DMA
-  // set-up cost per band, and it can be captured like any kernel); anything else, or a
-  // plan made with LOP_FLAG_DMA_COPY, goes through the runtime's copy engines.
-  void* mapped = (P->flags & LOP_FLAG_DMA_COPY) ? nullptr : device_view_of_host(P, h_out);
+  // set-up cost per band, and it can be captured like any kernel); a plan made with
+  // LOP_FLAG_DMA_COPY goes through the runtime's copy engines instead. Host memory that is
+  // not pinned is refused (the boundary asks for pinned memory: an asynchronous copy into
+  // pageable memory is staged by the runtime and is neither asynchronous nor cheap).
+  void* mapped = device_view_of_host(P, h_out);
+  if (!mapped) return LOP_ERR_INVALID_ARG;
+  if (P->flags & LOP_FLAG_DMA_COPY) mapped = nullptr;
   if (mapped) {
     LOP_HIP(lop::launch_copy_rows((char*)mapped + off, (const char*)d_out + off, img_b, len,
                                   t.in.n, s));
@@ -517,9 +522,9 @@ int setup_device(lop_plan_t* P) {
   const int n_lanes = P->t.reuse ? std::max(1, want) : std::max(1, std::min(want, live));
   P->lanes.assign(n_lanes, Lane{});
   for (Lane& L : P->lanes) {
-    if (P->arena_bytes) LOP_HIP(hipMalloc(&L.arena, align_up(P->arena_bytes, 256)));
+    if (P->arena_bytes) LOP_HIP(lop::dev_alloc(&L.arena, align_up(P->arena_bytes, 256)));
     if (P->conv_ws_bytes) {
-      LOP_HIP(hipMalloc(&L.conv_ws, P->conv_ws_bytes));
+      LOP_HIP(lop::dev_alloc(&L.conv_ws, P->conv_ws_bytes));
     }
     LOP_HIP(hipStreamCreateWithFlags(&L.stream, hipStreamNonBlocking));
     LOP_HIP(hipStreamCreateWithFlags(&L.copy, hipStreamNonBlocking));
@@ -631,8 +636,22 @@ int enqueue_chain_reuse(lop_plan_t* P, const void* d_in, void* d_out, void* h_ou
   return LOP_OK;
 }
 
-int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms) {
-  const int lane = P->t.reuse ? P->cur_lane : -1;
+// The bands of lane `lane` of an independent-mode chain, in order, on that lane's stream.
+int enqueue_lane(lop_plan_t* P, int lane, const void* d_in, void* d_out, void* h_out, bool capturing) {
+  hipStream_t cs = P->lanes[lane].stream;
+  for (int b = lane; b < P->t.n_bands; b += P->n_lanes()) {
+    if (band_empty(P, b)) continue;
+    int rc = enqueue_band(P, b, d_in, d_out, h_out, cs, cs, false, capturing);
+    if (rc != LOP_OK) return rc;
+  }
+  return LOP_OK;
+}
+
+// lane_only >= 0 (independent mode): the graph holds that lane's bands only and runs on the
+// lane's stream `ms`; -1: the whole chain forked from and joined into `ms`.
+int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms,
+                 int lane_only = -1) {
+  const int lane = P->t.reuse ? P->cur_lane : (lane_only >= 0 ? lane_only : -1);
   // an eager run may still have copies of the output rows in flight (on a copy stream that the
   // graph's stream is not ordered behind): a replay, and the first capture, wait for them
   for (int b = 0; b < P->t.n_bands; ++b)
@@ -649,7 +668,8 @@ int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipS
   hipGraph_t graph = nullptr;
   LOP_HIP(hipStreamBeginCapture(ms, hipStreamCaptureModeThreadLocal));
   int rc = P->t.reuse ? enqueue_chain_reuse(P, d_in, d_out, h_out, false, true)
-                      : enqueue_chain(P, d_in, d_out, h_out, ms, false, true);
+           : lane_only >= 0 ? enqueue_lane(P, lane_only, d_in, d_out, h_out, true)
+                            : enqueue_chain(P, d_in, d_out, h_out, ms, false, true);
   hipError_t e = hipStreamEndCapture(ms, &graph);
   if (rc != LOP_OK) {
     if (graph) (void)hipGraphDestroy(graph);
@@ -660,7 +680,7 @@ int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipS
   e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
   (void)hipGraphDestroy(graph);
   if (e != hipSuccess) return hip_fail(e);
-  if (P->graphs.size() >= 32) {  // bounded cache: drop the oldest
+  if (P->graphs.size() >= 128) {  // bounded cache: drop the oldest
     (void)hipGraphExecDestroy(P->graphs.front().exec);
     P->graphs.erase(P->graphs.begin());
   }
@@ -739,17 +759,17 @@ void lop_plan_destroy(lop_plan_t* P) {
     if (hipGetDevice(&cur) == hipSuccess && cur != P->device && P->device >= 0) (void)hipSetDevice(P->device);
     (void)hipDeviceSynchronize();
   }
-  for (void* w : P->d_w) if (w) (void)hipFree(w);
-  for (void* w : P->d_wd) if (w) (void)hipFree(w);
-  for (void* w : P->d_wd16) if (w) (void)hipFree(w);
-  for (float* b : P->d_bias) if (b) (void)hipFree(b);
+  for (void* w : P->d_w) if (w) (void)lop::dev_free(w);
+  for (void* w : P->d_wd) if (w) (void)lop::dev_free(w);
+  for (void* w : P->d_wd16) if (w) (void)lop::dev_free(w);
+  for (float* b : P->d_bias) if (b) (void)lop::dev_free(b);
   for (auto* v : {&P->ev_done, &P->ev_copied, &P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
   for (auto& g : P->graphs) (void)hipGraphExecDestroy(g.exec);
   for (hipEvent_t e : {P->ev_fork, P->ev_t0, P->ev_t1, P->ev_copy_tail}) if (e) (void)hipEventDestroy(e);
   for (Lane& L : P->lanes) {
-    if (L.arena) (void)hipFree(L.arena);
-    if (L.conv_ws) (void)hipFree(L.conv_ws);
+    if (L.arena) (void)lop::dev_free(L.arena);
+    if (L.conv_ws) (void)lop::dev_free(L.conv_ws);
     if (L.ev_join) (void)hipEventDestroy(L.ev_join);
     if (L.stream) (void)hipStreamDestroy(L.stream);
     if (L.copy) (void)hipStreamDestroy(L.copy);
@@ -851,6 +871,7 @@ int lop_run_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h
   if (band < 0 || band >= P->t.n_bands) return LOP_ERR_BAND_RANGE;
   if (!P->ready) return LOP_ERR_NOT_READY;
   if (band_empty(P, band)) return LOP_OK;
+  if (h_out && !(P->flags & LOP_FLAG_NO_D2H) && !device_view_of_host(P, h_out)) return LOP_ERR_INVALID_ARG;
   hipStream_t cs = compute_stream ? (hipStream_t)compute_stream : P->lane_of(band).stream;
   hipStream_t ds = copy_stream ? (hipStream_t)copy_stream : P->s_copy;
   if (compute_stream) P->last_user_stream = cs;
@@ -865,6 +886,7 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
   if (compute_stream) P->last_user_stream = ms;
   const int nb = P->t.n_bands;
   const bool copy = h_out && !(P->flags & LOP_FLAG_NO_D2H);
+  if (copy && !device_view_of_host(P, h_out)) return LOP_ERR_INVALID_ARG;  // not pinned host memory
   if (timing) {
     int rc = ensure_timing_events(P);
     if (rc != LOP_OK) return rc;
@@ -893,6 +915,19 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
       LOP_HIP(hipStreamWaitEvent(ms, L.ev_join, 0));
     }
   } else {
+    if (!compute_stream && !timing && P->n_lanes() > 1) {
+      // No stream of the caller's to order against: every lane takes its bands of this chain
+      // behind whatever it still has of earlier chains and nothing joins them, so the lanes
+      // drift apart by as much as their bands differ in work and consecutive chains overlap
+      // (band b of the next chain starts while slower bands of this one still run). The
+      // chain is complete after lop_synchronize.
+      for (int k = 0; k < P->n_lanes(); ++k) {
+        int rc = (P->flags & LOP_FLAG_GRAPH) ? launch_graph(P, d_in, d_out, h_out, P->lanes[k].stream, k)
+                                             : enqueue_lane(P, k, d_in, d_out, h_out, false);
+        if (rc != LOP_OK) return rc;
+      }
+      return LOP_OK;
+    }
     if ((P->flags & LOP_FLAG_GRAPH) && !timing) return launch_graph(P, d_in, d_out, h_out, ms);
     if (timing) LOP_HIP(hipEventRecord(P->ev_t0, ms));
     int rc = enqueue_chain(P, d_in, d_out, h_out, ms, timing != nullptr, false);
@@ -1040,6 +1075,7 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
 int lop_copy_chain(lop_plan_t* P, const void* d_out, void* h_out) {
   if (!P || !d_out || !h_out) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
+  if (!device_view_of_host(P, h_out)) return LOP_ERR_INVALID_ARG;
   for (int b = 0; b < P->t.n_bands; ++b) {
     int rc = enqueue_band_copy(P, b, d_out, h_out, P->s_copy);
     if (rc != LOP_OK) return rc;

@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <vector>
 
+#include "devmem.hpp"
 #include "plan_state.hpp"
 
 namespace {
@@ -64,8 +65,8 @@ struct Session {
     for (Party& p : party) {
       if (p.compute) { (void)hipStreamSynchronize(p.compute); (void)hipStreamDestroy(p.compute); }
       if (p.link_in) { (void)hipStreamSynchronize(p.link_in); (void)hipStreamDestroy(p.link_in); }
-      if (p.arena) (void)hipFree(p.arena);
-      if (p.ws) (void)hipFree(p.ws);
+      if (p.arena) (void)lop::dev_free(p.arena);
+      if (p.ws) (void)lop::dev_free(p.ws);
     }
     for (hipEvent_t e : events) (void)hipEventDestroy(e);
     if (t0) (void)hipEventDestroy(t0);
@@ -136,7 +137,7 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
   std::vector<lop::OpLaunch> launch[2];
   for (int d = 0; d < 2; ++d) {
     Party& p = S.party[d];
-    LOP_HIP(hipMalloc(&p.arena, total));
+    LOP_HIP(lop::dev_alloc(&p.arena, total));
     p.buf.resize(nl + 1);
     for (int u = -1; u < nl; ++u) p.buf[u + 1] = (char*)p.arena + off[u + 1];
     if (d == 0) {
@@ -174,7 +175,7 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
     }
   }
   for (int d = 0; d < 2; ++d) {
-    if (ws_bytes) LOP_HIP(hipMalloc(&S.party[d].ws, ws_bytes));
+    if (ws_bytes) LOP_HIP(lop::dev_alloc(&S.party[d].ws, ws_bytes));
     for (auto& o : launch[d]) o.ws = S.party[d].ws;
   }
   S.party[0].held[0].push_back(Piece{0, rows_of(-1)});  // the client holds the whole input

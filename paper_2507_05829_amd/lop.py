@@ -51,7 +51,7 @@ EXPORTS = [
     "lop_run_chain", "lop_synchronize", "lop_time_layer", "lop_plan_destroy", "lop_strerror",
     "lop_last_hip_error", "lop_plan_layer_kernel", "lop_profile_chain", "lop_copy_chain",
     "lop_plan_band_compute_rows", "lop_plan_rowwise", "lop_loss_eval", "lop_loss_solve",
-    "lop_run_two_party", "lop_measure_ceilings", "lop_run_chain_static",
+    "lop_run_two_party", "lop_measure_ceilings", "lop_run_chain_static", "lop_debug_guard_check",
 ]
 
 
@@ -144,6 +144,7 @@ def _load() -> ctypes.CDLL:
                                       POINTER(lop_loss_layer_t), c_double, c_double,
                                       POINTER(lop_two_party_stats_t)]),
         "lop_measure_ceilings": (c_int, [POINTER(lop_ceilings_t)]),
+        "lop_debug_guard_check": (c_int, []),
         "lop_strerror": (c_char_p, [c_int]),
         "lop_last_hip_error": (c_int, []),
     }
@@ -365,6 +366,10 @@ def lop_measure_ceilings() -> lop_ceilings_t:
     c = lop_ceilings_t()
     _check(_lib.lop_measure_ceilings(byref(c)), "lop_measure_ceilings")
     return c
+
+
+def lop_debug_guard_check() -> int:
+    return _lib.lop_debug_guard_check()
 
 
 def lop_strerror(code: int) -> str:

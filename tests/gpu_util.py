@@ -17,16 +17,39 @@ def to_device_nhwc(x_nchw: np.ndarray, dtype: str) -> torch.Tensor:
     return t
 
 
+MARGIN = 2048          # elements of NaN in front of and behind every output buffer
+_PARENTS = {}          # data_ptr of an output view -> the padded buffer it lives in
+
+
 def empty_out(shape_nchw, dtype: str, pinned: bool = False) -> torch.Tensor:
+    """NaN-filled NHWC output buffer that sits in the middle of a larger NaN-filled allocation,
+    so that a store in front of or behind the buffer lands in memory check_margins looks at."""
     n, c, h, w = shape_nchw
     td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    numel = n * h * w * c
     if pinned:
-        t = torch.empty((n, h, w, c), dtype=td, pin_memory=True)
+        parent = torch.empty(numel + 2 * MARGIN, dtype=td, pin_memory=True)
     else:
-        t = torch.empty((n, h, w, c), dtype=td, device="cuda")
-    t.fill_(float("nan"))
+        parent = torch.empty(numel + 2 * MARGIN, dtype=td, device="cuda")
+    parent.fill_(float("nan"))
     torch.cuda.synchronize()
+    t = parent[MARGIN:MARGIN + numel].view(n, h, w, c)
+    _PARENTS[t.data_ptr()] = parent
     return t
+
+
+def check_margins(*tensors) -> None:
+    """The memory around output buffers made by empty_out is still NaN."""
+    torch.cuda.synchronize()
+    for t in tensors:
+        if t is None:
+            continue
+        parent = _PARENTS.pop(t.data_ptr(), None)
+        if parent is None:
+            continue
+        numel = t.numel()
+        for part, name in ((parent[:MARGIN], "in front of"), (parent[MARGIN + numel:], "behind")):
+            assert bool(torch.isnan(part.float()).all()), f"a kernel or copy stored {name} its output buffer"
 
 
 def to_nchw(t: torch.Tensor) -> np.ndarray:
@@ -43,6 +66,7 @@ def run_gpu(chain, tensors, n_bands=None, use_host=True, flags=0):
         torch.cuda.synchronize()
         plan.run_chain(d_in, d_out, h_out)
         plan.synchronize()
+        check_margins(d_out, h_out)
         return to_nchw(d_out), (to_nchw(h_out) if use_host else None)
     finally:
         plan.destroy()

@@ -95,7 +95,14 @@ def named_workloads():
             for rep in range(3):                      # graph: capture once, replay twice
                 plan.run_chain(d_in, d_out, h_out)
                 plan.synchronize()
-            plan.run_chain(d_in, d_out, pageable)     # copy engines
+            try:                                      # host memory that is not pinned is refused
+                plan.run_chain(d_in, d_out, pageable)
+                raise SystemExit("a pageable host buffer was accepted")
+            except lop.LopError as e:
+                assert e.code == lop.LOP_ERR_INVALID_ARG or flags & lop.LOP_FLAG_NO_D2H
+            except SystemExit:
+                if not flags & lop.LOP_FLAG_NO_D2H:
+                    raise
             plan.run_chain(d_in, d_out, None)
             tm = plan.run_chain(d_in, d_out, h_out, timing=True)
             assert tm.n_bands == plan.n_bands
@@ -135,8 +142,59 @@ def named_workloads():
     return n + 1
 
 
+def scheduling_model_and_two_party():
+    """The scheduling-model calls and the two-party runtime as the GPU tests drive them: a
+    searched schedule for the full-size backbone with modelled device speeds, and seeded random
+    chains under random schedules."""
+    from oracle import loss, planner
+    n = 0
+    chain = workloads.resnet18_chain()
+    t = workloads.make_tensors(chain, zero_bias=False)
+    shapes = planner.infer_shapes(chain)
+    layers = []
+    for i, L in enumerate(chain.layers):
+        nn, c, h, w = shapes[i]
+        flop_row = planner.conv_flop(chain, shapes, i, 1) if L.op != "maxpool" else 40.0 * nn * c * w
+        layers.append(loss.LossLayer(n_ops=h, input_from=L.input_from, residual_from=L.residual_from,
+                                     k=L.k[0], s=L.s[0], p=L.p[0], d=L.d[0],
+                                     cm_fixed=5e-5, cm_row=flop_row / 5e10, cr_fixed=1e-5, cr_row=flop_row / 2e12,
+                                     row_bytes=float(nn * c * w * 4)))
+    nn, c, h, w = chain.in_shape
+    for bw in (4e6, 40e6):
+        for model in (lop.LOP_LINK_QUEUED, lop.LOP_LINK_INDEPENDENT):
+            sched, T, viol = lop.lop_loss_solve(layers, h, float(nn * c * w * 4), bw, 1e-3, generations=60,
+                                                seed=3, link_model=model)
+            lop.lop_loss_eval(layers, h, float(nn * c * w * 4), bw, 1e-3, sched, model)
+        plan = lop.Plan(chain, t, 1)
+        d_in, d_out, h_out = buffers(chain, plan)
+        plan.run_two_party(d_in, d_out, sched, bw, 1e-3, layers)
+        release(h_out)
+        plan.destroy()
+        n += 1
+    for dtype, base in (("f32", 4321), ("f32", 8765), ("bf16", 4321)):
+        rng = np.random.Generator(np.random.PCG64(base + (dtype == "bf16")))
+        done = 0
+        while done < 10:
+            chain = random_conv_chain(rng, dtype)
+            if chain is None:
+                continue
+            t = workloads.make_tensors(chain, zero_bias=False, seed=int(rng.integers(1, 1 << 30)))
+            heights = [sh[2] for sh in planner.infer_shapes(chain)]
+            sched = workloads.random_schedule(heights, seed=int(rng.integers(1, 1 << 30)), overlap=2)
+            plan = lop.Plan(chain, t, 1)
+            d_in, d_out, h_out = buffers(chain, plan)
+            plan.run_two_party(d_in, d_out, [(a["M"], a["R"]) for a in sched], 1e12, 0.0)
+            release(h_out)
+            plan.destroy()
+            done += 1
+            n += 1
+    return n
+
+
 def main():
-    total = random_chain_sets()
+    total = scheduling_model_and_two_party()
+    print("two-party sequences replayed:", total, flush=True)
+    total += random_chain_sets()
     print("random chains replayed:", total, flush=True)
     total += named_workloads()
     print("plans replayed:", total, "kernel launches:", stub.hipstub_launches(), flush=True)
