@@ -751,6 +751,204 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
   }
 }
 
+// Mid-size layers (hundreds to tens of thousands of pixels, 64..512 channels, a reduction of
+// hundreds to thousands of elements: most launches of the banded 224 x 224 and 720p chains).
+// Such a launch is too small for the 128-wide tiles to cover the chip and too large for the
+// operand-direct kernels, whose gathered 16-byte loads touch a new cache line per lane and
+// whose 1024-thread workgroups hold a whole compute unit while they wait. Here a 256-thread
+// workgroup owns a BM-pixel x BN-channel tile and both operands travel global -> LDS without
+// passing through registers (global_load_lds, 16 bytes per lane): a wavefront's load covers 8
+// rows (pixels of the im2col matrix, or output channels of the weights) x 128 contiguous bytes
+// of the reduction axis, i.e. 8 whole cache lines, and NST - 1 stages of 128 bytes per row are
+// in flight per workgroup without costing a register. The 16-byte chunks of a row are placed
+// at chunk ^ (row & 7) inside the row's 128 bytes (the placement is chosen through the address
+// each lane fetches from, since the LDS side of such a load is fixed: lane j writes bytes
+// [16 j, 16 j + 16) of the instruction's KiB), so a wavefront's MFMA operand read - 32 rows,
+// the same two chunks of each - hits every LDS bank equally. The four wavefronts split the
+// reduction axis inside a stage (wavefront w multiplies the w-th quarter of the 128 bytes) and
+// each accumulates the whole tile; the four partial tiles are added through LDS in wavefront
+// order at the end, so no operand byte is read from LDS twice and the result does not depend
+// on how the launch was cut. A tap outside the image (or the slab) is fetched from a
+// zero-filled device array instead of being masked afterwards. Needs C_in * sizeof(T) to be a
+// multiple of 128 (a stage never straddles two taps) and C_out a multiple of the 16-byte vector.
+static __device__ __attribute__((aligned(256))) unsigned char g_zero_line[256];
+
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
+// and leaves the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
+constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
+
+template <typename T, int BM, int BN, int NST>
+__global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
+  constexpr int KE = 16 / (int)sizeof(T);   // elements per 16-byte chunk
+  constexpr int SKE = 8 * KE;               // reduction elements per stage (128 bytes per row)
+  constexpr int TM = BM / 32, TN = BN / 32; // 32 x 32 MFMA tiles of the workgroup tile
+  constexpr int A_LD = BM / 32, B_LD = BN / 32;  // load instructions per wavefront and stage
+  constexpr int LPS = A_LD + B_LD;
+  constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
+  constexpr int CP = BN + 4;                // fp32 pitch of a staged partial tile
+  constexpr int VE = KE;
+  constexpr int PIECES = BM * (BN / VE);    // 16-byte output pieces of the tile
+  constexpr int RED_BYTES = 4 * BM * CP * 4;
+  constexpr int SMEM = NST * STAGE > RED_BYTES ? NST * STAGE : RED_BYTES;
+  static_assert(BM % 32 == 0 && BN % 32 == 0 && NST >= 2 && (NST - 2) * LPS < 64, "tile shape");
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+  const unsigned char* __restrict__ xg = (const unsigned char*)p.x;
+  const unsigned char* __restrict__ wg = (const unsigned char*)p.w;
+  const int ns = p.k_pad / SKE;             // stages
+
+  // ---- what this lane fetches: row (lane >> 3) of an 8-row group, chunk (lane & 7) ^ row
+  const int lrow = lane >> 3;
+  const int chunk = (lane & 7) ^ lrow;
+  int a_off[A_LD], a_ih0[A_LD], a_iw0[A_LD];
+#pragma unroll
+  for (int i = 0; i < A_LD; ++i) {
+    const int m = m0 + (wave * A_LD + i) * 8 + lrow;
+    const bool ok = m < p.M;
+    const int mm = ok ? m : 0;
+    const int ow = mm % p.W_out;
+    const int t = mm / p.W_out;
+    const int r = t % p.R, n = t / p.R;
+    const int ih0 = (p.out_lo + r) * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+    a_ih0[i] = ok ? ih0 : -(1 << 28);       // a row past the end of the launch: every tap "outside"
+    a_iw0[i] = iw0;
+    a_off[i] = (((n * p.x_rows - p.x_row0 + ih0) * p.W + iw0) * p.C_in + chunk * KE) * (int)sizeof(T);
+  }
+  unsigned b_off[B_LD];
+#pragma unroll
+  for (int i = 0; i < B_LD; ++i)
+    b_off[i] = (unsigned)(((co0 + (wave * B_LD + i) * 8 + lrow) * p.k_pad + chunk * KE) * (int)sizeof(T));
+  const int tap_row = p.dh * p.W * p.C_in * (int)sizeof(T), tap_col = p.dw * p.C_in * (int)sizeof(T);
+
+  // position of the next stage to issue on the reduction axis: k = (ia*kw + ib)*C_in + ici
+  int ia = 0, ib = 0, ici = 0, issued = 0;
+  auto issue = [&]() __attribute__((always_inline)) {
+    unsigned char* const dst = smem + (issued % NST) * STAGE;
+    const int toff = ia * tap_row + ib * tap_col + ici * (int)sizeof(T);
+    const int dih = ia * p.dh, diw = ib * p.dw;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+      const int ih = a_ih0[i] + dih, iw = a_iw0[i] + diw;
+      const bool ok = (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows) & (iw >= 0) & (iw < p.W) & (ia < p.kh);
+      const unsigned char* src = ok ? xg + (a_off[i] + toff) : g_zero_line + (lane & 7) * 16;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(dst + (wave * A_LD + i) * 1024),
+                                       16, 0, 0);
+    }
+    const unsigned koff = (unsigned)issued * (unsigned)(SKE * (int)sizeof(T));
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wg + b_off[i] + koff),
+                                       (__attribute__((address_space(3))) void*)(dst + A_BYTES + (wave * B_LD + i) * 1024),
+                                       16, 0, 0);
+    ++issued;
+    ici += SKE;
+    if (ici >= p.C_in) {
+      ici = 0;
+      if (++ib == p.kw) { ib = 0; ++ia; }
+    }
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int a = 0; a < TN; ++a)
+#pragma unroll
+    for (int b = 0; b < TM; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  // operand fragment of this lane inside a 32-row tile of a stage: row = lane & 31, chunks
+  // 2 * wave + (lane >> 5)
+  const int frow = lane & 31, fchunk = 2 * wave + (lane >> 5);
+  const int foff = (frow >> 3) * 1024 + ((frow & 7) * 8 + (fchunk ^ (frow & 7))) * 16;
+  // The operand reads are written as instructions: reads the compiler can see make it wait for
+  // EVERY global -> LDS load in flight before each of them (it cannot tell which stage a read
+  // touches), which would leave one stage in flight instead of NST - 1. The waits are placed by
+  // hand instead: vmcnt before the barrier for the stage about to be read, lgkmcnt behind the
+  // reads (tied to the fragment registers, so no MFMA can move in front of it).
+  const unsigned lds0 = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char*)smem + foff;
+  auto multiply = [&](int s) __attribute__((always_inline)) {
+    const unsigned at = lds0 + (unsigned)((s % NST) * STAGE);
+    u32x4 px[TM], wt[TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(px[tm]) : "v"(at), "n"(tm * 4096) : "memory");
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wt[tn]) : "v"(at), "n"(A_BYTES + tn * 4096) : "memory");
+    if constexpr (TM == 2 && TN == 2)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(px[1]), "+v"(wt[0]), "+v"(wt[1]) :: "memory");
+    else if constexpr (TM == 1 && TN == 2)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(wt[0]), "+v"(wt[1]) :: "memory");
+    else if constexpr (TM == 2 && TN == 1)
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(px[1]), "+v"(wt[0]) :: "memory");
+    else {
+      static_assert(TM == 1 && TN == 1, "tile shapes up to 64 x 64");
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(wt[0]) :: "memory");
+    }
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
+  };
+  auto stage_barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  // ---- NST - 1 stages in flight; one barrier per stage: behind it stage s is complete for
+  // every wavefront and nobody reads stage s - 1 any more, whose buffer the next issue reuses
+  const int pre = min(ns, NST - 1);
+  for (int s = 0; s < pre; ++s) issue();
+  int s = 0;
+  for (; s + NST - 1 < ns; ++s) {
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LPS));
+    stage_barrier();
+    issue();
+    multiply(s);
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  for (; s < ns; ++s) {
+    stage_barrier();
+    multiply(s);
+  }
+
+  // ---- add the four partial tiles in wavefront order through LDS, then the epilogue on
+  // 16-byte pieces (a lane of the accumulator holds pixel lane & 31 and channels
+  // g*8 + (lane >> 5)*4 + {0..3} of every 32 x 32 tile)
+  __syncthreads();
+  float* const mine = (float*)smem + wave * (BM * CP);
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *(float4*)(mine + (tm * 32 + (lane & 31)) * CP + tn * 32 + g * 8 + (lane >> 5) * 4) =
+            make_float4(acc[tn][tm][g * 4], acc[tn][tm][g * 4 + 1], acc[tn][tm][g * 4 + 2], acc[tn][tm][g * 4 + 3]);
+  __syncthreads();
+  for (int piece = tid; piece < PIECES; piece += 256) {
+    const int row = piece / (BN / VE), c = (piece % (BN / VE)) * VE;
+    const int m = m0 + row, co = co0 + c;
+    if (m >= p.M || co >= p.C_out) continue;
+    float v[VE];
+#pragma unroll
+    for (int j = 0; j < VE; ++j) v[j] = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+      for (int j = 0; j < VE; j += 4) {
+        const float4 q = *(const float4*)((const float*)smem + w * (BM * CP) + row * CP + c + j);
+        v[j] += q.x; v[j + 1] += q.y; v[j + 2] += q.z; v[j + 3] += q.w;
+      }
+    finish_vec<T, VE>(p, m, co, v);
+  }
+}
+
 // Whether (and how) the direct kernel takes a launch: only layers that the tiled kernel
 // would cut along the reduction axis, with vectorisable channel counts.
 // 16 x 16 MFMA tiles of the same operand-direct scheme, for the layers with very few pixels
@@ -779,6 +977,7 @@ __device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f
 }
 
 constexpr int kNarrowWaves = 16;
+constexpr int kLdsMinTiles = 96;   // fewer tiles than this leave most of the chip idle
 
 template <typename T>
 __global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const ConvParams p) {
@@ -897,6 +1096,30 @@ __global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const Co
 
 constexpr int kComputeUnits = 256;
 constexpr int kNarrowMaxTiles = 320;
+
+// The LDS-staged mid-size kernel: which tile, or bm == 0 when it does not apply.
+struct LdsChoice { int bm, bn; };
+LdsChoice choose_lds(const ConvParams& p, int dtype) {
+  const int esz = dtype == LOP_BF16 ? 2 : 4, ke = 16 / esz;
+  if ((p.C_in * esz) % 128 != 0 || p.C_out % ke != 0 || p.k_pad != p.K) return {0, 0};
+  // 32-bit signed byte offsets into the input slab
+  if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return {0, 0};
+  auto tiles = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn); };
+  if (dtype == LOP_BF16) {
+    if (tiles(64, 64) >= kLdsMinTiles) return {64, 64};
+    if (tiles(32, 64) >= kLdsMinTiles) return {32, 64};
+    return {0, 0};
+  }
+  if (tiles(32, 32) >= kLdsMinTiles) return {32, 32};
+  return {0, 0};
+}
+
+template <typename T, int BM, int BN, int NST>
+hipError_t launch_lds(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
+  dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN);
+  if ((int)grid.y * BN > conv_cout_pad(p.C_out) || grid.y > 65535) return hipErrorInvalidValue;
+  return launch_kernel(conv_lds_kernel<T, BM, BN, NST>, grid, dim3(256), s, ev, p);
+}
 
 struct DirectChoice {
   int wk, nt;      // wk == 0: not applicable
@@ -1021,6 +1244,15 @@ Choice choose(const ConvParams& p, int dtype) {
   return c;
 }
 
+// The mid-size kernel takes a launch that the operand-direct kernels would otherwise take
+// (the tiled kernel keeps the layers large enough for its 128-wide tiles to cover the chip)
+// unless the 16 x 16-tile kernel finishes it in one round of workgroups.
+LdsChoice lds_applies(const ConvParams& p, int dtype, const Choice& c, const DirectChoice& d) {
+  if (c.shape == S256x256 || (c.splits == 1 && (c.shape == S128x128 || c.shape == S128x64))) return {0, 0};
+  if (d.wk && d.narrow) return {0, 0};
+  return choose_lds(p, dtype);
+}
+
 template <typename T>
 hipError_t launch_finish(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
   const long work = (long)p.M * ((p.C_out + 3) / 4);
@@ -1048,6 +1280,16 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
   if ((size_t)p.N * p.x_rows * p.W * p.C_in * sizeof(T) >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   const Choice c = choose(p, dtype);
   const DirectChoice d = choose_direct(p, dtype, c.splits);
+  const LdsChoice ld = lds_applies(p, dtype, c, d);
+  if (ld.bm) {
+    p.ws = nullptr;
+    if constexpr (sizeof(T) == 2) {
+      if (ld.bm == 64) return launch_lds<T, 64, 64, 4>(p, s, ev);
+      return launch_lds<T, 32, 64, 4>(p, s, ev);
+    } else {
+      return launch_lds<T, 32, 32, 6>(p, s, ev);
+    }
+  }
   if (d.wk) {
     if (d.z > 1 && !ws) return hipErrorInvalidValue;
     p.splits = d.z;
@@ -1108,6 +1350,7 @@ size_t conv_workspace_bytes(const OpLaunch& L) {
   if (p.M <= 0) return 0;
   const Choice c = choose(p, L.dtype);
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
+  if (lds_applies(p, L.dtype, c, d).bm) return 0;
   if (d.wk) return d.z > 1 ? (size_t)d.z * p.M * p.C_out * sizeof(float) : 0;
   return c.splits > 1 ? (size_t)c.splits * p.M * p.C_out * sizeof(float) : 0;
 }
@@ -1127,6 +1370,11 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const Choice c = choose(p, L.dtype);
   static const int wm[] = {2, 2, 2, 4, 2}, wn[] = {2, 2, 2, 1, 4};
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
+  if (const LdsChoice ld = lds_applies(p, L.dtype, c, d); ld.bm) {
+    if (name && size)
+      snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
+    return 1;
+  }
   if (d.wk) {
     if (name && size) {
       if (d.narrow) snprintf(name, size, "conv_narrow_kernel<%s>", bf ? "__bf16" : "float");

@@ -62,15 +62,23 @@ struct Session {
   std::vector<hipEvent_t> events;
   hipEvent_t t0 = nullptr, t1 = nullptr;
   ~Session() {
+    // wait for all four streams, then release in the reverse order of dependence: events
+    // (recorded on, and waited for by, the streams) before the streams, buffers last
     for (Party& p : party) {
-      if (p.compute) { (void)hipStreamSynchronize(p.compute); (void)hipStreamDestroy(p.compute); }
-      if (p.link_in) { (void)hipStreamSynchronize(p.link_in); (void)hipStreamDestroy(p.link_in); }
-      if (p.arena) (void)lop::dev_free(p.arena);
-      if (p.ws) (void)lop::dev_free(p.ws);
+      if (p.compute) (void)hipStreamSynchronize(p.compute);
+      if (p.link_in) (void)hipStreamSynchronize(p.link_in);
     }
     for (hipEvent_t e : events) (void)hipEventDestroy(e);
     if (t0) (void)hipEventDestroy(t0);
     if (t1) (void)hipEventDestroy(t1);
+    for (Party& p : party) {
+      if (p.compute) (void)hipStreamDestroy(p.compute);
+      if (p.link_in) (void)hipStreamDestroy(p.link_in);
+    }
+    for (Party& p : party) {
+      if (p.arena) (void)lop::dev_free(p.arena);
+      if (p.ws) (void)lop::dev_free(p.ws);
+    }
   }
   hipError_t new_event(hipEvent_t* e) {
     const hipError_t rc = hipEventCreateWithFlags(e, hipEventDisableTiming);

@@ -29,6 +29,7 @@ struct Handle {
   bool alive = true;
   bool recorded = false;   // event
   bool capturing = false;  // stream
+  const void* on = nullptr; // event: the stream it was last recorded on
   size_t bytes = 0;        // allocation
 };
 
@@ -218,6 +219,11 @@ hipError_t hipStreamCreateWithFlags(hipStream_t* s, unsigned) {
 hipError_t hipStreamDestroy(hipStream_t s) {
   std::lock_guard<std::mutex> l(g_mu);
   if (use(s, kStream, "hipStreamDestroy").capturing) die("hipStreamDestroy of capturing stream %p", (void*)s);
+  // house rule of the library (stricter than the API): an event is released before the stream
+  // it was recorded on, so that no live event ever refers to a stream that is gone
+  for (const auto& kv : g_handles)
+    if (kv.second.kind == kEvent && kv.second.alive && kv.second.on == (const void*)s)
+      die("hipStreamDestroy of stream %p while event %p recorded on it is alive", (void*)s, kv.first);
   kill(s, kStream, "hipStreamDestroy");
   return hipSuccess;
 }
@@ -264,7 +270,9 @@ hipError_t hipEventDestroy(hipEvent_t e) {
 hipError_t hipEventRecord(hipEvent_t e, hipStream_t s) {
   std::lock_guard<std::mutex> l(g_mu);
   use_stream(s, "hipEventRecord");
-  use(e, kEvent, "hipEventRecord").recorded = true;
+  Handle& h = use(e, kEvent, "hipEventRecord");
+  h.recorded = true;
+  h.on = s;
   return hipSuccess;
 }
 hipError_t hipEventSynchronize(hipEvent_t e) {

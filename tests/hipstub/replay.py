@@ -171,6 +171,49 @@ def scheduling_model_and_two_party():
         release(h_out)
         plan.destroy()
         n += 1
+    def two_party_case(chain, t, sched, bw=1e12, lat=0.0, costs=None):
+        plan = lop.Plan(chain, t, 1)
+        d_in, d_out, h_out = buffers(chain, plan)
+        plan.run_two_party(d_in, d_out, [(a["M"], a["R"]) for a in sched], bw, lat, costs)
+        release(h_out)
+        plan.destroy()
+
+    heights_of = lambda ch: [sh[2] for sh in planner.infer_shapes(ch)]
+    # the schedules of the other two-party GPU tests, case by case
+    for mk, kw in ((workloads.tiny_chain, {}), (workloads.resnet18_chain, dict(h=64, w=48)),
+                   (workloads.mbv2_chain, dict(h=48, w=40, n=2)), (workloads.detector_chain, dict(h=90, w=64)),
+                   (workloads.vgg16_chain, dict(h=64, w=32))):
+        chain = mk(**kw)
+        t = workloads.make_tensors(chain, zero_bias=False)
+        for seed in range(3):
+            two_party_case(chain, t, workloads.random_schedule(heights_of(chain), seed=200 + seed, overlap=3))
+            n += 1
+    chain = workloads.resnet18_chain(h=40, w=24)
+    chain.layers = chain.layers[:4]
+    t = workloads.small_int_tensors(chain, seed=4)
+    for seed in (1, 2):
+        two_party_case(chain, t, workloads.random_schedule(heights_of(chain), seed=seed, overlap=2))
+        n += 1
+    from oracle import two_party as tp_oracle
+    chain = workloads.resnet18_chain(h=64, w=48)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    for party in ("M", "R"):
+        two_party_case(chain, t, tp_oracle.all_on(chain, party))
+        n += 1
+    shapes = planner.infer_shapes(chain)
+    costs = []
+    for i, L in enumerate(chain.layers):
+        nn, c, h, w = shapes[i]
+        costs.append(loss.LossLayer(n_ops=h, input_from=L.input_from, residual_from=L.residual_from,
+                                    k=L.k[0], s=L.s[0], p=L.p[0], d=L.d[0], cm_fixed=5e-4, cm_row=5e-5,
+                                    cr_fixed=2e-4, cr_row=1e-5, row_bytes=float(nn * c * w * 4)))
+    nn, c, h, w = chain.in_shape
+    for seed in (1, 2, 3):
+        sched = workloads.random_schedule(heights_of(chain), seed=300 + seed, overlap=2)
+        lop.lop_loss_eval(costs, h, float(nn * c * w * 4), 20e6, 5e-4, [(a["M"], a["R"]) for a in sched],
+                          lop.LOP_LINK_QUEUED)
+        two_party_case(chain, t, sched, 20e6, 5e-4, costs)
+        n += 1
     for dtype, base in (("f32", 4321), ("f32", 8765), ("bf16", 4321)):
         rng = np.random.Generator(np.random.PCG64(base + (dtype == "bf16")))
         done = 0

@@ -96,6 +96,52 @@ def test_conv_random_within_tolerance(oracle, cfg, dtype):
     assert rel_err(dev, want) <= TOL[dtype]
 
 
+LDS_GRID = [
+    # dtype, c_in, c_out, k, s, p, d, shape(n,h,w), residual
+    ("bf16", 64, 128, 3, 1, 1, 1, (1, 82, 106), False),    # 64 x 64 tiles, ragged last pixel tile
+    ("bf16", 128, 72, 3, 1, 1, 1, (2, 60, 74), True),      # channels not a multiple of the tile, residual, batch 2
+    ("bf16", 64, 256, 3, 2, 1, 1, (1, 127, 100), False),   # stride 2
+    ("bf16", 192, 64, 1, 2, 0, 1, (1, 180, 140), False),   # 1 x 1 stride 2: 3 stages (tail only), 32 x 64 tiles
+    ("bf16", 64, 64, 3, 1, 2, 2, (1, 100, 88), False),     # dilation 2
+    ("bf16", 64, 64, 3, 1, 1, 1, (1, 60, 120), True),      # 32 x 64 tiles with residual
+    ("f32", 32, 64, 3, 1, 1, 1, (1, 74, 90), True),        # fp32: 32 x 32 tiles, K = 288
+    ("f32", 64, 96, 3, 2, 1, 1, (2, 90, 80), False),
+    ("f32", 96, 32, 5, 1, 2, 1, (1, 80, 94), False),       # 5 x 5: 75 stages
+]
+
+
+@pytest.mark.parametrize("cfg", LDS_GRID)
+def test_lds_staged_kernel(oracle, cfg):
+    """The mid-size kernel (global -> LDS loads, reduction split over the wavefronts): shapes
+    that select it, checked by name, random values against the oracle within tolerance and small
+    integers bit for bit, banded and in one band."""
+    dtype, c_in, c_out, k, s_, p_, d, shape, residual = cfg
+    chain = _single(workloads.CONV, c_in, c_out, k, s_, p_, d, "relu", dtype, shape, n_bands=2,
+                    residual=residual and c_in == c_out)
+    if residual and c_in != c_out:       # a residual needs a same-shape source: 1 x 1 producer
+        chain = workloads.Chain("single", (shape[0], c_in, shape[1], shape[2]), dtype, 2)
+        a = chain.add(workloads.CONV, c_in, c_out, k, s_, p_, d, "none")
+        chain.add(workloads.CONV, c_out, c_out, 3, 1, 1, 1, "relu", residual_from=a) if (c_out * (2 if dtype == "bf16" else 4)) % 128 == 0 \
+            else chain.add(workloads.ELTWISE, c_out, c_out, act="relu", residual_from=a)
+    t = workloads.make_tensors(chain, zero_bias=False, seed=11)
+    plan = lop.Plan(chain, t)
+    try:
+        names = {plan.layer_kernel(b, l)[0] for b in range(plan.n_bands) for l in range(plan.n_layers)}
+    finally:
+        plan.destroy()
+    assert any(nm.startswith("conv_lds_kernel<") for nm in names), names
+    want = oracle.run_chain(chain, t)
+    for bands in (None, 1):
+        dev, host = run_gpu(chain, t, n_bands=bands)
+        np.testing.assert_array_equal(dev, host)
+        assert rel_err(dev, want) <= TOL[dtype], bands
+    ti = workloads.small_int_tensors(chain, seed=5)
+    want = oracle.run_chain(chain, ti)
+    if np.abs(want).max() < (256 if dtype == "bf16" else 2 ** 24):
+        dev, _ = run_gpu(chain, ti)
+        np.testing.assert_array_equal(dev, want)
+
+
 def test_small_layer_kernel_is_selected():
     """The grid above reaches every variant of the small-layer kernel: one launch, and a
     launch cut across workgroups followed by the finish kernel."""
