@@ -790,12 +790,15 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   constexpr int PIECES = BM * (BN / VE);    // 16-byte output pieces of the tile
   constexpr int RED_BYTES = 4 * BM * CP * 4;
   constexpr int SMEM = NST * STAGE > RED_BYTES ? NST * STAGE : RED_BYTES;
-  static_assert(BM % 32 == 0 && BN % 32 == 0 && NST >= 2 && (NST - 2) * LPS < 64, "tile shape");
+  static_assert(BM % 32 == 0 && BN % 32 == 0 && NST >= 2 && (NST - 2) * LPS < 64 && NST * STAGE <= 160 * 1024, "tile shape");
   __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+  // every XCD takes a contiguous stretch of the tiles (a few pixel tiles times the channel
+  // tiles), so that its L2 pulls a part of each operand instead of all of both
+  const TileId tile = xcd_tile(gridDim.x, gridDim.y, 1);
+  const int m0 = tile.m * BM, co0 = tile.n * BN;
   const unsigned char* __restrict__ xg = (const unsigned char*)p.x;
   const unsigned char* __restrict__ wg = (const unsigned char*)p.w;
   const int ns = p.k_pad / SKE;             // stages
@@ -823,33 +826,56 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
     b_off[i] = (unsigned)(((co0 + (wave * B_LD + i) * 8 + lrow) * p.k_pad + chunk * KE) * (int)sizeof(T));
   const int tap_row = p.dh * p.W * p.C_in * (int)sizeof(T), tap_col = p.dw * p.C_in * (int)sizeof(T);
 
+  // Workgroups that share an operand tile (the same pixels, or the same channels) would all ask
+  // for the same cache lines at the same moment if they walked the reduction axis in step, and
+  // the one that runs ahead would take every L2 miss of that tile by itself. Each workgroup
+  // therefore starts at a stage of its own and wraps around: the first touches of a tile are
+  // spread over the workgroups that share it. (The order of summation then depends on the tile
+  // index; it is fixed for a given launch.)
+  int st = (tile.m * 5 + tile.n * 11) % ns;
   // position of the next stage to issue on the reduction axis: k = (ia*kw + ib)*C_in + ici
-  int ia = 0, ib = 0, ici = 0, issued = 0;
-  auto issue = [&]() __attribute__((always_inline)) {
-    unsigned char* const dst = smem + (issued % NST) * STAGE;
-    const int toff = ia * tap_row + ib * tap_col + ici * (int)sizeof(T);
-    const int dih = ia * p.dh, diw = ib * p.dw;
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-      const int ih = a_ih0[i] + dih, iw = a_iw0[i] + diw;
-      const bool ok = (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows) & (iw >= 0) & (iw < p.W) & (ia < p.kh);
-      const unsigned char* src = ok ? xg + (a_off[i] + toff) : g_zero_line + (lane & 7) * 16;
+  int ia, ib, ici, issued = 0;
+  {
+    const int k0 = st * SKE, tap = k0 / p.C_in;
+    ici = k0 - tap * p.C_in;
+    ia = tap / p.kw;
+    ib = tap - ia * p.kw;
+  }
+  const unsigned char* const zero_src = g_zero_line + (lane & 7) * 16;  // what a padding tap fetches
+  // One load instruction of the stage being issued: j < A_LD a pixel group, else a channel group.
+  unsigned char* dst = smem;
+  int toff = 0, dih = 0, diw = 0;
+  unsigned koff = 0;
+  auto issue_begin = [&]() __attribute__((always_inline)) {
+    dst = smem + (issued % NST) * STAGE;
+    toff = ia * tap_row + ib * tap_col + ici * (int)sizeof(T);
+    dih = ia * p.dh;
+    diw = ib * p.dw;
+    koff = (unsigned)st * (unsigned)(SKE * (int)sizeof(T));
+  };
+  auto issue_one = [&](int j) __attribute__((always_inline)) {
+    if (j < A_LD) {
+      const int ih = a_ih0[j] + dih, iw = a_iw0[j] + diw;
+      const bool ok = (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows) & (iw >= 0) & (iw < p.W);
+      const unsigned char* src = ok ? xg + (a_off[j] + toff) : zero_src;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(dst + (wave * A_LD + i) * 1024),
+                                       (__attribute__((address_space(3))) void*)(dst + (wave * A_LD + j) * 1024),
                                        16, 0, 0);
-    }
-    const unsigned koff = (unsigned)issued * (unsigned)(SKE * (int)sizeof(T));
-#pragma unroll
-    for (int i = 0; i < B_LD; ++i)
+    } else {
+      const int i = j - A_LD;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wg + b_off[i] + koff),
                                        (__attribute__((address_space(3))) void*)(dst + A_BYTES + (wave * B_LD + i) * 1024),
                                        16, 0, 0);
+    }
+  };
+  auto issue_end = [&]() __attribute__((always_inline)) {
     ++issued;
     ici += SKE;
     if (ici >= p.C_in) {
       ici = 0;
       if (++ib == p.kw) { ib = 0; ++ia; }
     }
+    if (++st == ns) { st = 0; ia = 0; ib = 0; ici = 0; }
   };
 
   f32x16 acc[TN][TM];
@@ -870,9 +896,9 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   // hand instead: vmcnt before the barrier for the stage about to be read, lgkmcnt behind the
   // reads (tied to the fragment registers, so no MFMA can move in front of it).
   const unsigned lds0 = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char*)smem + foff;
-  auto multiply = [&](int s) __attribute__((always_inline)) {
+  u32x4 px[TM], wt[TN];
+  auto read_fragments = [&](int s) __attribute__((always_inline)) {
     const unsigned at = lds0 + (unsigned)((s % NST) * STAGE);
-    u32x4 px[TM], wt[TN];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
       asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(px[tm]) : "v"(at), "n"(tm * 4096) : "memory");
@@ -889,33 +915,68 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
       static_assert(TM == 1 && TN == 1, "tile shapes up to 64 x 64");
       asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(wt[0]) :: "memory");
     }
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm) mma<T>(wt[tn], px[tm], acc[tn][tm]);
   };
   auto stage_barrier = [&]() __attribute__((always_inline)) {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
+  // The MFMAs of the stage in the fragment registers, with the load instructions of a later stage
+  // between them (LOADS: whether there is one to issue): a wavefront issues in order and a load
+  // waits at issue until the memory pipeline takes it, so behind an MFMA that wait overlaps the
+  // MFMA's execution instead of adding to it.
+  auto multiply = [&](bool loads) __attribute__((always_inline)) {
+    constexpr int NM = TM * TN;
+    if (loads) issue_begin();
+#pragma unroll
+    for (int i = 0; i < (NM > LPS ? NM : LPS); ++i) {
+      if (i < NM) {
+        mma<T>(wt[i / TM], px[i % TM], acc[i / TM][i % TM]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (loads && i < LPS) {
+        issue_one(i);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (loads) issue_end();
+  };
 
-  // ---- NST - 1 stages in flight; one barrier per stage: behind it stage s is complete for
-  // every wavefront and nobody reads stage s - 1 any more, whose buffer the next issue reuses
+  // ---- NST - 1 stages in flight; one barrier per stage: behind it the next stage is complete
+  // for every wavefront and nobody reads the stage before this one any more, whose buffer the
+  // loads issued among this stage's MFMAs reuse
   const int pre = min(ns, NST - 1);
-  for (int s = 0; s < pre; ++s) issue();
+  for (int s = 0; s < pre; ++s) {
+    issue_begin();
+#pragma unroll
+    for (int j = 0; j < LPS; ++j) issue_one(j);
+    issue_end();
+  }
+  if (ns > NST - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LPS));
+  else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+  stage_barrier();
+  read_fragments(0);
   int s = 0;
-  for (; s + NST - 1 < ns; ++s) {
+  for (; s + NST < ns; ++s) {  // stage s + NST - 1 exists and so does stage s + 1
+    multiply(true);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LPS));
     stage_barrier();
-    issue();
-    multiply(s);
+    read_fragments(s + 1);
   }
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  for (; s < ns; ++s) {
+  if (s + NST - 1 < ns) {  // the last stage to issue
+    multiply(true);
+    ++s;
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     stage_barrier();
-    multiply(s);
+    read_fragments(s);
+  } else {
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   }
+  for (; s + 1 < ns; ++s) {  // everything is in LDS (and stays: no barrier needed any more)
+    multiply(false);
+    read_fragments(s + 1);
+  }
+  multiply(false);
 
   // ---- add the four partial tiles in wavefront order through LDS, then the epilogue on
   // 16-byte pieces (a lane of the accumulator holds pixel lane & 31 and channels
@@ -1098,20 +1159,20 @@ constexpr int kComputeUnits = 256;
 constexpr int kNarrowMaxTiles = 320;
 
 // The LDS-staged mid-size kernel: which tile, or bm == 0 when it does not apply.
-struct LdsChoice { int bm, bn; };
+struct LdsChoice { int bm, bn; long tiles; };
 LdsChoice choose_lds(const ConvParams& p, int dtype) {
   const int esz = dtype == LOP_BF16 ? 2 : 4, ke = 16 / esz;
-  if ((p.C_in * esz) % 128 != 0 || p.C_out % ke != 0 || p.k_pad != p.K) return {0, 0};
+  if ((p.C_in * esz) % 128 != 0 || p.C_out % ke != 0 || p.k_pad != p.K) return {0, 0, 0};
   // 32-bit signed byte offsets into the input slab
-  if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return {0, 0};
+  if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return {0, 0, 0};
   auto tiles = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn); };
   if (dtype == LOP_BF16) {
-    if (tiles(64, 64) >= kLdsMinTiles) return {64, 64};
-    if (tiles(32, 64) >= kLdsMinTiles) return {32, 64};
-    return {0, 0};
+    if (tiles(64, 64) >= kLdsMinTiles) return {64, 64, tiles(64, 64)};
+    if (tiles(32, 64) >= kLdsMinTiles) return {32, 64, tiles(32, 64)};
+    return {0, 0, 0};
   }
-  if (tiles(32, 32) >= kLdsMinTiles) return {32, 32};
-  return {0, 0};
+  if (tiles(32, 32) >= kLdsMinTiles) return {32, 32, tiles(32, 32)};
+  return {0, 0, 0};
 }
 
 template <typename T, int BM, int BN, int NST>
@@ -1248,8 +1309,8 @@ Choice choose(const ConvParams& p, int dtype) {
 // (the tiled kernel keeps the layers large enough for its 128-wide tiles to cover the chip)
 // unless the 16 x 16-tile kernel finishes it in one round of workgroups.
 LdsChoice lds_applies(const ConvParams& p, int dtype, const Choice& c, const DirectChoice& d) {
-  if (c.shape == S256x256 || (c.splits == 1 && (c.shape == S128x128 || c.shape == S128x64))) return {0, 0};
-  if (d.wk && d.narrow) return {0, 0};
+  if (c.shape == S256x256 || (c.splits == 1 && (c.shape == S128x128 || c.shape == S128x64))) return {0, 0, 0};
+  if (d.wk && d.narrow) return {0, 0, 0};
   return choose_lds(p, dtype);
 }
 
@@ -1284,6 +1345,9 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
   if (ld.bm) {
     p.ws = nullptr;
     if constexpr (sizeof(T) == 2) {
+      // (twice the stages in flight, 128 KB of LDS, measured no faster per launch - the loop is
+      // bound by what the L2s deliver, not by latency - and it keeps other streams' workgroups
+      // off the compute unit)
       if (ld.bm == 64) return launch_lds<T, 64, 64, 4>(p, s, ev);
       return launch_lds<T, 32, 64, 4>(p, s, ev);
     } else {
