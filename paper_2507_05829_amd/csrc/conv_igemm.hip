@@ -1038,7 +1038,7 @@ __device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f
 }
 
 constexpr int kNarrowWaves = 16;
-constexpr int kLdsMinTiles = 96;   // fewer tiles than this leave most of the chip idle
+constexpr int kLdsMinTiles = 48;   // below this the operand-direct kernels (one round of latency) win; 96 and 20 measured slower
 
 template <typename T>
 __global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const ConvParams p) {
