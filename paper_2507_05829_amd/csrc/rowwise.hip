@@ -159,17 +159,20 @@ __global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
 
 
 // Depthwise 3x3 (dilation 1, pad 1, stride S in both directions), register blocked: a
-// thread owns VEC channels of one output column and kDwRowsPerThread consecutive output
+// thread owns VEC channels of one output column and dw_rows_per_thread(S) consecutive output
 // rows; it loads the (rows-1)*S + 3 input rows it needs (3 vectors each) and the 9 x VEC
 // weights once, so an output costs about S + 0.5 vector loads instead of 9 loads plus 9
 // weight loads. Threads of a workgroup are (channel vector, column) with the channel
 // vector fastest: loads and stores of a wavefront stay contiguous and the left/right
 // neighbours' columns come out of the same CU's L1. No residual (rowwise_kernel has it).
-constexpr int kDwRowsPerThread = 4;
+// Output rows per thread: the (rows - 1) * S + 3 input rows are read once per thread, so the
+// rows shared with the chunk above and below are fetched twice: 6 for 4 with stride 1 (1.5 x),
+// 10 for 8 (1.25 x); with stride 2, 9 for 4 is 1.125 x already.
+constexpr int dw_rows_per_thread(int stride) { return stride == 1 ? 8 : 4; }
 struct Dw3Params {
   RowParams r;
   int cols_per_block;  // output columns per workgroup
-  int chunks;          // row chunks (kDwRowsPerThread output rows each) per image
+  int chunks;          // row chunks (dw_rows_per_thread output rows each) per image
 };
 
 // Raw 8- or 16-byte vector of the storage type and its expansion to fp32 values.
@@ -203,7 +206,7 @@ template <typename T, int VEC, int S>
 __global__ __launch_bounds__(256) void dwconv3x3_kernel(const Dw3Params q) {
   static_assert(VEC * sizeof(T) == 16 || VEC * sizeof(T) == 8, "8- or 16-byte vectors");
   typedef typename RawVec<VEC * sizeof(T)>::type Raw;
-  constexpr int RPT = kDwRowsPerThread;    // output rows per thread
+  constexpr int RPT = dw_rows_per_thread(S);  // output rows per thread
   constexpr int NR = (RPT - 1) * S + 3;    // input rows they read
   const RowParams& p = q.r;
   const int cv = p.C / VEC;
@@ -281,7 +284,8 @@ hipError_t launch_dw3(const RowParams& p, hipStream_t s, KernelEvents* ev) {
   q.r = p;
   const int cv = p.C / VEC;
   q.cols_per_block = std::max(1, 256 / cv);
-  q.chunks = (p.R + kDwRowsPerThread - 1) / kDwRowsPerThread;
+  const int rpt = dw_rows_per_thread(p.sh);
+  q.chunks = (p.R + rpt - 1) / rpt;
   dim3 grid((p.W_out + q.cols_per_block - 1) / q.cols_per_block, q.chunks * p.N);
   return p.sh == 1 ? launch_kernel(dwconv3x3_kernel<T, VEC, 1>, grid, dim3(256), s, ev, q)
                    : launch_kernel(dwconv3x3_kernel<T, VEC, 2>, grid, dim3(256), s, ev, q);
