@@ -117,7 +117,12 @@ typedef struct {
 #define LOP_FLAG_LANES(n) (((unsigned)(n) & 0xffu) << 8) /* bands are dealt round robin to n
                                  compute streams ("lanes", each with its own scratch) that run
                                  concurrently; 0 = LOP_DEFAULT_LANES, capped at the number of
-                                 non-empty bands                                          */
+                                 non-empty bands. With three or more lanes, independent
+                                 bands whose copies are long (more than 256 KiB per band,
+                                 at most 64 MiB per chain) leave one lane to the copies:
+                                 n - 1 lanes compute, and a lop_run_chain without
+                                 compute_stream and timing sends every band's copy to the
+                                 last lane behind an event                                */
 #define LOP_FLAG_GRAPH 4u     /* lop_run_chain (without timing) captures its launches and copies
                                  into a HIP graph on the first call for a given (d_in, d_out,
                                  h_out) and replays it afterwards; the graph joins the copies,

@@ -20,7 +20,7 @@ namespace lop {
 hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
 hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
 hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
-                            hipStream_t stream);
+                            hipStream_t stream, int workgroups);
 hipError_t launch_fill_words(void* dst, size_t bytes, unsigned word, hipStream_t stream);
 
 hipError_t launch_pointwise(const OpLaunch& L, hipStream_t stream, KernelEvents* ev);
@@ -410,6 +410,13 @@ void* device_view_of_host(lop_plan_t* P, void* h_out);
 // wait for on the lane. Larger outputs keep the paced copy kernel (stores over PCIe from a
 // whole grid hold up the HBM writes of the kernels beside them).
 constexpr size_t kDirectHostStoreMax = 256 * 1024;
+// Workgroups of a band copy that shares a stream with kernels: its stores are paced by the
+// link, and many of them in flight hold up the HBM writes of the kernels running beside the
+// copy (4 workgroups move about 30 GB/s; with 64 the copy was 1.7x faster and the other
+// streams lost more than that; on a lane of its own 8 and 16 workgroups cost the chains beside
+// it 8 % and 13 %).
+constexpr int kCopyWorkgroups = 4;
+constexpr size_t kCopyLaneMaxBytes = (size_t)64 << 20;
 
 // Device view of h_out if band `band` can deliver its rows that way, else nullptr.
 void* direct_host_target(lop_plan_t* P, int band, void* h_out) {
@@ -484,7 +491,7 @@ int enqueue_band_copy(lop_plan_t* P, int band, const void* d_out, void* h_out, h
   if (P->flags & LOP_FLAG_DMA_COPY) mapped = nullptr;
   if (mapped) {
     LOP_HIP(lop::launch_copy_rows((char*)mapped + off, (const char*)d_out + off, img_b, len,
-                                  t.in.n, s));
+                                  t.in.n, s, kCopyWorkgroups));
     return LOP_OK;
   }
   if (t.in.n == 1) {
@@ -521,9 +528,32 @@ int setup_device(lop_plan_t* P) {
   if (want == 0) want = LOP_DEFAULT_LANES;
   const int n_lanes = P->t.reuse ? std::max(1, want) : std::max(1, std::min(want, live));
   P->lanes.assign(n_lanes, Lane{});
+  // Long band copies (stores into host memory, paced by the link) get a lane of their own.
+  // On a compute lane a copy holds up that lane's next band, and because the bands are equal
+  // the lanes reach their copies together: all of them copy at once, at the link's rate, with
+  // nothing computing beside them, and then all compute at once with the link idle.
+  size_t longest_copy = 0, all_copies = 0;
+  for (int b = 0; b < nb; ++b) {
+    const lop_rows_t r = P->t.bands[b].need[P->t.n_layers()];
+    if (r.hi <= r.lo) continue;
+    const size_t bytes = (size_t)P->t.in.n * (r.hi - r.lo) * P->t.row_elems(P->t.n_layers() - 1) * P->t.esz();
+    longest_copy = std::max(longest_copy, bytes);
+    all_copies += bytes;
+  }
+  // Independent bands only: in reuse mode a lane holds a whole chain, and three chains in
+  // flight plus a copy lane measured slower than four chains that copy on their own lanes.
+  // Not for chains whose result is so large that the copies, one after another at the copy
+  // kernel's 30 GB/s, would take longer than the kernels (a matrix product chain with 134 MB of
+  // output per call: 215 calls/s with the copy lane, 350 with copies on every lane, which
+  // together reach the link's rate). The plan does not know the kernels' time; the bound on the
+  // bytes stands for it.
+  P->copy_lane = !P->t.reuse && n_lanes >= 3 && longest_copy > kDirectHostStoreMax &&
+                 all_copies <= kCopyLaneMaxBytes &&
+                 !(P->flags & (LOP_FLAG_NO_D2H | LOP_FLAG_DMA_COPY));
   for (Lane& L : P->lanes) {
-    if (P->arena_bytes) LOP_HIP(lop::dev_alloc(&L.arena, align_up(P->arena_bytes, 256)));
-    if (P->conv_ws_bytes) {
+    const bool computes = !P->copy_lane || &L != &P->lanes.back();
+    if (P->arena_bytes && computes) LOP_HIP(lop::dev_alloc(&L.arena, align_up(P->arena_bytes, 256)));
+    if (P->conv_ws_bytes && computes) {
       LOP_HIP(lop::dev_alloc(&L.conv_ws, P->conv_ws_bytes));
     }
     LOP_HIP(hipStreamCreateWithFlags(&L.stream, hipStreamNonBlocking));
@@ -649,25 +679,29 @@ int enqueue_lane(lop_plan_t* P, int lane, const void* d_in, void* d_out, void* h
 
 // lane_only >= 0 (independent mode): the graph holds that lane's bands only and runs on the
 // lane's stream `ms`; -1: the whole chain forked from and joined into `ms`.
+// band_only >= 0: the graph holds that band's kernels and nothing else (its copy is the
+// caller's business).
 int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms,
-                 int lane_only = -1) {
+                 int lane_only = -1, int band_only = -1) {
   const int lane = P->t.reuse ? P->cur_lane : (lane_only >= 0 ? lane_only : -1);
   // an eager run may still have copies of the output rows in flight (on a copy stream that the
   // graph's stream is not ordered behind): a replay, and the first capture, wait for them
   for (int b = 0; b < P->t.n_bands; ++b)
-    if (P->copied_valid[b]) {
+    if (P->copied_valid[b] && (band_only < 0 || b == band_only)) {
       LOP_HIP(hipStreamWaitEvent(ms, P->ev_copied[b], 0));
       P->copied_valid[b] = 0;
     }
   for (const auto& g : P->graphs)
-    if (g.d_in == d_in && g.d_out == d_out && g.h_out == h_out && g.lane == lane) {
+    if (g.d_in == d_in && g.d_out == d_out && g.h_out == h_out && g.lane == lane &&
+        g.band == band_only) {
       LOP_HIP(hipGraphLaunch(g.exec, ms));
       return LOP_OK;
     }
   if (h_out) (void)device_view_of_host(P, h_out);  // query before capture starts
   hipGraph_t graph = nullptr;
   LOP_HIP(hipStreamBeginCapture(ms, hipStreamCaptureModeThreadLocal));
-  int rc = P->t.reuse ? enqueue_chain_reuse(P, d_in, d_out, h_out, false, true)
+  int rc = band_only >= 0 ? enqueue_band_kernels(P, band_only, d_in, d_out, ms)
+           : P->t.reuse  ? enqueue_chain_reuse(P, d_in, d_out, h_out, false, true)
            : lane_only >= 0 ? enqueue_lane(P, lane_only, d_in, d_out, h_out, true)
                             : enqueue_chain(P, d_in, d_out, h_out, ms, false, true);
   hipError_t e = hipStreamEndCapture(ms, &graph);
@@ -684,8 +718,33 @@ int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipS
     (void)hipGraphExecDestroy(P->graphs.front().exec);
     P->graphs.erase(P->graphs.begin());
   }
-  P->graphs.push_back({d_in, d_out, h_out, lane, exec});
+  P->graphs.push_back({d_in, d_out, h_out, lane, band_only, exec});
   LOP_HIP(hipGraphLaunch(exec, ms));
+  return LOP_OK;
+}
+
+// Copy-lane schedule of one band: its kernels on compute stream `cs` (as a graph of their own
+// when graphs are on), its copy on the copy lane behind the band's "kernels finished" event.
+int enqueue_band_with_copy_lane(lop_plan_t* P, int band, const void* d_in, void* d_out,
+                                void* h_out, hipStream_t cs) {
+  hipStream_t ds = P->lanes.back().stream;
+  int rc;
+  if (P->flags & LOP_FLAG_GRAPH) {
+    rc = launch_graph(P, d_in, d_out, nullptr, cs, P->lane_index(band), band);
+  } else {
+    if (P->copied_valid[band]) {  // these rows of d_out may still be on their way to the host
+      LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[band], 0));
+      P->copied_valid[band] = 0;
+    }
+    rc = enqueue_band_kernels(P, band, d_in, d_out, cs);
+  }
+  if (rc != LOP_OK) return rc;
+  LOP_HIP(hipEventRecord(P->ev_done[band], cs));
+  LOP_HIP(hipStreamWaitEvent(ds, P->ev_done[band], 0));
+  rc = enqueue_band_copy(P, band, d_out, h_out, ds);
+  if (rc != LOP_OK) return rc;
+  LOP_HIP(hipEventRecord(P->ev_copied[band], ds));
+  P->copied_valid[band] = 1;
   return LOP_OK;
 }
 
@@ -894,6 +953,15 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
     if (rc != LOP_OK) return rc;
   }
   const auto t0 = std::chrono::steady_clock::now();
+  if (P->copy_lane && copy && !compute_stream && !timing) {
+    // Compute lanes run free, as below; every band's copy goes to the copy lane.
+    for (int b = 0; b < nb; ++b) {
+      if (band_empty(P, b)) continue;
+      int rc = enqueue_band_with_copy_lane(P, b, d_in, d_out, h_out, P->lane_of(b).stream);
+      if (rc != LOP_OK) return rc;
+    }
+    return LOP_OK;
+  }
   if (P->t.reuse) {
     // the whole chain runs on one lane; chains of consecutive calls rotate over the lanes
     // and overlap unless the caller's stream orders them

@@ -62,6 +62,7 @@ struct lop_plan_s {
   struct GraphEntry {
     const void* d_in; void* d_out; void* h_out;
     int lane;
+    int band;  // -1: every band of the lane (or chain); else that band's kernels only
     hipGraphExec_t exec;
   };
   std::vector<GraphEntry> graphs;  // LOP_FLAG_GRAPH: one instantiated graph per pointer set
@@ -70,10 +71,14 @@ struct lop_plan_s {
   int cur_lane = 0;   // reuse mode: the lane the chain being enqueued runs on
   int next_lane = 0;  // reuse mode: rotates with every lop_run_chain
 
-  int n_lanes() const { return (int)lanes.size(); }
+  // The last lane carries nothing but band copies when the bands' copies are long (see
+  // setup_device): the other lanes never wait for a copy, and the copies of equal bands, which
+  // would otherwise all fall into the same moments, follow each other on one stream.
+  bool copy_lane = false;
+  int n_lanes() const { return (int)lanes.size() - (copy_lane ? 1 : 0); }  // lanes that compute
   // Independent bands are dealt to the lanes round robin; in reuse mode a whole chain (all
   // bands, in order) runs on one lane and consecutive chains rotate over the lanes.
-  int lane_index(int band) const { return t.reuse ? cur_lane : band % (int)lanes.size(); }
+  int lane_index(int band) const { return t.reuse ? cur_lane : band % n_lanes(); }
   Lane& lane_of(int band) { return lanes[lane_index(band)]; }
   const Lane& lane_of(int band) const { return lanes[lane_index(band)]; }
   // While lop_run_chain_static enqueues, scratch comes from the library's static device array

@@ -369,13 +369,13 @@ hipError_t launch_fill_words(void* dst, size_t bytes, unsigned word, hipStream_t
 }
 
 hipError_t launch_copy_rows(void* dst, const void* src, size_t pitch, size_t len, int n,
-                            hipStream_t stream) {
+                            hipStream_t stream, int workgroups) {
   if (len == 0 || n <= 0) return hipSuccess;
   const size_t vec = (len + 15) / 16;
   // Few workgroups on purpose: the stores are paced by PCIe, and many of them in flight
   // hold up the HBM writes of the kernels running beside the copy (4 workgroups still move
   // about 30 GB/s; with 64 the copy was 1.7x faster and the other streams lost more than that).
-  const unsigned grid = (unsigned)std::min<size_t>((vec + 255) / 256, 4);
+  const unsigned grid = (unsigned)std::min<size_t>((vec + 255) / 256, (size_t)std::max(1, workgroups));
   hipLaunchKernelGGL(copy_rows_kernel, dim3(grid), dim3(256), 0, stream, (char*)dst,
                      (const char*)src, pitch, len, n);
   return hipGetLastError();

@@ -83,7 +83,8 @@ def random_chain_sets():
 def named_workloads():
     n = 0
     scaled = [workloads.tiny_chain(), workloads.resnet18_chain(h=64, w=48), workloads.vgg16_chain(h=64, w=64),
-              workloads.detector_chain(h=96, w=64), workloads.mbv2_chain(h=32, w=32, n=2, n_bands=4)]
+              workloads.detector_chain(h=96, w=64), workloads.mbv2_chain(h=32, w=32, n=2, n_bands=4),
+              workloads.mbv2_chain(h=192, w=192, n=8, n_bands=2)]   # long band copies: the copy lane
     for chain in scaled:
         t = workloads.make_tensors(chain, zero_bias=False)
         for flags in (0, lop.LOP_FLAG_REUSE, lop.LOP_FLAG_GRAPH, lop.LOP_FLAG_GRAPH | lop.LOP_FLAG_REUSE,
@@ -119,7 +120,10 @@ def named_workloads():
                     plan.layer_work(b, l)
             plan.stats()
             if hasattr(lop, "lop_run_chain_static") and not flags & lop.LOP_FLAG_REUSE:
-                lop.lop_run_chain_static(plan.handle, d_in, d_out, None)
+                try:
+                    lop.lop_run_chain_static(plan.handle, d_in, d_out, None)
+                except lop.LopError as e:   # layer by layer the large chain needs more than the array holds
+                    assert e.code == lop.LOP_ERR_TOO_LARGE and flags & lop.LOP_FLAG_NO_FUSE
                 plan.synchronize()
             if not flags:
                 heights = [plan.layer_shape(l)[2] for l in range(plan.n_layers)]

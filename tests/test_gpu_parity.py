@@ -373,6 +373,35 @@ def test_band_copies_through_the_copy_engines(oracle, name, kw):
     assert rel_err(dev, want) <= TOL[chain.dtype]
 
 
+@pytest.mark.parametrize("graph", [0, 1])
+def test_long_band_copies_on_the_copy_lane(oracle, graph):
+    """Independent bands whose copies are long (more than 256 KiB per band) leave through the
+    copy lane: three calls in a row on the same buffers (the second and third must wait for the
+    copies of the call before), then one into a second pair of buffers, every host result
+    equal to the device result and to the oracle."""
+    chain = workloads.mbv2_chain(h=192, w=192, n=8, n_bands=4)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    plan = lop.Plan(chain, t, None, lop.LOP_FLAG_GRAPH if graph else 0)
+    try:
+        n, c, h, w = plan.out_shape()
+        assert n * c * h * w * 2 // 4 > 256 * 1024
+        d_in = to_device_nhwc(t.x, chain.dtype)
+        pairs = [(empty_out(plan.out_shape(), chain.dtype), empty_out(plan.out_shape(), chain.dtype, pinned=True))
+                 for _ in range(2)]
+        for d_out, h_out in (pairs[0], pairs[0], pairs[0], pairs[1]):
+            h_out.fill_(float("nan"))
+            plan.run_chain(d_in, d_out, h_out)
+        plan.synchronize()
+        for d_out, h_out in pairs:
+            dev, host = to_nchw(d_out), to_nchw(h_out)
+            np.testing.assert_array_equal(host, dev)
+            assert rel_err(dev, want) <= TOL[chain.dtype]
+            check_margins(d_out, h_out)
+    finally:
+        plan.destroy()
+
+
 def test_host_memory_that_is_not_pinned_is_refused():
     """The boundary takes pinned host memory only: a pageable buffer is refused before anything
     is enqueued, by every call that takes a host pointer."""
