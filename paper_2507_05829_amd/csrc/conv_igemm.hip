@@ -54,6 +54,7 @@ struct ConvParams {
   int M;  // N * R * W_out
   int K, k_pad;
   int splits, kc_per_split;
+  int pool;  // conv_lds_kernel<..., true>: R, out_lo, W_out and y describe the 2 x 2 max-pooled tensor
 };
 
 __device__ __forceinline__ float apply_act(float v, int act) {
@@ -771,13 +772,20 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
 // on how the launch was cut. A tap outside the image (or the slab) is fetched from a
 // zero-filled device array instead of being masked afterwards. Needs C_in * sizeof(T) to be a
 // multiple of 128 (a stage never straddles two taps) and C_out a multiple of the 16-byte vector.
+//
+// POOL: a 2 x 2 stride-2 max pooling that follows the convolution is part of the launch. The
+// rows of the tile are then the convolution's pixels in the order (image, pooled row, pooled
+// column, position in the window), so every four consecutive rows are one window; the epilogue
+// takes their maximum per channel before bias, activation and rounding (all three are
+// non-decreasing, so the maximum of the rounded values is the rounded value of the maximum) and
+// stores pooled pixels: the convolution's own output never exists in memory.
 static __device__ __attribute__((aligned(256))) unsigned char g_zero_line[256];
 
 // s_waitcnt immediate that waits until at most n vector-memory operations are outstanding
 // and leaves the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
 constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
 
-template <typename T, int BM, int BN, int NST>
+template <typename T, int BM, int BN, int NST, bool POOL>
 __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   constexpr int KE = 16 / (int)sizeof(T);   // elements per 16-byte chunk
   constexpr int SKE = 8 * KE;               // reduction elements per stage (128 bytes per row)
@@ -811,11 +819,14 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   for (int i = 0; i < A_LD; ++i) {
     const int m = m0 + (wave * A_LD + i) * 8 + lrow;
     const bool ok = m < p.M;
-    const int mm = ok ? m : 0;
+    const int mm = ok ? (POOL ? m >> 2 : m) : 0;
     const int ow = mm % p.W_out;
     const int t = mm / p.W_out;
     const int r = t % p.R, n = t / p.R;
-    const int ih0 = (p.out_lo + r) * p.sh - p.ph, iw0 = ow * p.sw - p.pw;
+    // the convolution's output pixel behind this row of the tile
+    const int oy = POOL ? (p.out_lo + r) * 2 + ((m >> 1) & 1) : p.out_lo + r;
+    const int ox = POOL ? ow * 2 + (m & 1) : ow;
+    const int ih0 = oy * p.sh - p.ph, iw0 = ox * p.sw - p.pw;
     a_ih0[i] = ok ? ih0 : -(1 << 28);       // a row past the end of the launch: every tap "outside"
     a_iw0[i] = iw0;
     a_off[i] = (((n * p.x_rows - p.x_row0 + ih0) * p.W + iw0) * p.C_in + chunk * KE) * (int)sizeof(T);
@@ -992,6 +1003,31 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
         *(float4*)(mine + (tm * 32 + (lane & 31)) * CP + tn * 32 + g * 8 + (lane >> 5) * 4) =
             make_float4(acc[tn][tm][g * 4], acc[tn][tm][g * 4 + 1], acc[tn][tm][g * 4 + 2], acc[tn][tm][g * 4 + 3]);
   __syncthreads();
+  if constexpr (POOL) {
+    for (int piece = tid; piece < PIECES / 4; piece += 256) {
+      const int win = piece / (BN / VE), c = (piece % (BN / VE)) * VE;
+      const int m = m0 + win * 4, co = co0 + c;
+      if (m >= p.M || co >= p.C_out) continue;   // (M is a multiple of 4: whole windows)
+      float best[VE];
+#pragma unroll
+      for (int sub = 0; sub < 4; ++sub) {
+        float v[VE];
+#pragma unroll
+        for (int j = 0; j < VE; ++j) v[j] = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+          for (int j = 0; j < VE; j += 4) {
+            const float4 q = *(const float4*)((const float*)smem + w * (BM * CP) + (win * 4 + sub) * CP + c + j);
+            v[j] += q.x; v[j + 1] += q.y; v[j + 2] += q.z; v[j + 3] += q.w;
+          }
+#pragma unroll
+        for (int j = 0; j < VE; ++j) best[j] = sub == 0 ? v[j] : fmaxf(best[j], v[j]);
+      }
+      finish_vec<T, VE>(p, m >> 2, co, best);
+    }
+    return;
+  }
   for (int piece = tid; piece < PIECES; piece += 256) {
     const int row = piece / (BN / VE), c = (piece % (BN / VE)) * VE;
     const int m = m0 + row, co = co0 + c;
@@ -1179,7 +1215,8 @@ template <typename T, int BM, int BN, int NST>
 hipError_t launch_lds(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN);
   if ((int)grid.y * BN > conv_cout_pad(p.C_out) || grid.y > 65535) return hipErrorInvalidValue;
-  return launch_kernel(conv_lds_kernel<T, BM, BN, NST>, grid, dim3(256), s, ev, p);
+  if (p.pool) return launch_kernel(conv_lds_kernel<T, BM, BN, NST, true>, grid, dim3(256), s, ev, p);
+  return launch_kernel(conv_lds_kernel<T, BM, BN, NST, false>, grid, dim3(256), s, ev, p);
 }
 
 struct DirectChoice {
@@ -1398,6 +1435,7 @@ ConvParams make_params(const OpLaunch& L) {
   p.k_pad = L.k_pad;
   p.splits = 1;
   p.kc_per_split = 0;
+  p.pool = 0;
   return p;
 }
 
@@ -1436,7 +1474,7 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
   if (const LdsChoice ld = lds_applies(p, L.dtype, c, d); ld.bm) {
     if (name && size)
-      snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
+      snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, false>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
     return 1;
   }
   if (d.wk) {
@@ -1451,6 +1489,79 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
              c.bm, c.bn, wm[c.shape], wn[c.shape], c.shape == S256x256 ? kBigBKB : kBKB, kStages,
              vec ? "true" : "false");
   return c.splits;
+}
+
+// ---- convolution + the 2 x 2 stride-2 max pooling behind it as one launch (conv_lds_kernel<..., true>)
+
+namespace {
+// Parameters of the pooled launch: the convolution's operands and hyper-parameters with the
+// pooled tensor's rows, width and slab as the output.
+ConvParams make_pooled_params(const OpLaunch& conv, const OpLaunch& pool) {
+  OpLaunch o = conv;
+  o.y = pool.y;
+  o.y2 = pool.y2;
+  o.out_lo = pool.out_lo;
+  o.out_hi = pool.out_hi;
+  ConvParams p = make_params(o);
+  p.pool = 1;
+  p.M *= 4;
+  return p;
+}
+// The tile of a pooled launch: the LDS kernel always takes it (there is no other kernel that
+// pools), with the smaller pixel tile when the larger would leave most of the chip idle.
+LdsChoice choose_pooled(const ConvParams& p, int dtype) {
+  auto tiles = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn); };
+  if (dtype != LOP_BF16) return {32, 32, tiles(32, 32)};
+  if (tiles(64, 64) >= kLdsMinTiles) return {64, 64, tiles(64, 64)};
+  return {32, 64, tiles(32, 64)};
+}
+}  // namespace
+
+bool convpool_applies(const OpLaunch& conv, const OpLaunch& pool) {
+  if (conv.op != LOP_CONV2D || pool.op != LOP_MAXPOOL2D || conv.res.ptr) return false;
+  if (pool.kh != 2 || pool.kw != 2 || pool.sh != 2 || pool.sw != 2 || pool.ph != 0 || pool.pw != 0 ||
+      pool.dh != 1 || pool.dw != 1)
+    return false;
+  const int esz = conv.dtype == LOP_BF16 ? 2 : 4, ke = 16 / esz;
+  const int K = conv.x.c * conv.kh * conv.kw;
+  return (conv.x.c * esz) % 128 == 0 && conv.y.c % ke == 0 && conv.k_pad == K;
+}
+
+// Whether the pooled launch is worth taking for this launch of the conv (its own rows, its
+// slabs' geometry): not where the conv alone would run on one of the operand-direct kernels
+// (few pixels, a long reduction), which together with a separate pooling launch are faster
+// than the LDS kernel on so few tiles (8 + 4 us against 15-17 us on the 512-channel layers of
+// a banded VGG-16).
+bool convpool_pays(const OpLaunch& conv) {
+  const ConvParams p = make_params(conv);
+  if (p.M <= 0) return true;
+  const Choice c = choose(p, conv.dtype);
+  const DirectChoice d = choose_direct(p, conv.dtype, c.splits);
+  return !(d.wk && d.narrow);
+}
+
+hipError_t launch_convpool(const OpLaunch& conv, const OpLaunch& pool, hipStream_t stream, KernelEvents* ev) {
+  const ConvParams p = make_pooled_params(conv, pool);
+  if (p.M <= 0) return hipSuccess;
+  if (!convpool_applies(conv, pool)) return hipErrorInvalidValue;
+  const int esz = conv.dtype == LOP_BF16 ? 2 : 4;
+  // 32-bit signed byte offsets into the input slab
+  if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+  const LdsChoice ld = choose_pooled(p, conv.dtype);
+  if (conv.dtype == LOP_BF16) {
+    if (ld.bm == 64) return launch_lds<__bf16, 64, 64, 4>(p, stream, ev);
+    return launch_lds<__bf16, 32, 64, 4>(p, stream, ev);
+  }
+  return launch_lds<float, 32, 32, 6>(p, stream, ev);
+}
+
+int convpool_describe(const OpLaunch& conv, const OpLaunch& pool, char* name, size_t size) {
+  const ConvParams p = make_pooled_params(conv, pool);
+  const LdsChoice ld = choose_pooled(p, conv.dtype);
+  const bool bf = conv.dtype == LOP_BF16;
+  if (name && size)
+    snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, true>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
+  return 1;
 }
 
 }  // namespace lop

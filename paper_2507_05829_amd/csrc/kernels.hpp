@@ -70,6 +70,14 @@ struct KernelEvents {
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev = nullptr);
 // Whether launch_op's kernel for this operator honours OpLaunch::y2.
 bool stores_second_output(const OpLaunch& L);
+// A dense convolution and the 2 x 2 stride-2 max pooling that reads it, as one launch: whether
+// the pair qualifies (descriptors without slabs suffice), the launch (conv: input slab, weights,
+// hyper-parameters; pool: output slab, y2 and the pooled rows out_lo..out_hi) and its kernel name.
+bool convpool_applies(const OpLaunch& conv, const OpLaunch& pool);
+bool convpool_pays(const OpLaunch& conv);  // for one launch of the conv alone (rows and slab geometry set)
+hipError_t launch_convpool(const OpLaunch& conv, const OpLaunch& pool, hipStream_t stream,
+                           KernelEvents* ev = nullptr);
+int convpool_describe(const OpLaunch& conv, const OpLaunch& pool, char* name, size_t size);
 // Name of the kernel instance launch_op would pick, as a profiler prints it (without the
 // namespace and argument list), written to name[size]. Returns the number of K slices
 // (1: a single kernel; > 1: followed by splitk_finish_kernel).

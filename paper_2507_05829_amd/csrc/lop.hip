@@ -341,6 +341,46 @@ void find_fused_groups(lop_plan_t* P) {
     P->fused_away[h] = P->fused_away[m] = 1;
     h = q;
   }
+  // Groups of two: a dense conv and the 2 x 2 stride-2 max pooling that is its only reader.
+  // The pooling windows do not overlap, so the rows of the conv a band computes are exactly
+  // twice its pooled rows, in both modes (checked, since the launch derives them that way).
+  for (int h = 0; h + 1 < nl; ++h) {
+    const int q = h + 1;
+    if (P->fused_away[h] || P->fuse_head[h] >= 0 || P->fused_away[q] || P->fuse_head[q] >= 0) continue;
+    if (t.layers[q].d.input_from != h) continue;
+    bool shared = false;
+    for (int j = 0; j < nl; ++j) {
+      const lop_layer_t& d = t.layers[j].d;
+      if (j != q && d.input_from == h) shared = true;
+      if (d.residual_from == h) shared = true;
+    }
+    if (shared) continue;
+    if (!lop::convpool_applies(describe_layer(P, h), describe_layer(P, q))) continue;
+    const lop::LayerInfo& C = t.layers[h];
+    const size_t esz = t.esz();
+    if ((size_t)C.n * C.h_in * C.w_in * C.d.c_in * esz >= ((size_t)1 << 31)) continue;  // 32-bit offsets
+    bool rows_match = true;
+    for (int b = 0; b < t.n_bands; ++b) {
+      const lop_rows_t pr = t.bands[b].compute[q], cr = t.bands[b].compute[h];
+      if (pr.hi <= pr.lo) rows_match = rows_match && cr.hi <= cr.lo;
+      else rows_match = rows_match && cr.lo == 2 * pr.lo && cr.hi == 2 * pr.hi &&
+                        lop::convpool_pays(make_launch(P, b, h, nullptr, nullptr));
+    }
+    if (!rows_match) continue;
+    P->fuse_head[q] = h;
+    P->fused_away[h] = 1;
+  }
+}
+
+// Whether layer l ends a conv + pooling group (else, if it ends a group, an inverted-residual block).
+bool ends_convpool(const lop_plan_t* P, int l) { return P->fuse_head[l] >= 0 && P->fuse_head[l] == l - 1; }
+
+// The two descriptors of a conv + pooling launch of one band.
+void convpool_launches(const lop_plan_t* P, int band, int l, const void* d_in, void* d_out,
+                       lop::OpLaunch* conv, lop::OpLaunch* pool) {
+  const int h = P->fuse_head[l];
+  *pool = make_launch(P, band, l, d_in, d_out);
+  *conv = make_launch(P, band, h, d_in, d_out);   // (its y slab is never used: the layer has no buffer)
 }
 
 // Rows of layer l one launch of band `band` produces (none for a layer that is part of a
@@ -361,6 +401,12 @@ hipError_t launch_layer(const lop_plan_t* P, int band, int l, const void* d_in, 
     o.y2 = y2;
     return lop::launch_op(o, cs, ev);
   }
+  if (ends_convpool(P, l)) {
+    lop::OpLaunch conv, pool;
+    convpool_launches(P, band, l, d_in, d_out, &conv, &pool);
+    pool.y2 = y2;
+    return lop::launch_convpool(conv, pool, cs, ev);
+  }
   const int h = P->fuse_head[l];
   lop::OpLaunch e = describe_layer(P, h), d = describe_layer(P, h + 1);
   const lop::OpLaunch p = make_launch(P, band, l, d_in, d_out);
@@ -373,6 +419,11 @@ int describe_layer_launch(const lop_plan_t* P, int band, int l, char* name, size
   const lop_rows_t r = launch_rows(P, band, l);
   if (r.hi <= r.lo) return 0;
   if (P->fuse_head[l] < 0) return lop::describe_op(make_launch(P, band, l, nullptr, nullptr), name, size);
+  if (ends_convpool(P, l)) {
+    lop::OpLaunch conv, pool;
+    convpool_launches(P, band, l, nullptr, nullptr, &conv, &pool);
+    return lop::convpool_describe(conv, pool, name, size);
+  }
   return lop::mbconv_describe(describe_layer(P, l - 1), describe_layer(P, l), name, size);
 }
 
@@ -388,6 +439,18 @@ void launch_work(const lop_plan_t* P, int band, int l, double* flop, double* byt
   if (P->fuse_head[l] < 0) {
     *flop = t.layer_flop(l, r.hi - r.lo);
     *bytes = t.layer_bytes(band, l);
+    return;
+  }
+  if (ends_convpool(P, l)) {
+    // the conv's operations on twice the pooled rows plus the comparisons; bytes of the conv's
+    // input rows and weights and of the pooled rows only
+    const int h = P->fuse_head[l];
+    const lop::LayerInfo &C = t.layers[h], &Q = t.layers[l];
+    const lop_rows_t rd = t.bands[band].reads[h];
+    *flop = t.layer_flop(h, 2 * (r.hi - r.lo)) + t.layer_flop(l, r.hi - r.lo);
+    const double e = (double)t.esz();
+    *bytes = e * Q.n * ((double)(rd.hi - rd.lo) * C.w_in * C.d.c_in + (double)(r.hi - r.lo) * Q.w_out * Q.d.c_out) +
+             e * (double)C.d.c_out * C.d.c_in * C.d.kh * C.d.kw;
     return;
   }
   const int h = P->fuse_head[l], m = h + 1;
@@ -423,11 +486,13 @@ void* direct_host_target(lop_plan_t* P, int band, void* h_out) {
   if (!h_out || (P->flags & (LOP_FLAG_NO_D2H | LOP_FLAG_DMA_COPY))) return nullptr;
   const lop::Tables& t = P->t;
   const int last = t.n_layers() - 1;
-  if (P->fuse_head[last] >= 0) return nullptr;
+  if (P->fuse_head[last] >= 0 && !ends_convpool(P, last)) return nullptr;
   const lop_rows_t r = t.bands[band].need[t.n_layers()];
   const size_t bytes = (size_t)t.in.n * (r.hi - r.lo) * t.row_elems(last) * t.esz();
   if (bytes == 0 || bytes > kDirectHostStoreMax) return nullptr;
-  if (!lop::stores_second_output(make_launch(P, band, last, nullptr, nullptr))) return nullptr;
+  if (!ends_convpool(P, last) &&   // (the pooled launch stores to both destinations)
+      !lop::stores_second_output(make_launch(P, band, last, nullptr, nullptr)))
+    return nullptr;
   return device_view_of_host(P, h_out);
 }
 

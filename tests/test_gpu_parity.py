@@ -142,6 +142,54 @@ def test_lds_staged_kernel(oracle, cfg):
         np.testing.assert_array_equal(dev, want)
 
 
+POOLED_GRID = [
+    # dtype, c_in, c_out, k, s, p, shape(n,h,w), bands, then a third layer behind the pooling?
+    ("bf16", 64, 128, 3, 1, 1, (1, 82, 106), 3, False),   # 64 x 64 tiles, ragged last tile
+    ("bf16", 64, 64, 3, 1, 1, (2, 37, 53), 2, True),      # odd height and width: last row and column unused; batch 2
+    ("bf16", 128, 72, 3, 1, 1, (1, 28, 28), 4, False),    # few pixels: 32 x 64 tiles; channels not a multiple of the tile
+    ("bf16", 64, 64, 1, 1, 0, (1, 40, 64), 2, True),      # 1 x 1: a single stage
+    ("bf16", 64, 96, 3, 2, 1, (1, 90, 70), 2, False),     # stride-2 conv in front of the pooling
+    ("f32", 32, 64, 3, 1, 1, (1, 50, 66), 2, True),       # fp32: 32 x 32 tiles
+    ("f32", 64, 40, 3, 1, 1, (2, 30, 34), 5, False),
+]
+
+
+@pytest.mark.parametrize("reuse", [0, 1])
+@pytest.mark.parametrize("cfg", POOLED_GRID)
+def test_conv_with_pooling_in_one_launch(oracle, cfg, reuse):
+    """A dense conv followed by a 2 x 2 stride-2 max pooling runs as one launch (checked by
+    name; the conv itself launches nothing): random values against the oracle within tolerance,
+    small integers bit for bit, equal to the layer-by-layer path within tolerance, as the
+    chain's last layers (rows straight to the host) and with a layer behind them, in both modes."""
+    dtype, c_in, c_out, k, s_, p_, shape, bands, tail = cfg
+    chain = workloads.Chain("convpool", (shape[0], c_in, shape[1], shape[2]), dtype, bands)
+    chain.add(workloads.CONV, c_in, c_out, k, s_, p_, 1, "relu")
+    chain.add(workloads.MAXPOOL, c_out, c_out, 2, 2, 0)
+    if tail:
+        chain.add(workloads.CONV, c_out, c_out, 3, 1, 1, 1, "relu")
+    flags = lop.LOP_FLAG_REUSE if reuse else 0
+    t = workloads.make_tensors(chain, zero_bias=False, seed=23)
+    plan = lop.Plan(chain, t, None, flags)
+    try:
+        for b in range(plan.n_bands):
+            assert plan.layer_kernel(b, 0)[0] == ""
+            nm = plan.layer_kernel(b, 1)[0]
+            assert nm.startswith("conv_lds_kernel<") and nm.endswith(", true>"), nm
+    finally:
+        plan.destroy()
+    want = oracle.run_chain(chain, t)
+    dev, host = run_gpu(chain, t, flags=flags)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL[dtype]
+    unfused, _ = run_gpu(chain, t, flags=flags | lop.LOP_FLAG_NO_FUSE)
+    assert rel_err(dev, unfused) <= TOL[dtype]
+    ti = workloads.small_int_tensors(chain, seed=7)
+    want = oracle.run_chain(chain, ti)
+    if np.abs(want).max() < (256 if dtype == "bf16" else 2 ** 24):
+        dev, _ = run_gpu(chain, ti, flags=flags)
+        np.testing.assert_array_equal(dev, want)
+
+
 def test_small_layer_kernel_is_selected():
     """The grid above reaches every variant of the small-layer kernel: one launch, and a
     launch cut across workgroups followed by the finish kernel."""
