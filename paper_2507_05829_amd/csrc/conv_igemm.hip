@@ -771,7 +771,8 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
 // order at the end, so no operand byte is read from LDS twice and the result does not depend
 // on how the launch was cut. A tap outside the image (or the slab) is fetched from a
 // zero-filled device array instead of being masked afterwards. Needs C_in * sizeof(T) to be a
-// multiple of 128 (a stage never straddles two taps) and C_out a multiple of the 16-byte vector.
+// multiple of 128 (a stage lies inside one tap) or 64 (TPS below) and C_out a multiple of the
+// 16-byte vector.
 //
 // POOL: a 2 x 2 stride-2 max pooling that follows the convolution is part of the launch. The
 // rows of the tile are then the convolution's pixels in the order (image, pooled row, pooled
@@ -785,7 +786,12 @@ static __device__ __attribute__((aligned(256))) unsigned char g_zero_line[256];
 // and leaves the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
 constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
 
-template <typename T, int BM, int BN, int NST, bool POOL>
+//
+// TPS: taps per stage. 1: C_in * sizeof(T) is a multiple of 128. 2: it is 64, a stage's 128
+// bytes per row are two taps of 64 bytes (the lanes that fetch chunks 4..7 of a row address the
+// second one), and the reduction axis may end in the middle of the last stage: the tap past the
+// end is fetched from the zero line like a tap outside the image (its weights are zero padding).
+template <typename T, int BM, int BN, int NST, bool POOL, int TPS>
 __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   constexpr int KE = 16 / (int)sizeof(T);   // elements per 16-byte chunk
   constexpr int SKE = 8 * KE;               // reduction elements per stage (128 bytes per row)
@@ -814,6 +820,8 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   // ---- what this lane fetches: row (lane >> 3) of an 8-row group, chunk (lane & 7) ^ row
   const int lrow = lane >> 3;
   const int chunk = (lane & 7) ^ lrow;
+  constexpr int CPT = 8 / TPS;              // 16-byte chunks of one tap inside a stage
+  const bool second = chunk >= CPT;         // TPS == 2: this lane fetches the stage's second tap
   int a_off[A_LD], a_ih0[A_LD], a_iw0[A_LD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
@@ -829,7 +837,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
     const int ih0 = oy * p.sh - p.ph, iw0 = ox * p.sw - p.pw;
     a_ih0[i] = ok ? ih0 : -(1 << 28);       // a row past the end of the launch: every tap "outside"
     a_iw0[i] = iw0;
-    a_off[i] = (((n * p.x_rows - p.x_row0 + ih0) * p.W + iw0) * p.C_in + chunk * KE) * (int)sizeof(T);
+    a_off[i] = (((n * p.x_rows - p.x_row0 + ih0) * p.W + iw0) * p.C_in + (chunk % CPT) * KE) * (int)sizeof(T);
   }
   unsigned b_off[B_LD];
 #pragma unroll
@@ -848,7 +856,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   int ia, ib, ici, issued = 0;
   {
     const int k0 = st * SKE, tap = k0 / p.C_in;
-    ici = k0 - tap * p.C_in;
+    ici = k0 - tap * p.C_in;                // (TPS == 2: always 0)
     ia = tap / p.kw;
     ib = tap - ia * p.kw;
   }
@@ -856,18 +864,28 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   // One load instruction of the stage being issued: j < A_LD a pixel group, else a channel group.
   unsigned char* dst = smem;
   int toff = 0, dih = 0, diw = 0;
+  bool tap_ok = true;
   unsigned koff = 0;
   auto issue_begin = [&]() __attribute__((always_inline)) {
     dst = smem + (issued % NST) * STAGE;
-    toff = ia * tap_row + ib * tap_col + ici * (int)sizeof(T);
-    dih = ia * p.dh;
-    diw = ib * p.dw;
+    if constexpr (TPS == 1) {
+      toff = ia * tap_row + ib * tap_col + ici * (int)sizeof(T);
+      dih = ia * p.dh;
+      diw = ib * p.dw;
+    } else {
+      int ja = ia, jb = ib + 1;             // the stage's second tap
+      if (jb == p.kw) { jb = 0; ++ja; }
+      toff = second ? ja * tap_row + jb * tap_col : ia * tap_row + ib * tap_col;
+      dih = (second ? ja : ia) * p.dh;
+      diw = (second ? jb : ib) * p.dw;
+      tap_ok = (second ? ja : ia) < p.kh;
+    }
     koff = (unsigned)st * (unsigned)(SKE * (int)sizeof(T));
   };
   auto issue_one = [&](int j) __attribute__((always_inline)) {
     if (j < A_LD) {
       const int ih = a_ih0[j] + dih, iw = a_iw0[j] + diw;
-      const bool ok = (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows) & (iw >= 0) & (iw < p.W);
+      const bool ok = (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows) & (iw >= 0) & (iw < p.W) & tap_ok;
       const unsigned char* src = ok ? xg + (a_off[j] + toff) : zero_src;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                        (__attribute__((address_space(3))) void*)(dst + (wave * A_LD + j) * 1024),
@@ -881,10 +899,15 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   };
   auto issue_end = [&]() __attribute__((always_inline)) {
     ++issued;
-    ici += SKE;
-    if (ici >= p.C_in) {
-      ici = 0;
-      if (++ib == p.kw) { ib = 0; ++ia; }
+    if constexpr (TPS == 1) {
+      ici += SKE;
+      if (ici >= p.C_in) {
+        ici = 0;
+        if (++ib == p.kw) { ib = 0; ++ia; }
+      }
+    } else {
+      ib += TPS;
+      while (ib >= p.kw) { ib -= p.kw; ++ia; }
     }
     if (++st == ns) { st = 0; ia = 0; ib = 0; ici = 0; }
   };
@@ -1198,11 +1221,14 @@ constexpr int kNarrowMaxTiles = 320;
 struct LdsChoice { int bm, bn; long tiles; };
 LdsChoice choose_lds(const ConvParams& p, int dtype) {
   const int esz = dtype == LOP_BF16 ? 2 : 4, ke = 16 / esz;
-  if ((p.C_in * esz) % 128 != 0 || p.C_out % ke != 0 || p.k_pad != p.K) return {0, 0, 0};
+  const bool half_rows = p.C_in * esz == 64;   // two taps per stage
+  if (!half_rows && ((p.C_in * esz) % 128 != 0 || p.k_pad != p.K)) return {0, 0, 0};
+  if (p.C_out % ke != 0 || (p.k_pad * esz) % 128 != 0) return {0, 0, 0};
   // 32-bit signed byte offsets into the input slab
   if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return {0, 0, 0};
   auto tiles = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn); };
   if (dtype == LOP_BF16) {
+    if (p.C_out <= 32 && tiles(64, 32) >= kLdsMinTiles) return {64, 32, tiles(64, 32)};
     if (tiles(64, 64) >= kLdsMinTiles) return {64, 64, tiles(64, 64)};
     if (tiles(32, 64) >= kLdsMinTiles) return {32, 64, tiles(32, 64)};
     return {0, 0, 0};
@@ -1215,8 +1241,14 @@ template <typename T, int BM, int BN, int NST>
 hipError_t launch_lds(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
   dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN);
   if ((int)grid.y * BN > conv_cout_pad(p.C_out) || grid.y > 65535) return hipErrorInvalidValue;
-  if (p.pool) return launch_kernel(conv_lds_kernel<T, BM, BN, NST, true>, grid, dim3(256), s, ev, p);
-  return launch_kernel(conv_lds_kernel<T, BM, BN, NST, false>, grid, dim3(256), s, ev, p);
+  const int row_bytes = p.C_in * (int)sizeof(T);
+  if (row_bytes == 64) {
+    if (p.pool) return hipErrorInvalidValue;
+    return launch_kernel(conv_lds_kernel<T, BM, BN, NST, false, 2>, grid, dim3(256), s, ev, p);
+  }
+  if (row_bytes % 128 != 0 || p.k_pad != p.K) return hipErrorInvalidValue;
+  if (p.pool) return launch_kernel(conv_lds_kernel<T, BM, BN, NST, true, 1>, grid, dim3(256), s, ev, p);
+  return launch_kernel(conv_lds_kernel<T, BM, BN, NST, false, 1>, grid, dim3(256), s, ev, p);
 }
 
 struct DirectChoice {
@@ -1385,6 +1417,7 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
       // (twice the stages in flight, 128 KB of LDS, measured no faster per launch - the loop is
       // bound by what the L2s deliver, not by latency - and it keeps other streams' workgroups
       // off the compute unit)
+      if (ld.bn == 32) return launch_lds<T, 64, 32, 4>(p, s, ev);
       if (ld.bm == 64) return launch_lds<T, 64, 64, 4>(p, s, ev);
       return launch_lds<T, 32, 64, 4>(p, s, ev);
     } else {
@@ -1474,7 +1507,8 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
   if (const LdsChoice ld = lds_applies(p, L.dtype, c, d); ld.bm) {
     if (name && size)
-      snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, false>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
+      snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, false, %d>", bf ? "__bf16" : "float", ld.bm, ld.bn,
+               bf ? 4 : 6, p.C_in * (bf ? 2 : 4) == 64 ? 2 : 1);
     return 1;
   }
   if (d.wk) {
@@ -1560,7 +1594,7 @@ int convpool_describe(const OpLaunch& conv, const OpLaunch& pool, char* name, si
   const LdsChoice ld = choose_pooled(p, conv.dtype);
   const bool bf = conv.dtype == LOP_BF16;
   if (name && size)
-    snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, true>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
+    snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, true, 1>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
   return 1;
 }
 

@@ -107,6 +107,12 @@ LDS_GRID = [
     ("f32", 32, 64, 3, 1, 1, 1, (1, 74, 90), True),        # fp32: 32 x 32 tiles, K = 288
     ("f32", 64, 96, 3, 2, 1, 1, (2, 90, 80), False),
     ("f32", 96, 32, 5, 1, 2, 1, (1, 80, 94), False),       # 5 x 5: 75 stages
+    ("bf16", 32, 32, 3, 1, 1, 1, (1, 90, 128), True),      # rows of 64 bytes: two taps per stage, 9 taps = 4.5 stages; 64 x 32 tiles
+    ("bf16", 32, 64, 3, 2, 1, 1, (2, 101, 77), False),     # ... stride 2, batch 2
+    ("bf16", 32, 96, 1, 2, 0, 1, (1, 140, 180), False),    # ... 1 x 1 stride 2: one tap, half a stage
+    ("bf16", 32, 64, 5, 1, 2, 1, (1, 60, 64), False),      # ... 5 x 5: 25 taps, kw odd
+    ("bf16", 32, 64, 3, 1, 2, 2, (1, 64, 60), False),      # ... dilation 2
+    ("f32", 16, 64, 3, 1, 1, 1, (1, 70, 66), False),       # fp32 rows of 64 bytes
 ]
 
 
@@ -174,7 +180,7 @@ def test_conv_with_pooling_in_one_launch(oracle, cfg, reuse):
         for b in range(plan.n_bands):
             assert plan.layer_kernel(b, 0)[0] == ""
             nm = plan.layer_kernel(b, 1)[0]
-            assert nm.startswith("conv_lds_kernel<") and nm.endswith(", true>"), nm
+            assert nm.startswith("conv_lds_kernel<") and nm.endswith(", true, 1>"), nm
     finally:
         plan.destroy()
     want = oracle.run_chain(chain, t)
