@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblop.so")
 
-SOURCES = ["plan_tables.cpp", "devmem.hip", "loss.cpp", "conv_igemm.hip", "pointwise.hip", "mbconv.hip", "rowwise.hip", "two_party.hip", "ceilings.hip", "lop.hip"]
+SOURCES = ["plan_tables.cpp", "devmem.hip", "loss.cpp", "conv_igemm.hip", "conv_stem.hip", "pointwise.hip", "mbconv.hip", "rowwise.hip", "two_party.hip", "ceilings.hip", "lop.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument",

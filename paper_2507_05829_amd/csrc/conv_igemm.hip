@@ -1481,6 +1481,7 @@ int conv_k_pad(int c_in, int kh, int kw, int dtype) {
 }
 
 size_t conv_workspace_bytes(const OpLaunch& L) {
+  if (stem_applies(L)) return 0;
   const ConvParams p = make_params(L);
   if (p.M <= 0) return 0;
   const Choice c = choose(p, L.dtype);

@@ -1,0 +1,195 @@
+// First layers of a backbone: a dense convolution over very few input channels (an RGB image),
+// e.g. 7 x 7 stride 2 over 3 channels. The reduction axis is short (27 .. 192 elements) and does
+// not come in 16-byte pieces (3 channels), so the implicit-GEMM kernels gather it element by
+// element; the arithmetic itself is small enough for the vector ALUs (Sec. IV-A local operator:
+// every output pixel depends on a kh x kw window of the input only).
+//
+// A workgroup of four wavefronts owns 64 consecutive pixels of one output row and 16 output
+// channels. It first copies the kh input rows x the columns those 64 windows touch into LDS as
+// fp32 (coalesced loads along the row, zeros for padding), then lane p of wavefront w computes
+// pixel p for channels 4 w .. 4 w + 3: for every element of the reduction axis one LDS read of
+// its input value and one 16-byte load of four weights whose address is the same for the whole
+// wavefront (the compiler turns those into scalar loads, and the multiply-adds take the weights
+// from scalar registers). The weights are packed [C_out / 4][K][4] fp32 for that: a wavefront
+// walks 16 contiguous bytes per reduction element. KJ: kw * C_in when it is one of the usual
+// values (the loop over a kernel row is then unrolled and its weight loads are issued together),
+// else 0.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+
+#include "act.hpp"
+#include "kernels.hpp"
+#include "launch.hpp"
+#include "lop.h"
+
+namespace lop {
+namespace {
+
+constexpr int kStemPixels = 64;       // output pixels per workgroup (one per lane)
+constexpr int kStemChannels = 16;     // output channels per workgroup (four per wavefront)
+constexpr int kStemPatchMax = 4096;   // fp32 elements of the staged input patch
+constexpr int kStemRowChunks = 3;     // a staged row has at most 3 * 256 elements
+constexpr int kStemMaxCin = 4;
+constexpr int kStemMaxK = 192;
+
+struct StemParams {
+  const void* x;
+  void* y;
+  void* y2;             // second destination with y's layout, or nullptr
+  const float* wq;      // [C_out / 4][K][4]
+  const float* bias;    // or nullptr
+  int x_row0, x_rows, W, C_in;
+  int y_row0, y_rows, W_out, C_out;
+  int kh, kw, sh, sw, ph, pw;
+  int act, out_lo, R, N;
+  int tiles_x;          // 64-pixel tiles per output row
+  int patch_w;          // elements of one staged input row: ((64 - 1) * sw + kw) * C_in
+};
+
+__device__ __forceinline__ float load_f32(const float* p) { return *p; }
+__device__ __forceinline__ float load_f32(const __bf16* p) { return (float)*p; }
+__device__ __forceinline__ void store4(float* y, const float* v) { *(float4*)y = make_float4(v[0], v[1], v[2], v[3]); }
+__device__ __forceinline__ void store4(__bf16* y, const float* v) {
+  alignas(8) __bf16 o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) o[j] = (__bf16)v[j];
+  *(uint2*)y = *(const uint2*)o;
+}
+
+template <typename T, int KJ>
+__global__ __launch_bounds__(256) void conv_stem_kernel(const StemParams p) {
+  __shared__ float patch[kStemPatchMax];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int xt = blockIdx.x % p.tiles_x;
+  const int t = blockIdx.x / p.tiles_x;
+  const int r = t % p.R, n = t / p.R;
+  const int oy = p.out_lo + r, ox0 = xt * kStemPixels;
+
+  // ---- stage: kh rows x patch_w elements, element e of a row is input element iw0 * C_in + e
+  const int ih0 = oy * p.sh - p.ph;
+  const int e0 = (ox0 * p.sw - p.pw) * p.C_in;         // may be negative: left padding
+  const int row_elems = p.W * p.C_in;
+  const T* const xg = (const T*)p.x + (size_t)n * p.x_rows * row_elems;
+  // (four rows at a time, every load of the batch issued before the first is used: a tap
+  // outside the image or the slab loads the slab's first element instead and is zeroed after)
+  for (int a0 = 0; a0 < p.kh; a0 += 4) {
+    float v[4][kStemRowChunks];
+#pragma unroll
+    for (int da = 0; da < 4; ++da)
+#pragma unroll
+      for (int c = 0; c < kStemRowChunks; ++c) {
+        const int ih = ih0 + a0 + da, ge = e0 + tid + c * 256;
+        const bool ok = a0 + da < p.kh && tid + c * 256 < p.patch_w && ih >= p.x_row0 &&
+                        ih < p.x_row0 + p.x_rows && ge >= 0 && ge < row_elems;
+        const float got = load_f32(xg + (ok ? (size_t)(ih - p.x_row0) * row_elems + ge : 0));
+        v[da][c] = ok ? got : 0.f;
+      }
+#pragma unroll
+    for (int da = 0; da < 4; ++da)
+#pragma unroll
+      for (int c = 0; c < kStemRowChunks; ++c)
+        if (a0 + da < p.kh && tid + c * 256 < p.patch_w) patch[(a0 + da) * p.patch_w + tid + c * 256] = v[da][c];
+  }
+  __syncthreads();
+
+  // ---- multiply: this lane's window starts at element lane * sw * C_in of every staged row
+  const int kj = KJ ? KJ : p.kw * p.C_in;               // reduction elements per kernel row
+  const float* wq = p.wq + (size_t)(blockIdx.y * 4 + wave) * p.kh * kj * 4;
+  const float* px = patch + lane * p.sw * p.C_in;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int a = 0; a < p.kh; ++a) {
+    if constexpr (KJ != 0) {
+#pragma unroll
+      for (int j = 0; j < KJ; ++j) {
+        const float xv = px[j];
+        const float4 w4 = *(const float4*)(wq + j * 4);
+        acc[0] += xv * w4.x; acc[1] += xv * w4.y; acc[2] += xv * w4.z; acc[3] += xv * w4.w;
+      }
+    } else {
+#pragma unroll 4
+      for (int j = 0; j < kj; ++j) {
+        const float xv = px[j];
+        const float4 w4 = *(const float4*)(wq + j * 4);
+        acc[0] += xv * w4.x; acc[1] += xv * w4.y; acc[2] += xv * w4.z; acc[3] += xv * w4.w;
+      }
+    }
+    px += p.patch_w;
+    wq += kj * 4;
+  }
+
+  // ---- bias, activation, the one rounding, 4 consecutive channels per store
+  const int ox = ox0 + lane;
+  if (ox >= p.W_out) return;
+  const int co = blockIdx.y * kStemChannels + wave * 4;
+  const Clamp cl = make_clamp(p.act);
+  float v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v[j] = clamp_act(acc[j] + (p.bias ? p.bias[co + j] : 0.f), cl);
+  const size_t off = ((size_t)(n * p.y_rows + oy - p.y_row0) * p.W_out + ox) * p.C_out + co;
+  store4((T*)p.y + off, v);
+  if (p.y2) store4((T*)p.y2 + off, v);
+}
+
+StemParams make_stem_params(const OpLaunch& L) {
+  StemParams p;
+  p.x = L.x.ptr; p.y = L.y.ptr; p.y2 = L.y2; p.wq = (const float*)L.wstem; p.bias = L.bias;
+  p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.W = L.x.w; p.C_in = L.x.c;
+  p.y_row0 = L.y.row0; p.y_rows = L.y.rows; p.W_out = L.y.w; p.C_out = L.y.c;
+  p.kh = L.kh; p.kw = L.kw; p.sh = L.sh; p.sw = L.sw; p.ph = L.ph; p.pw = L.pw;
+  p.act = L.act; p.out_lo = L.out_lo; p.R = L.out_hi - L.out_lo; p.N = L.x.n;
+  p.tiles_x = (p.W_out + kStemPixels - 1) / kStemPixels;
+  p.patch_w = ((kStemPixels - 1) * p.sw + p.kw) * p.C_in;
+  return p;
+}
+
+// kw * C_in if the kernel is instantiated for it (3 x 3 and 7 x 7 over 3 channels), else 0
+int stem_kj(const OpLaunch& L) {
+  const int kj = L.kw * L.x.c;
+  return kj == 9 || kj == 21 ? kj : 0;
+}
+
+}  // namespace
+
+bool stem_shape_applies(int c_in, int c_out, int kh, int kw, int sw, int dh, int dw, bool residual) {
+  if (residual || dh != 1 || dw != 1) return false;
+  if (c_in > kStemMaxCin || c_in * kh * kw > kStemMaxK || c_out % kStemChannels != 0) return false;
+  const int patch_w = ((kStemPixels - 1) * sw + kw) * c_in;
+  return patch_w <= kStemRowChunks * 256 && kh * patch_w <= kStemPatchMax;
+}
+
+bool stem_applies(const OpLaunch& L) {
+  return L.op == LOP_CONV2D && L.wstem &&
+         stem_shape_applies(L.x.c, L.y.c, L.kh, L.kw, L.sw, L.dh, L.dw, L.res.ptr != nullptr);
+}
+
+hipError_t launch_stem(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
+  if (!stem_applies(L)) return hipErrorInvalidValue;
+  const StemParams p = make_stem_params(L);
+  if (p.R <= 0 || p.N <= 0) return hipSuccess;
+  // the staged patch must fit, and the grid's x extent
+  if (p.kh * p.patch_w > kStemPatchMax || p.patch_w > kStemRowChunks * 256) return hipErrorInvalidValue;
+  if ((size_t)p.x_rows * p.W * p.C_in == 0) return hipErrorInvalidValue;  // (padding taps load element 0)
+  const long tiles = (long)p.N * p.R * p.tiles_x;
+  if (tiles > 0x7fffffffL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)tiles, (unsigned)(p.C_out / kStemChannels));
+  const int kj = stem_kj(L);
+  if (L.dtype == LOP_BF16) {
+    if (kj == 9) return launch_kernel(conv_stem_kernel<__bf16, 9>, grid, dim3(256), stream, ev, p);
+    if (kj == 21) return launch_kernel(conv_stem_kernel<__bf16, 21>, grid, dim3(256), stream, ev, p);
+    return launch_kernel(conv_stem_kernel<__bf16, 0>, grid, dim3(256), stream, ev, p);
+  }
+  if (kj == 9) return launch_kernel(conv_stem_kernel<float, 9>, grid, dim3(256), stream, ev, p);
+  if (kj == 21) return launch_kernel(conv_stem_kernel<float, 21>, grid, dim3(256), stream, ev, p);
+  return launch_kernel(conv_stem_kernel<float, 0>, grid, dim3(256), stream, ev, p);
+}
+
+int stem_describe(const OpLaunch& L, char* name, size_t size) {
+  if (name && size)
+    snprintf(name, size, "conv_stem_kernel<%s, %d>", L.dtype == LOP_BF16 ? "__bf16" : "float", stem_kj(L));
+  return 1;
+}
+
+}  // namespace lop

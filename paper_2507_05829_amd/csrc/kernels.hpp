@@ -24,6 +24,8 @@ struct OpLaunch {
   const void* w = nullptr;      // device, kernel layout (see pack_* below)
   const void* wd = nullptr;     // dense conv: the weights in operand order, or nullptr
   const void* wd16 = nullptr;   // dense conv: ... in the operand order of 16 x 16 tiles, or nullptr
+  const void* wstem = nullptr;  // dense conv over very few input channels: fp32 weights
+                                // [c_out / 4][k][4] for the first-layer kernel, or nullptr
   const float* bias = nullptr;  // device or nullptr
   int kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0, dh = 1, dw = 1;
   int act = 0;
@@ -70,6 +72,13 @@ struct KernelEvents {
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev = nullptr);
 // Whether launch_op's kernel for this operator honours OpLaunch::y2.
 bool stores_second_output(const OpLaunch& L);
+// The first-layer kernel (very few input channels, a short reduction axis, vector ALUs):
+// whether a layer of this shape gets the packing it needs, whether a launch takes it, the
+// launch and its kernel name.
+bool stem_shape_applies(int c_in, int c_out, int kh, int kw, int sw, int dh, int dw, bool residual);
+bool stem_applies(const OpLaunch& L);
+hipError_t launch_stem(const OpLaunch& L, hipStream_t stream, KernelEvents* ev = nullptr);
+int stem_describe(const OpLaunch& L, char* name, size_t size);
 // A dense convolution and the 2 x 2 stride-2 max pooling that reads it, as one launch: whether
 // the pair qualifies (descriptors without slabs suffice), the launch (conv: input slab, weights,
 // hyper-parameters; pool: output slab, y2 and the pooled rows out_lo..out_hi) and its kernel name.

@@ -34,17 +34,20 @@ int rowwise_describe(const OpLaunch& L, char* name, size_t size);
 
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   if (L.out_hi <= L.out_lo) return hipSuccess;
-  if (L.op == LOP_CONV2D)
+  if (L.op == LOP_CONV2D) {
+    if (stem_applies(L)) return launch_stem(L, stream, ev);
     return pointwise_applies(L) ? launch_pointwise(L, stream, ev) : launch_conv_igemm(L, stream, ev);
+  }
   return launch_rowwise_op(L, stream, ev);
 }
 
 bool stores_second_output(const OpLaunch& L) {
-  return L.op != LOP_CONV2D || !pointwise_applies(L);
+  return L.op != LOP_CONV2D || stem_applies(L) || !pointwise_applies(L);
 }
 
 int describe_op(const OpLaunch& L, char* name, size_t size) {
   if (L.op != LOP_CONV2D) return rowwise_describe(L, name, size);
+  if (stem_applies(L)) return stem_describe(L, name, size);
   return pointwise_applies(L) ? pointwise_describe(L, name, size) : conv_igemm_describe(L, name, size);
 }
 }  // namespace lop
@@ -106,6 +109,7 @@ int upload_weights(lop_plan_t* P) {
   P->d_w.assign(nl, nullptr);
   P->d_wd.assign(nl, nullptr);
   P->d_wd16.assign(nl, nullptr);
+  P->d_wstem.assign(nl, nullptr);
   P->d_bias.assign(nl, nullptr);
   for (int l = 0; l < nl; ++l) {
     const lop::LayerInfo& L = t.layers[l];
@@ -127,6 +131,28 @@ int upload_weights(lop_plan_t* P) {
             }
       LOP_HIP(lop::dev_alloc(&P->d_w[l], host.size()));
       LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size(), hipMemcpyHostToDevice));
+      if (P->has_wstem[l]) {
+        // fp32 [c_out / 4][k][4], k = (a*kw + b)*c_in + ci: four weights of one reduction
+        // element are one 16-byte load whose address a whole wavefront shares
+        const size_t K = (size_t)d.c_in * d.kh * d.kw;
+        std::vector<float> q((size_t)d.c_out * K);
+        for (int co = 0; co < d.c_out; ++co)
+          for (size_t k = 0; k < K; ++k) {
+            float v;
+            const unsigned char* src = &host[((size_t)co * kp + k) * esz];
+            if (bf) {
+              unsigned short h;
+              std::memcpy(&h, src, 2);
+              const unsigned u = (unsigned)h << 16;
+              std::memcpy(&v, &u, 4);
+            } else {
+              std::memcpy(&v, src, 4);
+            }
+            q[((size_t)(co / 4) * K + k) * 4 + co % 4] = v;
+          }
+        LOP_HIP(lop::dev_alloc(&P->d_wstem[l], q.size() * 4));
+        LOP_HIP(hipMemcpy(P->d_wstem[l], q.data(), q.size() * 4, hipMemcpyHostToDevice));
+      }
       const int ke = 16 / (int)esz;
       if (P->has_wd[l]) {
         // the same values in MFMA operand order: [co / 32][step][half*32 + co % 32] x 16 B
@@ -270,12 +296,14 @@ lop::OpLaunch make_launch(const lop_plan_t* P, int band, int l, const void* d_in
     o.w = P->d_w[l];
     o.wd = P->d_wd[l];
     o.wd16 = P->d_wd16[l];
+    o.wstem = P->d_wstem[l];
     o.bias = P->d_bias[l];
   } else {
     // not uploaded (yet): the kernel choice only asks which packings exist, so a marker that
     // is never dereferenced stands for each that upload_weights would make
     o.wd = P->has_wd[l] ? (const void*)P : nullptr;
     o.wd16 = P->has_wd16[l] ? (const void*)P : nullptr;
+    o.wstem = P->has_wstem[l] ? (const void*)P : nullptr;
   }
   o.k_pad = P->k_pad[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
@@ -299,10 +327,11 @@ OpLaunch describe_layer(const lop_plan_s* P, int l) {
   o.x.n = o.y.n = P->t.in.n;
   if (L.d.residual_from != LOP_NO_RESIDUAL) o.res.ptr = const_cast<lop_plan_t*>(P);
   if (!P->d_w.empty()) {  // uploaded (not a plan-only plan)
-    o.w = P->d_w[l]; o.wd = P->d_wd[l]; o.wd16 = P->d_wd16[l]; o.bias = P->d_bias[l];
+    o.w = P->d_w[l]; o.wd = P->d_wd[l]; o.wd16 = P->d_wd16[l]; o.wstem = P->d_wstem[l]; o.bias = P->d_bias[l];
   } else {
     o.wd = P->has_wd[l] ? (const void*)P : nullptr;
     o.wd16 = P->has_wd16[l] ? (const void*)P : nullptr;
+    o.wstem = P->has_wstem[l] ? (const void*)P : nullptr;
   }
   o.k_pad = P->k_pad[l];
   o.kh = L.d.kh; o.kw = L.d.kw; o.sh = L.d.sh; o.sw = L.d.sw;
@@ -829,6 +858,7 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
   P->k_pad.assign((size_t)n_layers, 0);  // padded reduction length of every dense conv
   P->has_wd.assign((size_t)n_layers, 0);
   P->has_wd16.assign((size_t)n_layers, 0);
+  P->has_wstem.assign((size_t)n_layers, 0);
   const int ke = 16 / (int)P->t.esz();
   for (int l = 0; l < n_layers; ++l) {
     const lop_layer_t& d = P->t.layers[l].d;
@@ -836,6 +866,8 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
     P->k_pad[l] = lop::conv_k_pad(d.c_in, d.kh, d.kw, in->dtype);
     P->has_wd[l] = d.c_in % ke == 0 && d.c_out % ke == 0;
     P->has_wd16[l] = P->has_wd[l] && P->k_pad[l] % (4 * ke) == 0;
+    P->has_wstem[l] = lop::stem_shape_applies(d.c_in, d.c_out, d.kh, d.kw, d.sw, d.dh, d.dw,
+                                              d.residual_from != LOP_NO_RESIDUAL);
   }
   find_fused_groups(P);
   size_scratch(P);
@@ -886,6 +918,7 @@ void lop_plan_destroy(lop_plan_t* P) {
   for (void* w : P->d_w) if (w) (void)lop::dev_free(w);
   for (void* w : P->d_wd) if (w) (void)lop::dev_free(w);
   for (void* w : P->d_wd16) if (w) (void)lop::dev_free(w);
+  for (void* w : P->d_wstem) if (w) (void)lop::dev_free(w);
   for (float* b : P->d_bias) if (b) (void)lop::dev_free(b);
   for (auto* v : {&P->ev_done, &P->ev_copied, &P->ev_c0, &P->ev_c1, &P->ev_d0, &P->ev_d1})
     for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);

@@ -38,6 +38,7 @@ struct lop_plan_s {
   std::vector<void*> d_w;      // per layer packed weights (device) or nullptr
   std::vector<void*> d_wd;     // dense conv weights in MFMA operand order, or nullptr
   std::vector<void*> d_wd16;   // ... in the operand order of 16 x 16 tiles, or nullptr
+  std::vector<void*> d_wstem;  // ... as fp32 [c_out / 4][k][4] for the first-layer kernel, or nullptr
   // Layers that run as one launch: fuse_head[t] = first layer of the group whose last layer is
   // t (else -1); fused_away[l] = 1 for the layers of a group before its last (no launch, no
   // buffer of their own).
@@ -46,6 +47,7 @@ struct lop_plan_s {
   std::vector<float*> d_bias;  // per layer bias (device) or nullptr
   std::vector<int> k_pad;
   std::vector<char> has_wd, has_wd16;  // which of the two operand-order packings a layer gets
+  std::vector<char> has_wstem;         // ... and whether it gets the first-layer packing
   size_t conv_ws_bytes = 0;
   size_t arena_bytes = 0;
   std::vector<std::vector<size_t>> slab_off;  // [band][layer] byte offset into a lane's arena

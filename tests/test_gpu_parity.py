@@ -196,6 +196,49 @@ def test_conv_with_pooling_in_one_launch(oracle, cfg, reuse):
         np.testing.assert_array_equal(dev, want)
 
 
+STEM_GRID = [
+    # dtype, c_in, c_out, k, s, p, shape(n,h,w), bands
+    ("f32", 3, 64, 7, 2, 3, (1, 97, 131), 3),     # 7 x 7 stride 2 over RGB (unrolled row of 21), ragged last pixel tile
+    ("bf16", 3, 32, 3, 2, 1, (2, 70, 150), 2),    # 3 x 3 stride 2 (row of 9), batch 2
+    ("bf16", 3, 64, 3, 1, 1, (1, 40, 200), 4),    # stride 1, several pixel tiles per row
+    ("f32", 3, 16, 5, 1, 2, (1, 33, 65), 2),      # 5 x 5: the generic loop (row of 15), one pixel past a tile
+    ("f32", 1, 32, 3, 1, 0, (1, 30, 40), 2),      # one input channel, no padding
+    ("bf16", 4, 48, 3, 2, 0, (1, 51, 77), 1),     # four input channels, one band
+    ("f32", 3, 32, 1, 1, 0, (1, 20, 30), 2),      # 1 x 1 over RGB
+]
+
+
+@pytest.mark.parametrize("reuse", [0, 1])
+@pytest.mark.parametrize("cfg", STEM_GRID)
+def test_first_layer_kernel(oracle, cfg, reuse):
+    """Dense convs over at most four input channels run on the first-layer kernel (checked by
+    name): random values against the oracle within tolerance, small integers bit for bit, alone
+    (rows straight to the host) and with a layer behind, in both modes."""
+    dtype, c_in, c_out, k, s_, p_, shape, bands = cfg
+    flags = lop.LOP_FLAG_REUSE if reuse else 0
+    for tail in (False, True):
+        chain = workloads.Chain("stem", (shape[0], c_in, shape[1], shape[2]), dtype, bands)
+        chain.add(workloads.CONV, c_in, c_out, k, s_, p_, 1, "relu")
+        if tail:
+            chain.add(workloads.MAXPOOL, c_out, c_out, 3, 2, 1)
+        t = workloads.make_tensors(chain, zero_bias=False, seed=31)
+        plan = lop.Plan(chain, t, None, flags)
+        try:
+            for b in range(plan.n_bands):
+                assert plan.layer_kernel(b, 0)[0].startswith("conv_stem_kernel<"), plan.layer_kernel(b, 0)
+        finally:
+            plan.destroy()
+        want = oracle.run_chain(chain, t)
+        dev, host = run_gpu(chain, t, flags=flags)
+        np.testing.assert_array_equal(dev, host)
+        assert rel_err(dev, want) <= TOL[dtype]
+        ti = workloads.small_int_tensors(chain, seed=9)
+        want = oracle.run_chain(chain, ti)
+        if np.abs(want).max() < (256 if dtype == "bf16" else 2 ** 24):
+            dev, _ = run_gpu(chain, ti, flags=flags)
+            np.testing.assert_array_equal(dev, want)
+
+
 def test_small_layer_kernel_is_selected():
     """The grid above reaches every variant of the small-layer kernel: one launch, and a
     launch cut across workgroups followed by the finish kernel."""
