@@ -801,10 +801,11 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
   constexpr int CP = BN + 4;                // fp32 pitch of a staged partial tile
   constexpr int VE = KE;
+  constexpr bool AHEAD = sizeof(T) == 4;    // read the next stage's fragments during this stage's MFMAs
   constexpr int PIECES = BM * (BN / VE);    // 16-byte output pieces of the tile
   constexpr int RED_BYTES = 4 * BM * CP * 4;
   constexpr int SMEM = NST * STAGE > RED_BYTES ? NST * STAGE : RED_BYTES;
-  static_assert(BM % 32 == 0 && BN % 32 == 0 && NST >= 2 && (NST - 2) * LPS < 64 && NST * STAGE <= 160 * 1024, "tile shape");
+  static_assert(BM % 32 == 0 && BN % 32 == 0 && NST >= 3 && (NST - 2) * LPS < 64 && NST * STAGE <= 160 * 1024, "tile shape");
   __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -930,25 +931,33 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   // hand instead: vmcnt before the barrier for the stage about to be read, lgkmcnt behind the
   // reads (tied to the fragment registers, so no MFMA can move in front of it).
   const unsigned lds0 = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char*)smem + foff;
-  u32x4 px[TM], wt[TN];
-  auto read_fragments = [&](int s) __attribute__((always_inline)) {
+  u32x4 px[TM], wt[TN];      // fragments of the stage being multiplied
+  u32x4 px_n[TM], wt_n[TN];  // ... of the next stage, on their way from LDS meanwhile
+  auto read_issue = [&](int s) __attribute__((always_inline)) {
     const unsigned at = lds0 + (unsigned)((s % NST) * STAGE);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(px[tm]) : "v"(at), "n"(tm * 4096) : "memory");
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(px_n[tm]) : "v"(at), "n"(tm * 4096) : "memory");
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wt[tn]) : "v"(at), "n"(A_BYTES + tn * 4096) : "memory");
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(wt_n[tn]) : "v"(at), "n"(A_BYTES + tn * 4096) : "memory");
+  };
+  // waits for the reads of read_issue and makes the fragments current
+  auto read_take = [&]() __attribute__((always_inline)) {
     if constexpr (TM == 2 && TN == 2)
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(px[1]), "+v"(wt[0]), "+v"(wt[1]) :: "memory");
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px_n[0]), "+v"(px_n[1]), "+v"(wt_n[0]), "+v"(wt_n[1]) :: "memory");
     else if constexpr (TM == 1 && TN == 2)
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(wt[0]), "+v"(wt[1]) :: "memory");
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px_n[0]), "+v"(wt_n[0]), "+v"(wt_n[1]) :: "memory");
     else if constexpr (TM == 2 && TN == 1)
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(px[1]), "+v"(wt[0]) :: "memory");
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px_n[0]), "+v"(px_n[1]), "+v"(wt_n[0]) :: "memory");
     else {
       static_assert(TM == 1 && TN == 1, "tile shapes up to 64 x 64");
-      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px[0]), "+v"(wt[0]) :: "memory");
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(px_n[0]), "+v"(wt_n[0]) :: "memory");
     }
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) px[tm] = px_n[tm];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) wt[tn] = wt_n[tn];
   };
   auto stage_barrier = [&]() __attribute__((always_inline)) {
     asm volatile("" ::: "memory");
@@ -976,9 +985,13 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
     if (loads) issue_end();
   };
 
-  // ---- NST - 1 stages in flight; one barrier per stage: behind it the next stage is complete
-  // for every wavefront and nobody reads the stage before this one any more, whose buffer the
-  // loads issued among this stage's MFMAs reuse
+  // ---- NST - 1 stages issued ahead; one barrier per stage. AHEAD (fp32, whose MFMAs of a stage
+  // take four times as long as bf16's): behind the barrier of stage s the stage after it is
+  // complete for every wavefront, its fragments are read from LDS while the MFMAs of stage s
+  // run, and the loads issued among those MFMAs reuse the buffer of stage s - 1, which nobody
+  // reads any more (+2.5 % on the fp32 chain). Otherwise the barrier follows the MFMAs and the
+  // fragments of the next stage are read behind it (the bf16 loop is bound by what the L2s
+  // deliver; reading ahead costs it one stage of prefetch depth and measured 2-3 % slower).
   const int pre = min(ns, NST - 1);
   for (int s = 0; s < pre; ++s) {
     issue_begin();
@@ -989,26 +1002,47 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   if (ns > NST - 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LPS));
   else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   stage_barrier();
-  read_fragments(0);
+  read_issue(0);
+  read_take();
   int s = 0;
-  for (; s + NST < ns; ++s) {  // stage s + NST - 1 exists and so does stage s + 1
-    multiply(true);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LPS));
-    stage_barrier();
-    read_fragments(s + 1);
-  }
-  if (s + NST - 1 < ns) {  // the last stage to issue
-    multiply(true);
-    ++s;
+  if constexpr (AHEAD) {
+    for (; s + NST - 1 < ns; ++s) {  // stage s + NST - 1 is still to be issued (and stage s + 1 exists)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 3) * LPS));
+      stage_barrier();
+      read_issue(s + 1);
+      multiply(true);
+      read_take();
+    }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    stage_barrier();
-    read_fragments(s);
+    stage_barrier();                 // everything is in LDS, for every wavefront, and stays
+    for (; s + 1 < ns; ++s) {
+      read_issue(s + 1);
+      multiply(false);
+      read_take();
+    }
   } else {
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  }
-  for (; s + 1 < ns; ++s) {  // everything is in LDS (and stays: no barrier needed any more)
-    multiply(false);
-    read_fragments(s + 1);
+    for (; s + NST < ns; ++s) {      // stage s + NST - 1 exists and so does stage s + 1
+      multiply(true);
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((NST - 2) * LPS));
+      stage_barrier();
+      read_issue(s + 1);
+      read_take();
+    }
+    if (s + NST - 1 < ns) {          // the last stage to issue
+      multiply(true);
+      ++s;
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      stage_barrier();
+      read_issue(s);
+      read_take();
+    } else {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
+    for (; s + 1 < ns; ++s) {        // everything is in LDS (and stays: no barrier needed any more)
+      multiply(false);
+      read_issue(s + 1);
+      read_take();
+    }
   }
   multiply(false);
 
@@ -1097,6 +1131,7 @@ __device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f
 }
 
 constexpr int kNarrowWaves = 16;
+constexpr int kLdsStagesBf16 = 4, kLdsStagesF32 = 8;  // stages of 128 bytes per row in LDS per workgroup
 constexpr int kLdsMinTiles = 48;   // below this the operand-direct kernels (one round of latency) win; 96 and 20 measured slower
 
 template <typename T>
@@ -1417,11 +1452,11 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
       // (twice the stages in flight, 128 KB of LDS, measured no faster per launch - the loop is
       // bound by what the L2s deliver, not by latency - and it keeps other streams' workgroups
       // off the compute unit)
-      if (ld.bn == 32) return launch_lds<T, 64, 32, 4>(p, s, ev);
-      if (ld.bm == 64) return launch_lds<T, 64, 64, 4>(p, s, ev);
-      return launch_lds<T, 32, 64, 4>(p, s, ev);
+      if (ld.bn == 32) return launch_lds<T, 64, 32, kLdsStagesBf16>(p, s, ev);
+      if (ld.bm == 64) return launch_lds<T, 64, 64, kLdsStagesBf16>(p, s, ev);
+      return launch_lds<T, 32, 64, kLdsStagesBf16>(p, s, ev);
     } else {
-      return launch_lds<T, 32, 32, 6>(p, s, ev);
+      return launch_lds<T, 32, 32, kLdsStagesF32>(p, s, ev);
     }
   }
   if (d.wk) {
@@ -1509,7 +1544,7 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   if (const LdsChoice ld = lds_applies(p, L.dtype, c, d); ld.bm) {
     if (name && size)
       snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, false, %d>", bf ? "__bf16" : "float", ld.bm, ld.bn,
-               bf ? 4 : 6, p.C_in * (bf ? 2 : 4) == 64 ? 2 : 1);
+               bf ? kLdsStagesBf16 : kLdsStagesF32, p.C_in * (bf ? 2 : 4) == 64 ? 2 : 1);
     return 1;
   }
   if (d.wk) {
@@ -1584,10 +1619,10 @@ hipError_t launch_convpool(const OpLaunch& conv, const OpLaunch& pool, hipStream
   if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return hipErrorInvalidValue;
   const LdsChoice ld = choose_pooled(p, conv.dtype);
   if (conv.dtype == LOP_BF16) {
-    if (ld.bm == 64) return launch_lds<__bf16, 64, 64, 4>(p, stream, ev);
-    return launch_lds<__bf16, 32, 64, 4>(p, stream, ev);
+    if (ld.bm == 64) return launch_lds<__bf16, 64, 64, kLdsStagesBf16>(p, stream, ev);
+    return launch_lds<__bf16, 32, 64, kLdsStagesBf16>(p, stream, ev);
   }
-  return launch_lds<float, 32, 32, 6>(p, stream, ev);
+  return launch_lds<float, 32, 32, kLdsStagesF32>(p, stream, ev);
 }
 
 int convpool_describe(const OpLaunch& conv, const OpLaunch& pool, char* name, size_t size) {
@@ -1595,7 +1630,7 @@ int convpool_describe(const OpLaunch& conv, const OpLaunch& pool, char* name, si
   const LdsChoice ld = choose_pooled(p, conv.dtype);
   const bool bf = conv.dtype == LOP_BF16;
   if (name && size)
-    snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, true, 1>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? 4 : 6);
+    snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, true, 1>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? kLdsStagesBf16 : kLdsStagesF32);
   return 1;
 }
 
