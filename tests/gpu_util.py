@@ -75,3 +75,10 @@ def run_gpu(chain, tensors, n_bands=None, use_host=True, flags=0):
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     scale = float(np.abs(want).max())
     return float(np.abs(got.astype(np.float64) - want.astype(np.float64)).max()) / max(scale, 1e-30)
+
+
+def elementwise_err(got: np.ndarray, want: np.ndarray) -> float:
+    """Second error figure: max over elements of |gpu - oracle| / max(|oracle|, 1e-3 max|oracle|)
+    (a floor under the denominator because ReLU outputs hold exact zeros)."""
+    w = np.abs(want.astype(np.float64))
+    return float((np.abs(got.astype(np.float64) - want.astype(np.float64)) / np.maximum(w, 1e-3 * w.max())).max())
