@@ -423,12 +423,18 @@ def main():
     head["one_band"] = one_band_reference(torch, lop, workloads, a.workload, a.mode, a)
     c = lop.lop_measure_ceilings()
     ceil = {"hbm_copy_GBps": round(c.hbm_copy_gbs, 1), "mfma_bf16_TFLOPps": round(c.mfma_bf16_tflops, 1),
-            "mfma_f32_TFLOPps": round(c.mfma_f32_tflops, 1)}
+            "mfma_f32_TFLOPps": round(c.mfma_f32_tflops, 1), "launch_floor_us": round(c.launch_floor_us, 2)}
 
     def against_measured(roof, dtype):
         m = c.hbm_copy_gbs if roof["bound"] == "hbm" else (c.mfma_bf16_tflops if dtype == "bf16" else c.mfma_f32_tflops)
         roof["measured_peak"] = round(m, 1)
         roof["frac_of_measured"] = round(roof["achieved"] / m, 4)
+        # what a launch of this size could reach at most: its work at the published peak behind
+        # the measured cost of a launch that does nothing
+        work = roof["algorithmic_bytes_per_launch"] / 1e3 if roof["bound"] == "hbm" else roof["algorithmic_flop_per_launch"] / 1e6
+        t_peak_us = work / roof["peak"]            # kB / (GB/s) and MFLOP / (TFLOP/s) are both microseconds
+        roof["launch_floor_us"] = round(c.launch_floor_us, 2)
+        roof["frac_ceiling_at_this_launch_size"] = round(t_peak_us / (t_peak_us + c.launch_floor_us), 4)
 
     against_measured(head["roofline"], head["dtype"])
     against_measured(second["roofline"], second["dtype"])

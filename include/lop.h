@@ -326,10 +326,12 @@ LOP_API int lop_run_two_party(lop_plan_t* plan, const void* d_in, void* d_out, c
  * plain 16-byte-vector copy between two 1 GiB device buffers; mfma_bf16_tflops / mfma_f32_tflops
  * = rate of a loop of nothing but independent 32x32x16 bf16 (32x32x2 fp32) MFMAs with two
  * wavefronts on every SIMD and operand bits that differ per lane (all-zero operands clock
- * higher than real data). Best of five launches each. Allocates and frees 2 GiB of device
+ * higher than real data). Best of five launches each. launch_floor_us: mean duration, from
+ * events attached to the dispatch, of a kernel of 128 workgroups that returns at once: what a
+ * launch costs before it does anything. Allocates and frees 2 GiB of device
  * memory inside the call; synchronous; uses the null stream. Measurement aid: the roofline's
  * denominators stay the published peaks, these say how close any kernel can get here. */
-typedef struct { double hbm_copy_gbs, mfma_bf16_tflops, mfma_f32_tflops; } lop_ceilings_t;
+typedef struct { double hbm_copy_gbs, mfma_bf16_tflops, mfma_f32_tflops, launch_floor_us; } lop_ceilings_t;
 LOP_API int lop_measure_ceilings(lop_ceilings_t* out /* host */);
 
 /* Time one layer's kernel of one band in isolation: `iters` launches on the plan's

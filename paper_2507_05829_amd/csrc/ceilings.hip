@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include "lop.h"
+#include "launch.hpp"
 #include "plan_state.hpp"
 
 namespace {
@@ -93,6 +94,9 @@ struct Buffers {
   }
 };
 
+// Returns at once (the argument only gives the launch something to pass).
+__global__ void empty_kernel(float* sink) { (void)sink; }
+
 }  // namespace
 
 extern "C" int lop_measure_ceilings(lop_ceilings_t* out) {
@@ -132,6 +136,25 @@ extern "C" int lop_measure_ceilings(lop_ceilings_t* out) {
   rc = timed([&] { hipLaunchKernelGGL(mfma_f32_kernel, dim3(kWaveGrid), dim3(256), 0, nullptr, B.sink); }, 5, &t);
   if (rc != LOP_OK) return rc;
   out->mfma_f32_tflops = waves * kMfmaIters * kMfmaChains * (2.0 * 32 * 32 * 2) / (t * 1e-3) / 1e12;
+  // what a launch costs before it does anything: a kernel of 128 workgroups that returns at
+  // once, timed by events attached to the dispatch like every per-launch figure of the library
+  {
+    lop::KernelEvents ev;
+    LOP_HIP(hipEventCreate(&ev.start[0]));
+    LOP_HIP(hipEventCreate(&ev.stop[0]));
+    double sum = 0.0;
+    constexpr int kReps = 20;
+    for (int r = 0; r < kReps + 1; ++r) {
+      ev.n = 0;
+      LOP_HIP(lop::launch_kernel(empty_kernel, dim3(128), dim3(256), nullptr, &ev, B.sink));
+      LOP_HIP(hipEventSynchronize(ev.stop[0]));
+      LOP_HIP(hipEventElapsedTime(&ms, ev.start[0], ev.stop[0]));
+      if (r > 0) sum += ms;   // (the first one warms up)
+    }
+    out->launch_floor_us = sum / kReps * 1e3;
+    (void)hipEventDestroy(ev.start[0]);
+    (void)hipEventDestroy(ev.stop[0]);
+  }
   LOP_HIP(hipDeviceSynchronize());
   return LOP_OK;
 }
