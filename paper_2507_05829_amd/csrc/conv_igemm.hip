@@ -1254,6 +1254,28 @@ constexpr int kNarrowMaxTiles = 320;
 
 // The LDS-staged mid-size kernel: which tile, or bm == 0 when it does not apply.
 struct LdsChoice { int bm, bn; long tiles; };
+// The tile of a launch. The reduction loop of this kernel is bound by the rate at which one
+// compute unit pulls its tile's operand rows (BM + BN rows of 128 bytes per stage), and launches
+// of this size leave compute units idle: a smaller tile spreads the same rows over more compute
+// units, until there are more workgroups than units and some unit has to take two. So the cost of
+// a shape is (workgroups per compute unit, rounded up) x (BM + BN); the cheapest shape with at
+// least min_tiles workgroups wins, the larger one on a tie (less traffic from the L2s).
+LdsChoice pick_lds_tile(const ConvParams& p, int dtype, long min_tiles) {
+  auto tiles = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn); };
+  if (dtype != LOP_BF16) return tiles(32, 32) >= min_tiles ? LdsChoice{32, 32, tiles(32, 32)} : LdsChoice{0, 0, 0};
+  static const int shapes[][2] = {{64, 64}, {32, 64}, {64, 32}, {32, 32}};
+  LdsChoice best{0, 0, 0};
+  long best_cost = 0;
+  for (const auto& sh : shapes) {
+    if (sh[1] == 32 && sh[0] == 64 && p.C_out > 32) continue;   // (the 64 x 32 tile is there for narrow layers)
+    const long t = tiles(sh[0], sh[1]);
+    if (t < min_tiles) continue;
+    const long cost = (t + kComputeUnits - 1) / kComputeUnits * (sh[0] + sh[1]);
+    if (!best.bm || cost < best_cost) { best = {sh[0], sh[1], t}; best_cost = cost; }
+  }
+  return best;
+}
+
 LdsChoice choose_lds(const ConvParams& p, int dtype) {
   const int esz = dtype == LOP_BF16 ? 2 : 4, ke = 16 / esz;
   const bool half_rows = p.C_in * esz == 64;   // two taps per stage
@@ -1261,15 +1283,7 @@ LdsChoice choose_lds(const ConvParams& p, int dtype) {
   if (p.C_out % ke != 0 || (p.k_pad * esz) % 128 != 0) return {0, 0, 0};
   // 32-bit signed byte offsets into the input slab
   if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return {0, 0, 0};
-  auto tiles = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn); };
-  if (dtype == LOP_BF16) {
-    if (p.C_out <= 32 && tiles(64, 32) >= kLdsMinTiles) return {64, 32, tiles(64, 32)};
-    if (tiles(64, 64) >= kLdsMinTiles) return {64, 64, tiles(64, 64)};
-    if (tiles(32, 64) >= kLdsMinTiles) return {32, 64, tiles(32, 64)};
-    return {0, 0, 0};
-  }
-  if (tiles(32, 32) >= kLdsMinTiles) return {32, 32, tiles(32, 32)};
-  return {0, 0, 0};
+  return pick_lds_tile(p, dtype, kLdsMinTiles);
 }
 
 template <typename T, int BM, int BN, int NST>
@@ -1452,6 +1466,7 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
       // (twice the stages in flight, 128 KB of LDS, measured no faster per launch - the loop is
       // bound by what the L2s deliver, not by latency - and it keeps other streams' workgroups
       // off the compute unit)
+      if (ld.bm == 32 && ld.bn == 32) return launch_lds<T, 32, 32, kLdsStagesBf16>(p, s, ev);
       if (ld.bn == 32) return launch_lds<T, 64, 32, kLdsStagesBf16>(p, s, ev);
       if (ld.bm == 64) return launch_lds<T, 64, 64, kLdsStagesBf16>(p, s, ev);
       return launch_lds<T, 32, 64, kLdsStagesBf16>(p, s, ev);
@@ -1580,10 +1595,8 @@ ConvParams make_pooled_params(const OpLaunch& conv, const OpLaunch& pool) {
 // The tile of a pooled launch: the LDS kernel always takes it (there is no other kernel that
 // pools), with the smaller pixel tile when the larger would leave most of the chip idle.
 LdsChoice choose_pooled(const ConvParams& p, int dtype) {
-  auto tiles = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((p.C_out + bn - 1) / bn); };
-  if (dtype != LOP_BF16) return {32, 32, tiles(32, 32)};
-  if (tiles(64, 64) >= kLdsMinTiles) return {64, 64, tiles(64, 64)};
-  return {32, 64, tiles(32, 64)};
+  const LdsChoice c = pick_lds_tile(p, dtype, 1);
+  return c.bm ? c : LdsChoice{32, 32, 1};
 }
 }  // namespace
 
@@ -1619,6 +1632,8 @@ hipError_t launch_convpool(const OpLaunch& conv, const OpLaunch& pool, hipStream
   if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return hipErrorInvalidValue;
   const LdsChoice ld = choose_pooled(p, conv.dtype);
   if (conv.dtype == LOP_BF16) {
+    if (ld.bm == 32 && ld.bn == 32) return launch_lds<__bf16, 32, 32, kLdsStagesBf16>(p, stream, ev);
+    if (ld.bn == 32) return launch_lds<__bf16, 64, 32, kLdsStagesBf16>(p, stream, ev);
     if (ld.bm == 64) return launch_lds<__bf16, 64, 64, kLdsStagesBf16>(p, stream, ev);
     return launch_lds<__bf16, 32, 64, kLdsStagesBf16>(p, stream, ev);
   }
