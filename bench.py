@@ -482,7 +482,10 @@ def main():
         # their kernel time against the matrix-core peak of the type, and the share of the
         # output's link time (bytes / measured D2H rate) that did not lengthen the chain
         "mfma_utilisation": dense.get("frac_of_mfma_peak"),
-        "d2h_hidden": head["d2h"]["hidden_vs_link_rate"],
+        # (null when the exposed time is within the spread of the repeats: a 49 KiB output per
+        # image is 1-2 us at the link's rate, which a difference of two timed runs cannot resolve)
+        "d2h_hidden": None if head["d2h"]["within_noise"] else head["d2h"]["hidden_vs_link_rate"],
+        "d2h_exposed_us_per_chain": head["d2h"]["exposed_us_per_chain"],
         "measured_ceilings": ceil,
         "modes": {a.mode: head, other: second},
         "also": also,
