@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--chains-per-step", type=int, default=64,
                     help="chains (images, or batches for a batched chain) back to back in one step")
     ap.add_argument("--workload", default="resnet18")
-    ap.add_argument("--mode", default="independent", choices=["independent", "reuse"],
+    ap.add_argument("--mode", default="independent", choices=["independent", "reuse", "batched"],
                     help="independent: every band recomputes its halos (the method as stated); "
                          "reuse: bands run in order and reuse rows earlier bands produced")
     ap.add_argument("--also", default="detector720p,vgg16,mbv2,mbv2:nofuse,tiny",
@@ -98,6 +98,7 @@ class Case:
         flags = (lop.LOP_FLAG_LANES(a.lanes) | (lop.LOP_FLAG_GRAPH if a.graph else 0)
                  | (lop.LOP_FLAG_DMA_COPY if a.dma_copy else 0)
                  | (lop.LOP_FLAG_REUSE if mode == "reuse" else 0)
+                 | (lop.LOP_FLAG_BATCH_BANDS if mode == "batched" else 0)
                  | (lop.LOP_FLAG_NO_FUSE if nofuse else 0))
         self.plan = (lop.Plan.rowwise if rowwise else lop.Plan)(self.chain, self.tensors, flags=flags)
         x = torch.from_numpy(self.tensors.x if rowwise else
@@ -161,6 +162,16 @@ def d2h_bandwidth(torch, nbytes=64 << 20):
     return best
 
 
+def weight_bytes(chain, l):
+    """Bytes of layer l's weights as the work model counts them."""
+    L = chain.layers[l]
+    if getattr(L, "op", None) not in ("conv", "dwconv"):
+        return 0.0
+    esz = 2 if chain.dtype == "bf16" else 4
+    groups = L.c_in if L.op == "dwconv" else 1
+    return float(esz * L.c_out * (L.c_in // groups) * L.k[0] * L.k[1])
+
+
 def launch_rows(case, iters):
     """Every (layer, band) launch of one chain, timed on one stream, one lane, with a start and
     a stop HIP event attached to the dispatch itself (the kernel's own duration, as a
@@ -179,6 +190,11 @@ def launch_rows(case, iters):
             if not name:
                 continue
             flop, byts = plan.layer_work(b, l)
+            if case.mode == "batched":      # one launch for all bands: their work, the weights once
+                parts = [plan.layer_work(bb, l) for bb in range(plan.n_bands)]
+                active = sum(1 for f, _ in parts if f > 0)
+                flop = sum(f for f, _ in parts)
+                byts = sum(y for _, y in parts) - max(active - 1, 0) * weight_bytes(case.chain, l)
             us = float(ms[b, l]) * 1e3
             fus = float(fin[b, l]) * 1e3 if slices > 1 else 0.0
             ai = flop / max(byts, 1.0)
@@ -339,7 +355,9 @@ def measure(torch, lop, workloads, name, mode, a, steps, warmup, link_gbs, nofus
 def one_band_reference(torch, lop, workloads, name, mode, a, nofuse=False, tables=True):
     """The same chain as ONE band (no partition): throughput, single-request latency and the
     per-layer table at B = 1."""
-    case = Case(torch, lop, workloads, name, mode, a, 1, nofuse)
+    # (scheduled like reuse mode, so that consecutive chains rotate over the lanes: with one band
+    # the modes compute the same, and independent mode would keep a single band on a single lane)
+    case = Case(torch, lop, workloads, name, "reuse", a, 1, nofuse)
     cps = max(1, a.chains_per_step // case.images)
     chains = max(2, a.steps // 2) * cps
     t = repeated_regions(case, chains, 2 * cps, copy=True, min_s=0.2)
@@ -417,9 +435,15 @@ def main():
         return
 
     link = d2h_bandwidth(torch)
-    other = "reuse" if a.mode == "independent" else "independent"
+    others = [m for m in ("independent", "batched", "reuse") if m != a.mode]
     head_case, head = measure(torch, lop, workloads, a.workload, a.mode, a, a.steps, a.warmup, link)
-    _, second = measure(torch, lop, workloads, a.workload, other, a, a.steps, a.warmup, link)
+    seconds = {}
+    for m in others:
+        try:
+            _, seconds[m] = measure(torch, lop, workloads, a.workload, m, a, a.steps, a.warmup, link)
+        except lop.LopError as e:     # (launches batched over the bands: not every kernel has that form)
+            if e.code != lop.LOP_ERR_UNSUPPORTED:
+                raise
     head["one_band"] = one_band_reference(torch, lop, workloads, a.workload, a.mode, a)
     c = lop.lop_measure_ceilings()
     ceil = {"hbm_copy_GBps": round(c.hbm_copy_gbs, 1), "mfma_bf16_TFLOPps": round(c.mfma_bf16_tflops, 1),
@@ -437,7 +461,8 @@ def main():
         roof["frac_ceiling_at_this_launch_size"] = round(t_peak_us / (t_peak_us + c.launch_floor_us), 4)
 
     against_measured(head["roofline"], head["dtype"])
-    against_measured(second["roofline"], second["dtype"])
+    for r in seconds.values():
+        against_measured(r["roofline"], r["dtype"])
 
     also = {}
     light_steps = max(2, a.steps // 4)
@@ -447,12 +472,17 @@ def main():
         if name == a.workload and not nofuse:
             continue
         per_mode = {}
-        for mode in (a.mode, other):
+        for mode in [a.mode] + others:
             if nofuse and mode != a.mode:
                 continue      # the layer-by-layer run is there for its kernels' own rates
             tables = name in ("vgg16", "detector720p") or nofuse
-            _, r = measure(torch, lop, workloads, name, mode, a, light_steps, 1, link, nofuse,
-                           tables=tables, min_s=0.25)
+            try:
+                _, r = measure(torch, lop, workloads, name, mode, a, light_steps, 1, link, nofuse,
+                               tables=tables, min_s=0.25)
+            except lop.LopError as e:
+                if e.code != lop.LOP_ERR_UNSUPPORTED:
+                    raise
+                continue
             against_measured(r["roofline"], r["dtype"])
             if mode == a.mode and not nofuse:
                 r["one_band"] = one_band_reference(torch, lop, workloads, name, mode, a, nofuse,
@@ -471,8 +501,10 @@ def main():
         "dtype": "f32" if chain.dtype == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload} {'x'.join(map(str, chain.in_shape))} {chain.dtype}, "
                                f"{head['n_bands']} row bands, {head['n_layers']} layers",
-                   "mode": ("independent: every band recomputes its halos" if a.mode == "independent" else
-                            "reuse: bands in order, rows produced by earlier bands are reused"),
+                   "mode": {"independent": "independent: every band recomputes its halos, one launch per band and layer",
+                            "batched": "independent bands (every band recomputes its halos), one launch per layer for "
+                                       "all bands (operation batching, Sec. IV-D)",
+                            "reuse": "reuse: bands in order, rows produced by earlier bands are reused"}[a.mode],
                    "chains_per_step": head["chains_per_step"], "images_per_chain": head["images_per_chain"],
                    "timed_region": f"{a.steps} steps, median of {head['repeats']} repeats",
                    "executed_over_useful_flop": head["executed_over_useful"],
@@ -487,7 +519,7 @@ def main():
         "d2h_hidden": None if head["d2h"]["within_noise"] else head["d2h"]["hidden_vs_link_rate"],
         "d2h_exposed_us_per_chain": head["d2h"]["exposed_us_per_chain"],
         "measured_ceilings": ceil,
-        "modes": {a.mode: head, other: second},
+        "modes": {a.mode: head, **seconds},
         "also": also,
     }
     if not a.no_cpu_baseline:

@@ -105,6 +105,15 @@ typedef struct {
                                  lanes. lop_run_band must be called for bands 0,1,2,... in
                                  order.                                                   */
 #define LOP_DEFAULT_LANES 4
+#define LOP_FLAG_BATCH_BANDS 128u /* independent bands (every halo row recomputed) whose launches are
+                                 batched per operator (Sec. IV-D operation batching): all bands of
+                                 a chain run on one lane, every layer is one launch that computes
+                                 its rows for every band (each band on its own slabs), and chains
+                                 of consecutive calls rotate over the lanes. The bands' rows leave
+                                 behind the last layer's launch. Not with LOP_FLAG_REUSE; at most
+                                 16 bands; LOP_ERR_UNSUPPORTED if an operator of the chain has no
+                                 kernel form that takes several bands (the inverted-residual
+                                 block, the 1x1 streaming and 3x3 depthwise kernels)      */
 #define LOP_FLAG_NO_FUSE 32u  /* run every layer as a launch of its own. By default a 1x1 conv,
                                  a 3x3 depthwise conv and a 1x1 conv in a row whose middle
                                  tensors nobody else reads (an inverted-residual block) run as

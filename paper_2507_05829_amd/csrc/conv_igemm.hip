@@ -184,9 +184,9 @@ __device__ __forceinline__ void finish_vec(const ConvParams& p, int m, int co, f
 // 8 x 8 tiles that shares 8 pixel tiles and 8 weight tiles. Reduction slices are outermost.
 struct TileId { int m, n, z; };
 constexpr int kXcds = 8, kGroupM = 8;
-__device__ __forceinline__ TileId xcd_tile(int mx, int ny, int nz) {
+__device__ __forceinline__ TileId xcd_tile(int bx, int mx, int ny, int nz) {
   const int total = mx * ny * nz;
-  const int launch = blockIdx.x + mx * (blockIdx.y + ny * blockIdx.z);
+  const int launch = bx + mx * (blockIdx.y + ny * blockIdx.z);
   const int xcd = launch % kXcds, slot = launch / kXcds;
   const int q = total / kXcds, r = total % kXcds;
   const int v = xcd * q + min(xcd, r) + slot;  // XCD k owns q (+1 for the first r) consecutive tiles
@@ -207,7 +207,7 @@ __device__ __forceinline__ TileId xcd_tile(int mx, int ny, int nz) {
 // never straddles two taps. blockIdx.z selects a slice of the reduction (split-K): the
 // slices' fp32 partial tiles go to p.ws and splitk_finish_kernel adds them in slice order.
 template <typename T, int BM, int BN, int WM, int WN, int BKB, int NS, bool VEC_A>
-__global__ __launch_bounds__(64 * WM * WN) void conv_igemm_kernel(const ConvParams p) {
+__device__ __forceinline__ void conv_igemm_kernel_body(const ConvParams& p, const int bx, const int gx) {
   constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
   constexpr int CH = BKB / 16;             // vectors per row and step
   constexpr int BKE = CH * KE;             // reduction elements per step
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_igemm_kernel(const ConvPara
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
-  const TileId tile = xcd_tile(gridDim.x, gridDim.y, gridDim.z);
+  const TileId tile = xcd_tile(bx, gx, gridDim.y, gridDim.z);
   const int m0 = tile.m * BM, co0 = tile.n * BN;
   const int lrow = tid / CH, chunk = tid % CH;
   const T* __restrict__ xg = (const T*)p.x;
@@ -514,12 +514,24 @@ __global__ __launch_bounds__(64 * WM * WN) void conv_igemm_kernel(const ConvPara
   }
 }
 
+template <typename T, int BM, int BN, int WM, int WN, int BKB, int NS, bool VEC_A>
+__global__ __launch_bounds__(64 * WM * WN) void conv_igemm_kernel(const ConvParams p) {
+  conv_igemm_kernel_body<T, BM, BN, WM, WN, BKB, NS, VEC_A>(p, blockIdx.x, gridDim.x);
+}
+// The same for several bands of one layer in one grid (band b owns blocks first[b] .. first[b + 1] of x).
+template <typename T, int BM, int BN, int WM, int WN, int BKB, int NS, bool VEC_A>
+__global__ __launch_bounds__(64 * WM * WN) void conv_igemm_kernel_bands(const Batch<ConvParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  conv_igemm_kernel_body<T, BM, BN, WM, WN, BKB, NS, VEC_A>(t.p[b], blockIdx.x - t.first[b], t.first[b + 1] - t.first[b]);
+}
+
+
 // Adds the split-K slices in slice order and applies the epilogue: one thread per 4
 // consecutive channels of a pixel.
 template <typename T>
-__global__ __launch_bounds__(256) void splitk_finish_kernel(const ConvParams p) {
+__device__ __forceinline__ void splitk_finish_kernel_body(const ConvParams& p, const int bx, const int gx) {
   const int cq = (p.C_out + 3) / 4;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)bx * 256 + threadIdx.x;
   if (gid >= (long)p.M * cq) return;
   const int m = (int)(gid / cq), co = (int)(gid % cq) * 4;
   float v[4] = {0.f, 0.f, 0.f, 0.f};
@@ -558,6 +570,18 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const ConvParams p) 
   finish4<T>(p, pixel_addr(p, m), co, v);
 }
 
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(const ConvParams p) {
+  splitk_finish_kernel_body<T>(p, blockIdx.x, gridDim.x);
+}
+// The same for several bands of one layer in one grid (band b owns blocks first[b] .. first[b + 1] of x).
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_finish_kernel_bands(const Batch<ConvParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  splitk_finish_kernel_body<T>(t.p[b], blockIdx.x - t.first[b], t.first[b + 1] - t.first[b]);
+}
+
+
 // Small layers (few output pixels x channels, long reduction): one workgroup owns a
 // 32-pixel x (32*NT)-channel tile and its WK wavefronts split the reduction axis among
 // themselves, each taking one contiguous slice. Nothing is shared between the wavefronts
@@ -575,7 +599,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(const ConvParams p) 
 // sustains a small share of the HBM rate) also cut the reduction across blockIdx.z: every
 // slice writes its fp32 partial tile to p.ws and splitk_finish_kernel adds the slices.
 template <typename T, int WK, int NT>
-__global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p) {
+__device__ __forceinline__ void conv_direct_kernel_body(const ConvParams& p, const int bx, const int gx) {
   constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
   constexpr int MK = 2 * KE;               // reduction elements per step (two lane halves)
   constexpr int U = (WK == 16 && NT == 2) ? 4 : 8;  // steps of loads in flight (register budget)
@@ -591,7 +615,7 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int px = lane & 31, kg = lane >> 5;
-  const int m0 = blockIdx.x * BM, co0 = blockIdx.y * BN;
+  const int m0 = bx * BM, co0 = blockIdx.y * BN;
   const T* __restrict__ xg = (const T*)p.x;
   const u32x4* __restrict__ wg = (const u32x4*)p.wd;
   const bool partial = p.ws != nullptr;
@@ -752,6 +776,18 @@ __global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p
   }
 }
 
+template <typename T, int WK, int NT>
+__global__ __launch_bounds__(64 * WK) void conv_direct_kernel(const ConvParams p) {
+  conv_direct_kernel_body<T, WK, NT>(p, blockIdx.x, gridDim.x);
+}
+// The same for several bands of one layer in one grid (band b owns blocks first[b] .. first[b + 1] of x).
+template <typename T, int WK, int NT>
+__global__ __launch_bounds__(64 * WK) void conv_direct_kernel_bands(const Batch<ConvParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  conv_direct_kernel_body<T, WK, NT>(t.p[b], blockIdx.x - t.first[b], t.first[b + 1] - t.first[b]);
+}
+
+
 // Mid-size layers (hundreds to tens of thousands of pixels, 64..512 channels, a reduction of
 // hundreds to thousands of elements: most launches of the banded 224 x 224 and 720p chains).
 // Such a launch is too small for the 128-wide tiles to cover the chip and too large for the
@@ -792,7 +828,7 @@ constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4
 // second one), and the reduction axis may end in the middle of the last stage: the tap past the
 // end is fetched from the zero line like a tap outside the image (its weights are zero padding).
 template <typename T, int BM, int BN, int NST, bool POOL, int TPS>
-__global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
+__device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const int bx, const int gx) {
   constexpr int KE = 16 / (int)sizeof(T);   // elements per 16-byte chunk
   constexpr int SKE = 8 * KE;               // reduction elements per stage (128 bytes per row)
   constexpr int TM = BM / 32, TN = BN / 32; // 32 x 32 MFMA tiles of the workgroup tile
@@ -812,7 +848,7 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // every XCD takes a contiguous stretch of the tiles (a few pixel tiles times the channel
   // tiles), so that its L2 pulls a part of each operand instead of all of both
-  const TileId tile = xcd_tile(gridDim.x, gridDim.y, 1);
+  const TileId tile = xcd_tile(bx, gx, gridDim.y, 1);
   const int m0 = tile.m * BM, co0 = tile.n * BN;
   const unsigned char* __restrict__ xg = (const unsigned char*)p.x;
   const unsigned char* __restrict__ wg = (const unsigned char*)p.w;
@@ -1103,6 +1139,18 @@ __global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
   }
 }
 
+template <typename T, int BM, int BN, int NST, bool POOL, int TPS>
+__global__ __launch_bounds__(256) void conv_lds_kernel(const ConvParams p) {
+  conv_lds_kernel_body<T, BM, BN, NST, POOL, TPS>(p, blockIdx.x, gridDim.x);
+}
+// The same for several bands of one layer in one grid (band b owns blocks first[b] .. first[b + 1] of x).
+template <typename T, int BM, int BN, int NST, bool POOL, int TPS>
+__global__ __launch_bounds__(256) void conv_lds_kernel_bands(const Batch<ConvParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  conv_lds_kernel_body<T, BM, BN, NST, POOL, TPS>(t.p[b], blockIdx.x - t.first[b], t.first[b + 1] - t.first[b]);
+}
+
+
 // Whether (and how) the direct kernel takes a launch: only layers that the tiled kernel
 // would cut along the reduction axis, with vectorisable channel counts.
 // 16 x 16 MFMA tiles of the same operand-direct scheme, for the layers with very few pixels
@@ -1135,7 +1183,7 @@ constexpr int kLdsStagesBf16 = 4, kLdsStagesF32 = 8;  // stages of 128 bytes per
 constexpr int kLdsMinTiles = 48;   // below this the operand-direct kernels (one round of latency) win; 96 and 20 measured slower
 
 template <typename T>
-__global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const ConvParams p) {
+__device__ __forceinline__ void conv_narrow_kernel_body(const ConvParams& p, const int bx, const int gx) {
   constexpr int WK = kNarrowWaves;
   constexpr int KE = 16 / (int)sizeof(T);  // elements per 16-byte vector
   constexpr int MK = 4 * KE;               // reduction elements per step (four lane quarters)
@@ -1149,7 +1197,7 @@ __global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const Co
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int px = lane & 15, kq = lane >> 4;
-  const int m0 = blockIdx.x * 16, co0 = blockIdx.y * 16;
+  const int m0 = bx * 16, co0 = blockIdx.y * 16;
   const T* __restrict__ xg = (const T*)p.x;
   const u32x4* __restrict__ wg = (const u32x4*)p.wd16;
 
@@ -1249,6 +1297,18 @@ __global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const Co
   if (p.y2) *(u32x4*)((T*)p.y2 + e_y) = *(const u32x4*)o;
 }
 
+template <typename T>
+__global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel(const ConvParams p) {
+  conv_narrow_kernel_body<T>(p, blockIdx.x, gridDim.x);
+}
+// The same for several bands of one layer in one grid (band b owns blocks first[b] .. first[b + 1] of x).
+template <typename T>
+__global__ __launch_bounds__(64 * kNarrowWaves) void conv_narrow_kernel_bands(const Batch<ConvParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  conv_narrow_kernel_body<T>(t.p[b], blockIdx.x - t.first[b], t.first[b + 1] - t.first[b]);
+}
+
+
 constexpr int kComputeUnits = 256;
 constexpr int kNarrowMaxTiles = 320;
 
@@ -1286,18 +1346,30 @@ LdsChoice choose_lds(const ConvParams& p, int dtype) {
   return pick_lds_tile(p, dtype, kLdsMinTiles);
 }
 
+// blocks of x per band for tiles of `per` pixels
+inline void blocks_per_band(const ConvParams* ps, int n, int per, unsigned* gx) {
+  for (int b = 0; b < n; ++b) gx[b] = (unsigned)((ps[b].M + per - 1) / per);
+}
+
 template <typename T, int BM, int BN, int NST>
-hipError_t launch_lds(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
-  dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN);
-  if ((int)grid.y * BN > conv_cout_pad(p.C_out) || grid.y > 65535) return hipErrorInvalidValue;
+hipError_t launch_lds(const ConvParams* ps, int n, hipStream_t s, KernelEvents* ev) {
+  const ConvParams& p = ps[0];
+  unsigned gx[kMaxBatch];
+  blocks_per_band(ps, n, BM, gx);
+  const unsigned gy = (unsigned)((p.C_out + BN - 1) / BN);
+  if ((int)gy * BN > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
   const int row_bytes = p.C_in * (int)sizeof(T);
   if (row_bytes == 64) {
     if (p.pool) return hipErrorInvalidValue;
-    return launch_kernel(conv_lds_kernel<T, BM, BN, NST, false, 2>, grid, dim3(256), s, ev, p);
+    return launch_group(conv_lds_kernel<T, BM, BN, NST, false, 2>, conv_lds_kernel_bands<T, BM, BN, NST, false, 2>,
+                        ps, n, gx, gy, 1, dim3(256), s, ev);
   }
   if (row_bytes % 128 != 0 || p.k_pad != p.K) return hipErrorInvalidValue;
-  if (p.pool) return launch_kernel(conv_lds_kernel<T, BM, BN, NST, true, 1>, grid, dim3(256), s, ev, p);
-  return launch_kernel(conv_lds_kernel<T, BM, BN, NST, false, 1>, grid, dim3(256), s, ev, p);
+  if (p.pool)
+    return launch_group(conv_lds_kernel<T, BM, BN, NST, true, 1>, conv_lds_kernel_bands<T, BM, BN, NST, true, 1>,
+                        ps, n, gx, gy, 1, dim3(256), s, ev);
+  return launch_group(conv_lds_kernel<T, BM, BN, NST, false, 1>, conv_lds_kernel_bands<T, BM, BN, NST, false, 1>,
+                      ps, n, gx, gy, 1, dim3(256), s, ev);
 }
 
 struct DirectChoice {
@@ -1343,28 +1415,35 @@ DirectChoice choose_direct(const ConvParams& p, int dtype, int splits) {
 }
 
 template <typename T, int WK, int NT>
-hipError_t launch_direct(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
-  dim3 grid((p.M + 31) / 32, (p.C_out + 32 * NT - 1) / (32 * NT), p.splits);
-  if ((int)grid.y * 32 * NT > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;  // unguarded weight loads
-  return launch_kernel(conv_direct_kernel<T, WK, NT>, grid, dim3(64 * WK), s, ev, p);
+hipError_t launch_direct(const ConvParams* ps, int n, hipStream_t s, KernelEvents* ev) {
+  const ConvParams& p = ps[0];
+  unsigned gx[kMaxBatch];
+  blocks_per_band(ps, n, 32, gx);
+  const unsigned gy = (unsigned)((p.C_out + 32 * NT - 1) / (32 * NT));
+  if ((int)gy * 32 * NT > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;  // unguarded weight loads
+  return launch_group(conv_direct_kernel<T, WK, NT>, conv_direct_kernel_bands<T, WK, NT>, ps, n, gx, gy,
+                      (unsigned)p.splits, dim3(64 * WK), s, ev);
 }
 
 template <typename T>
-hipError_t launch_direct_any(const ConvParams& p, const DirectChoice& d, hipStream_t s,
+hipError_t launch_direct_any(const ConvParams* ps, int n, const DirectChoice& d, hipStream_t s,
                              KernelEvents* ev) {
   if (d.narrow) {
-    dim3 grid((p.M + 15) / 16, (p.C_out + 15) / 16);
-    if ((int)grid.y * 16 > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
-    return launch_kernel(conv_narrow_kernel<T>, grid, dim3(64 * kNarrowWaves), s, ev, p);
+    unsigned gx[kMaxBatch];
+    blocks_per_band(ps, n, 16, gx);
+    const unsigned gy = (unsigned)((ps[0].C_out + 15) / 16);
+    if ((int)gy * 16 > conv_cout_pad(ps[0].C_out)) return hipErrorInvalidValue;
+    return launch_group(conv_narrow_kernel<T>, conv_narrow_kernel_bands<T>, ps, n, gx, gy, 1,
+                        dim3(64 * kNarrowWaves), s, ev);
   }
   if (d.nt == 2) {
-    if (d.wk == 4) return launch_direct<T, 4, 2>(p, s, ev);
-    if (d.wk == 8) return launch_direct<T, 8, 2>(p, s, ev);
-    return launch_direct<T, 16, 2>(p, s, ev);
+    if (d.wk == 4) return launch_direct<T, 4, 2>(ps, n, s, ev);
+    if (d.wk == 8) return launch_direct<T, 8, 2>(ps, n, s, ev);
+    return launch_direct<T, 16, 2>(ps, n, s, ev);
   }
-  if (d.wk == 4) return launch_direct<T, 4, 1>(p, s, ev);
-  if (d.wk == 8) return launch_direct<T, 8, 1>(p, s, ev);
-  return launch_direct<T, 16, 1>(p, s, ev);
+  if (d.wk == 4) return launch_direct<T, 4, 1>(ps, n, s, ev);
+  if (d.wk == 8) return launch_direct<T, 8, 1>(ps, n, s, ev);
+  return launch_direct<T, 16, 1>(ps, n, s, ev);
 }
 
 enum Shape { S128x128, S128x64, S64x64, S128x32, S256x256 };
@@ -1433,62 +1512,93 @@ LdsChoice lds_applies(const ConvParams& p, int dtype, const Choice& c, const Dir
 }
 
 template <typename T>
-hipError_t launch_finish(const ConvParams& p, hipStream_t s, KernelEvents* ev) {
-  const long work = (long)p.M * ((p.C_out + 3) / 4);
-  return launch_kernel(splitk_finish_kernel<T>, dim3((unsigned)((work + 255) / 256)), dim3(256), s, ev, p);
+hipError_t launch_finish(const ConvParams* ps, int n, hipStream_t s, KernelEvents* ev) {
+  unsigned gx[kMaxBatch];
+  for (int b = 0; b < n; ++b) gx[b] = (unsigned)(((long)ps[b].M * ((ps[b].C_out + 3) / 4) + 255) / 256);
+  return launch_group(splitk_finish_kernel<T>, splitk_finish_kernel_bands<T>, ps, n, gx, 1, 1, dim3(256), s, ev);
 }
 
 template <typename T, int BM, int BN, int WM, int WN>
-hipError_t launch_shape(const ConvParams& p, bool vec_a, hipStream_t s, KernelEvents* ev) {
-  dim3 grid((p.M + BM - 1) / BM, (p.C_out + BN - 1) / BN, p.splits);
+hipError_t launch_shape(const ConvParams* ps, int n, bool vec_a, hipStream_t s, KernelEvents* ev) {
+  const ConvParams& p = ps[0];
+  unsigned gx[kMaxBatch];
+  blocks_per_band(ps, n, BM, gx);
+  const unsigned gy = (unsigned)((p.C_out + BN - 1) / BN);
   const dim3 block(64 * WM * WN);
   // weight loads are unguarded: the channel tiles must end inside the padded packing
-  if ((int)grid.y * BN > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
+  if ((int)gy * BN > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
   const hipError_t e =
-      vec_a ? launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>, grid, block, s, ev, p)
-            : launch_kernel(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>, grid, block, s, ev, p);
+      vec_a ? launch_group(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, true>,
+                           conv_igemm_kernel_bands<T, BM, BN, WM, WN, kBKB, kStages, true>, ps, n, gx, gy,
+                           (unsigned)p.splits, block, s, ev)
+            : launch_group(conv_igemm_kernel<T, BM, BN, WM, WN, kBKB, kStages, false>,
+                           conv_igemm_kernel_bands<T, BM, BN, WM, WN, kBKB, kStages, false>, ps, n, gx, gy,
+                           (unsigned)p.splits, block, s, ev);
   if (e != hipSuccess || !p.ws) return e;
-  return launch_finish<T>(p, s, ev);
+  return launch_finish<T>(ps, n, s, ev);
+}
+
+// The parameters a group of bands is judged by when a kernel is chosen for all of them: those
+// of the first band with the pixels of all (every other field that matters is the layer's).
+ConvParams group_params(const ConvParams* ps, int n) {
+  ConvParams g = ps[0];
+  for (int b = 1; b < n; ++b) g.M += ps[b].M;
+  return g;
+}
+
+// Split-K partial sums of the bands of a group, one region after the other in the workspace.
+size_t assign_workspace(ConvParams* ps, int n, int splits, int kc_per_split, float* ws) {
+  size_t at = 0;
+  for (int b = 0; b < n; ++b) {
+    ps[b].splits = splits;
+    ps[b].kc_per_split = kc_per_split;
+    ps[b].ws = splits > 1 && ws ? ws + at : nullptr;
+    if (splits > 1) at += (size_t)splits * ps[b].M * ps[b].C_out;
+  }
+  return at * sizeof(float);
 }
 
 template <typename T>
-hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, KernelEvents* ev) {
+hipError_t launch_typed(ConvParams* ps, int n, int dtype, float* ws, hipStream_t s, KernelEvents* ev) {
   constexpr int KE = 16 / (int)sizeof(T);
-  const bool vec_a = p.C_in % KE == 0;
+  const bool vec_a = ps[0].C_in % KE == 0;
   // the kernels address a slab with 32-bit byte offsets
-  if ((size_t)p.N * p.x_rows * p.W * p.C_in * sizeof(T) >= ((size_t)1 << 32)) return hipErrorInvalidValue;
-  const Choice c = choose(p, dtype);
-  const DirectChoice d = choose_direct(p, dtype, c.splits);
-  const LdsChoice ld = lds_applies(p, dtype, c, d);
+  for (int b = 0; b < n; ++b)
+    if ((size_t)ps[b].N * ps[b].x_rows * ps[b].W * ps[b].C_in * sizeof(T) >= ((size_t)1 << 32)) return hipErrorInvalidValue;
+  const ConvParams g = group_params(ps, n);
+  const Choice c = choose(g, dtype);
+  const DirectChoice d = choose_direct(g, dtype, c.splits);
+  const LdsChoice ld = lds_applies(g, dtype, c, d);
   if (ld.bm) {
-    p.ws = nullptr;
+    for (int b = 0; b < n; ++b) {
+      ps[b].ws = nullptr;
+      if ((size_t)ps[b].N * ps[b].x_rows * ps[b].W * ps[b].C_in * sizeof(T) >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    }
     if constexpr (sizeof(T) == 2) {
       // (twice the stages in flight, 128 KB of LDS, measured no faster per launch - the loop is
       // bound by what the L2s deliver, not by latency - and it keeps other streams' workgroups
       // off the compute unit)
-      if (ld.bm == 32 && ld.bn == 32) return launch_lds<T, 32, 32, kLdsStagesBf16>(p, s, ev);
-      if (ld.bn == 32) return launch_lds<T, 64, 32, kLdsStagesBf16>(p, s, ev);
-      if (ld.bm == 64) return launch_lds<T, 64, 64, kLdsStagesBf16>(p, s, ev);
-      return launch_lds<T, 32, 64, kLdsStagesBf16>(p, s, ev);
+      if (ld.bm == 32 && ld.bn == 32) return launch_lds<T, 32, 32, kLdsStagesBf16>(ps, n, s, ev);
+      if (ld.bn == 32) return launch_lds<T, 64, 32, kLdsStagesBf16>(ps, n, s, ev);
+      if (ld.bm == 64) return launch_lds<T, 64, 64, kLdsStagesBf16>(ps, n, s, ev);
+      return launch_lds<T, 32, 64, kLdsStagesBf16>(ps, n, s, ev);
     } else {
-      return launch_lds<T, 32, 32, kLdsStagesF32>(p, s, ev);
+      return launch_lds<T, 32, 32, kLdsStagesF32>(ps, n, s, ev);
     }
   }
   if (d.wk) {
     if (d.z > 1 && !ws) return hipErrorInvalidValue;
-    p.splits = d.z;
-    p.kc_per_split = d.per_z;
-    p.ws = d.z > 1 ? ws : nullptr;
-    const hipError_t e = launch_direct_any<T>(p, d, s, ev);
-    if (e != hipSuccess || !p.ws) return e;
-    return launch_finish<T>(p, s, ev);
+    assign_workspace(ps, n, d.z, d.per_z, ws);
+    const hipError_t e = launch_direct_any<T>(ps, n, d, s, ev);
+    if (e != hipSuccess || !ps[0].ws) return e;
+    return launch_finish<T>(ps, n, s, ev);
   }
-  p.splits = c.splits;
-  p.kc_per_split = c.kc_per_split;
   if (c.splits > 1 && !ws) return hipErrorInvalidValue;
-  p.ws = c.splits > 1 ? ws : nullptr;
+  assign_workspace(ps, n, c.splits, c.kc_per_split, ws);
   if (c.shape == S256x256) {
     if constexpr (sizeof(T) == 2) {
+      if (n != 1) return hipErrorInvalidValue;   // (chosen for single launches of at least 256 tiles only)
+      const ConvParams& p = ps[0];
       dim3 grid((p.M + 255) / 256, (p.C_out + 255) / 256, 1);
       if ((int)grid.y * 256 > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
       return launch_kernel(conv_igemm_kernel<T, 256, 256, 2, 4, kBigBKB, kStages, true>, grid, dim3(512), s, ev, p);
@@ -1496,10 +1606,10 @@ hipError_t launch_typed(ConvParams& p, int dtype, float* ws, hipStream_t s, Kern
     return hipErrorInvalidValue;
   }
   switch (c.shape) {
-    case S128x128: return launch_shape<T, 128, 128, 2, 2>(p, vec_a, s, ev);
-    case S128x64: return launch_shape<T, 128, 64, 2, 2>(p, vec_a, s, ev);
-    case S64x64: return launch_shape<T, 64, 64, 2, 2>(p, vec_a, s, ev);
-    default: return launch_shape<T, 128, 32, 4, 1>(p, vec_a, s, ev);
+    case S128x128: return launch_shape<T, 128, 128, 2, 2>(ps, n, vec_a, s, ev);
+    case S128x64: return launch_shape<T, 128, 64, 2, 2>(ps, n, vec_a, s, ev);
+    case S64x64: return launch_shape<T, 64, 64, 2, 2>(ps, n, vec_a, s, ev);
+    default: return launch_shape<T, 128, 32, 4, 1>(ps, n, vec_a, s, ev);
   }
 }
 
@@ -1530,27 +1640,58 @@ int conv_k_pad(int c_in, int kh, int kw, int dtype) {
   return (k + bke - 1) / bke * bke;
 }
 
-size_t conv_workspace_bytes(const OpLaunch& L) {
-  if (stem_applies(L)) return 0;
-  const ConvParams p = make_params(L);
-  if (p.M <= 0) return 0;
-  const Choice c = choose(p, L.dtype);
-  const DirectChoice d = choose_direct(p, L.dtype, c.splits);
-  if (lds_applies(p, L.dtype, c, d).bm) return 0;
-  if (d.wk) return d.z > 1 ? (size_t)d.z * p.M * p.C_out * sizeof(float) : 0;
-  return c.splits > 1 ? (size_t)c.splits * p.M * p.C_out * sizeof(float) : 0;
+namespace {
+// Parameters of the bands of a group that compute something (n_out of them).
+int group_of(const OpLaunch* Ls, int n, ConvParams* ps) {
+  int m = 0;
+  for (int b = 0; b < n && m < kMaxBatch; ++b) {
+    const ConvParams p = make_params(Ls[b]);
+    if (p.M > 0) ps[m++] = p;
+  }
+  return m;
+}
+}  // namespace
+
+size_t conv_workspace_bytes_bands(const OpLaunch* Ls, int n) {
+  if (n < 1 || n > kMaxBatch || stem_applies(Ls[0])) return 0;
+  ConvParams ps[kMaxBatch];
+  const int m = group_of(Ls, n, ps);
+  if (m == 0) return 0;
+  const int dtype = Ls[0].dtype;
+  const ConvParams g = group_params(ps, m);
+  const Choice c = choose(g, dtype);
+  const DirectChoice d = choose_direct(g, dtype, c.splits);
+  if (lds_applies(g, dtype, c, d).bm) return 0;
+  if (d.wk) return d.z > 1 ? assign_workspace(ps, m, d.z, d.per_z, nullptr) : 0;
+  return c.splits > 1 ? assign_workspace(ps, m, c.splits, c.kc_per_split, nullptr) : 0;
+}
+
+size_t conv_workspace_bytes(const OpLaunch& L) { return conv_workspace_bytes_bands(&L, 1); }
+
+hipError_t launch_conv_igemm_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev) {
+  if (n < 1 || n > kMaxBatch) return hipErrorInvalidValue;
+  ConvParams ps[kMaxBatch];
+  const int m = group_of(Ls, n, ps);
+  if (m == 0) return hipSuccess;
+  return Ls[0].dtype == LOP_BF16 ? launch_typed<__bf16>(ps, m, Ls[0].dtype, (float*)Ls[0].ws, stream, ev)
+                                 : launch_typed<float>(ps, m, Ls[0].dtype, (float*)Ls[0].ws, stream, ev);
 }
 
 hipError_t launch_conv_igemm(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
-  ConvParams p = make_params(L);
-  if (p.M <= 0) return hipSuccess;
-  return L.dtype == LOP_BF16 ? launch_typed<__bf16>(p, L.dtype, (float*)L.ws, stream, ev)
-                             : launch_typed<float>(p, L.dtype, (float*)L.ws, stream, ev);
+  return launch_conv_igemm_bands(&L, 1, stream, ev);
 }
 
 // Name of the kernel instance as a profiler prints it, and the number of K slices.
-int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
-  const ConvParams p = make_params(L);
+int conv_igemm_describe_bands(const OpLaunch* Ls, int n, char* name, size_t size) {
+  ConvParams ps[kMaxBatch];
+  const int m = n >= 1 && n <= kMaxBatch ? group_of(Ls, n, ps) : 0;
+  if (m == 0) {
+    if (name && size) name[0] = 0;
+    return 0;
+  }
+  const OpLaunch& L = Ls[0];
+  const ConvParams p = group_params(ps, m);
+  const char* const form = m > 1 ? "_bands" : "";
   const bool bf = L.dtype == LOP_BF16;
   const bool vec = p.C_in % (bf ? 8 : 4) == 0;
   const Choice c = choose(p, L.dtype);
@@ -1558,22 +1699,31 @@ int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);
   if (const LdsChoice ld = lds_applies(p, L.dtype, c, d); ld.bm) {
     if (name && size)
-      snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, false, %d>", bf ? "__bf16" : "float", ld.bm, ld.bn,
+      snprintf(name, size, "conv_lds_kernel%s<%s, %d, %d, %d, false, %d>", form, bf ? "__bf16" : "float", ld.bm, ld.bn,
                bf ? kLdsStagesBf16 : kLdsStagesF32, p.C_in * (bf ? 2 : 4) == 64 ? 2 : 1);
     return 1;
   }
   if (d.wk) {
     if (name && size) {
-      if (d.narrow) snprintf(name, size, "conv_narrow_kernel<%s>", bf ? "__bf16" : "float");
-      else snprintf(name, size, "conv_direct_kernel<%s, %d, %d>", bf ? "__bf16" : "float", d.wk, d.nt);
+      if (d.narrow) snprintf(name, size, "conv_narrow_kernel%s<%s>", form, bf ? "__bf16" : "float");
+      else snprintf(name, size, "conv_direct_kernel%s<%s, %d, %d>", form, bf ? "__bf16" : "float", d.wk, d.nt);
     }
     return d.z;
   }
   if (name && size)
-    snprintf(name, size, "conv_igemm_kernel<%s, %d, %d, %d, %d, %d, %d, %s>", bf ? "__bf16" : "float",
+    snprintf(name, size, "conv_igemm_kernel%s<%s, %d, %d, %d, %d, %d, %d, %s>", form, bf ? "__bf16" : "float",
              c.bm, c.bn, wm[c.shape], wn[c.shape], c.shape == S256x256 ? kBigBKB : kBKB, kStages,
              vec ? "true" : "false");
   return c.splits;
+}
+
+int conv_igemm_describe(const OpLaunch& L, char* name, size_t size) {
+  if (make_params(L).M <= 0) {   // (a band that computes nothing of the layer still names its kernel)
+    OpLaunch one = L;
+    one.out_hi = one.out_lo + 1;
+    return conv_igemm_describe_bands(&one, 1, name, size);
+  }
+  return conv_igemm_describe_bands(&L, 1, name, size);
 }
 
 // ---- convolution + the 2 x 2 stride-2 max pooling behind it as one launch (conv_lds_kernel<..., true>)
@@ -1623,30 +1773,56 @@ bool convpool_pays(const OpLaunch& conv) {
   return !(d.wk && d.narrow);
 }
 
-hipError_t launch_convpool(const OpLaunch& conv, const OpLaunch& pool, hipStream_t stream, KernelEvents* ev) {
-  const ConvParams p = make_pooled_params(conv, pool);
-  if (p.M <= 0) return hipSuccess;
-  if (!convpool_applies(conv, pool)) return hipErrorInvalidValue;
-  const int esz = conv.dtype == LOP_BF16 ? 2 : 4;
-  // 32-bit signed byte offsets into the input slab
-  if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return hipErrorInvalidValue;
-  const LdsChoice ld = choose_pooled(p, conv.dtype);
-  if (conv.dtype == LOP_BF16) {
-    if (ld.bm == 32 && ld.bn == 32) return launch_lds<__bf16, 32, 32, kLdsStagesBf16>(p, stream, ev);
-    if (ld.bn == 32) return launch_lds<__bf16, 64, 32, kLdsStagesBf16>(p, stream, ev);
-    if (ld.bm == 64) return launch_lds<__bf16, 64, 64, kLdsStagesBf16>(p, stream, ev);
-    return launch_lds<__bf16, 32, 64, kLdsStagesBf16>(p, stream, ev);
+hipError_t launch_convpool_bands(const OpLaunch* convs, const OpLaunch* pools, int n, hipStream_t stream,
+                                 KernelEvents* ev) {
+  if (n < 1 || n > kMaxBatch) return hipErrorInvalidValue;
+  ConvParams ps[kMaxBatch];
+  int m = 0;
+  const int esz = convs[0].dtype == LOP_BF16 ? 2 : 4;
+  for (int b = 0; b < n; ++b) {
+    const ConvParams p = make_pooled_params(convs[b], pools[b]);
+    if (p.M <= 0) continue;
+    if (!convpool_applies(convs[b], pools[b])) return hipErrorInvalidValue;
+    // 32-bit signed byte offsets into the input slab
+    if ((size_t)p.N * p.x_rows * p.W * p.C_in * esz >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    ps[m++] = p;
   }
-  return launch_lds<float, 32, 32, kLdsStagesF32>(p, stream, ev);
+  if (m == 0) return hipSuccess;
+  const LdsChoice ld = choose_pooled(group_params(ps, m), convs[0].dtype);
+  if (convs[0].dtype == LOP_BF16) {
+    if (ld.bm == 32 && ld.bn == 32) return launch_lds<__bf16, 32, 32, kLdsStagesBf16>(ps, m, stream, ev);
+    if (ld.bn == 32) return launch_lds<__bf16, 64, 32, kLdsStagesBf16>(ps, m, stream, ev);
+    if (ld.bm == 64) return launch_lds<__bf16, 64, 64, kLdsStagesBf16>(ps, m, stream, ev);
+    return launch_lds<__bf16, 32, 64, kLdsStagesBf16>(ps, m, stream, ev);
+  }
+  return launch_lds<float, 32, 32, kLdsStagesF32>(ps, m, stream, ev);
+}
+
+hipError_t launch_convpool(const OpLaunch& conv, const OpLaunch& pool, hipStream_t stream, KernelEvents* ev) {
+  return launch_convpool_bands(&conv, &pool, 1, stream, ev);
+}
+
+int convpool_describe_bands(const OpLaunch* convs, const OpLaunch* pools, int n, char* name, size_t size) {
+  ConvParams ps[kMaxBatch];
+  int m = 0;
+  for (int b = 0; b < n && m < kMaxBatch; ++b) {
+    const ConvParams p = make_pooled_params(convs[b], pools[b]);
+    if (p.M > 0) ps[m++] = p;
+  }
+  if (m == 0) {
+    if (name && size) name[0] = 0;
+    return 0;
+  }
+  const LdsChoice ld = choose_pooled(group_params(ps, m), convs[0].dtype);
+  const bool bf = convs[0].dtype == LOP_BF16;
+  if (name && size)
+    snprintf(name, size, "conv_lds_kernel%s<%s, %d, %d, %d, true, 1>", m > 1 ? "_bands" : "", bf ? "__bf16" : "float",
+             ld.bm, ld.bn, bf ? kLdsStagesBf16 : kLdsStagesF32);
+  return 1;
 }
 
 int convpool_describe(const OpLaunch& conv, const OpLaunch& pool, char* name, size_t size) {
-  const ConvParams p = make_pooled_params(conv, pool);
-  const LdsChoice ld = choose_pooled(p, conv.dtype);
-  const bool bf = conv.dtype == LOP_BF16;
-  if (name && size)
-    snprintf(name, size, "conv_lds_kernel<%s, %d, %d, %d, true, 1>", bf ? "__bf16" : "float", ld.bm, ld.bn, bf ? kLdsStagesBf16 : kLdsStagesF32);
-  return 1;
+  return convpool_describe_bands(&conv, &pool, 1, name, size);
 }
 
 }  // namespace lop

@@ -59,12 +59,12 @@ __device__ __forceinline__ void store4(__bf16* y, const float* v) {
 }
 
 template <typename T, int KJ>
-__global__ __launch_bounds__(256) void conv_stem_kernel(const StemParams p) {
+__device__ __forceinline__ void conv_stem_kernel_body(const StemParams& p, const int bx) {
   __shared__ float patch[kStemPatchMax];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int xt = blockIdx.x % p.tiles_x;
-  const int t = blockIdx.x / p.tiles_x;
+  const int xt = bx % p.tiles_x;
+  const int t = bx / p.tiles_x;
   const int r = t % p.R, n = t / p.R;
   const int oy = p.out_lo + r, ox0 = xt * kStemPixels;
 
@@ -133,6 +133,17 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(const StemParams p) {
   if (p.y2) store4((T*)p.y2 + off, v);
 }
 
+template <typename T, int KJ>
+__global__ __launch_bounds__(256) void conv_stem_kernel(const StemParams p) {
+  conv_stem_kernel_body<T, KJ>(p, blockIdx.x);
+}
+// The same for several bands of the layer in one grid (band b owns blocks first[b] .. first[b + 1]).
+template <typename T, int KJ>
+__global__ __launch_bounds__(256) void conv_stem_kernel_bands(const Batch<StemParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  conv_stem_kernel_body<T, KJ>(t.p[b], blockIdx.x - t.first[b]);
+}
+
 StemParams make_stem_params(const OpLaunch& L) {
   StemParams p;
   p.x = L.x.ptr; p.y = L.y.ptr; p.y2 = L.y2; p.wq = (const float*)L.wstem; p.bias = L.bias;
@@ -165,25 +176,40 @@ bool stem_applies(const OpLaunch& L) {
          stem_shape_applies(L.x.c, L.y.c, L.kh, L.kw, L.sw, L.dh, L.dw, L.res.ptr != nullptr);
 }
 
-hipError_t launch_stem(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
-  if (!stem_applies(L)) return hipErrorInvalidValue;
-  const StemParams p = make_stem_params(L);
-  if (p.R <= 0 || p.N <= 0) return hipSuccess;
-  // the staged patch must fit, and the grid's x extent
-  if (p.kh * p.patch_w > kStemPatchMax || p.patch_w > kStemRowChunks * 256) return hipErrorInvalidValue;
-  if ((size_t)p.x_rows * p.W * p.C_in == 0) return hipErrorInvalidValue;  // (padding taps load element 0)
-  const long tiles = (long)p.N * p.R * p.tiles_x;
-  if (tiles > 0x7fffffffL) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)tiles, (unsigned)(p.C_out / kStemChannels));
-  const int kj = stem_kj(L);
-  if (L.dtype == LOP_BF16) {
-    if (kj == 9) return launch_kernel(conv_stem_kernel<__bf16, 9>, grid, dim3(256), stream, ev, p);
-    if (kj == 21) return launch_kernel(conv_stem_kernel<__bf16, 21>, grid, dim3(256), stream, ev, p);
-    return launch_kernel(conv_stem_kernel<__bf16, 0>, grid, dim3(256), stream, ev, p);
+hipError_t launch_stem_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev) {
+  if (n < 1 || n > kMaxBatch) return hipErrorInvalidValue;
+  StemParams ps[kMaxBatch];
+  unsigned gx[kMaxBatch];
+  int m = 0;
+  for (int b = 0; b < n; ++b) {
+    if (!stem_applies(Ls[b])) return hipErrorInvalidValue;
+    const StemParams p = make_stem_params(Ls[b]);
+    if (p.R <= 0 || p.N <= 0) continue;
+    // the staged patch must fit, and the grid's x extent
+    if (p.kh * p.patch_w > kStemPatchMax || p.patch_w > kStemRowChunks * 256) return hipErrorInvalidValue;
+    if ((size_t)p.x_rows * p.W * p.C_in == 0) return hipErrorInvalidValue;  // (padding taps load element 0)
+    const long tiles = (long)p.N * p.R * p.tiles_x;
+    if (tiles > 0x7fffffffL) return hipErrorInvalidValue;
+    ps[m] = p;
+    gx[m++] = (unsigned)tiles;
   }
-  if (kj == 9) return launch_kernel(conv_stem_kernel<float, 9>, grid, dim3(256), stream, ev, p);
-  if (kj == 21) return launch_kernel(conv_stem_kernel<float, 21>, grid, dim3(256), stream, ev, p);
-  return launch_kernel(conv_stem_kernel<float, 0>, grid, dim3(256), stream, ev, p);
+  if (m == 0) return hipSuccess;
+  const OpLaunch& L = Ls[0];
+  const unsigned gy = (unsigned)(ps[0].C_out / kStemChannels);
+  const int kj = stem_kj(L);
+  const dim3 block(256);
+  if (L.dtype == LOP_BF16) {
+    if (kj == 9) return launch_group(conv_stem_kernel<__bf16, 9>, conv_stem_kernel_bands<__bf16, 9>, ps, m, gx, gy, 1, block, stream, ev);
+    if (kj == 21) return launch_group(conv_stem_kernel<__bf16, 21>, conv_stem_kernel_bands<__bf16, 21>, ps, m, gx, gy, 1, block, stream, ev);
+    return launch_group(conv_stem_kernel<__bf16, 0>, conv_stem_kernel_bands<__bf16, 0>, ps, m, gx, gy, 1, block, stream, ev);
+  }
+  if (kj == 9) return launch_group(conv_stem_kernel<float, 9>, conv_stem_kernel_bands<float, 9>, ps, m, gx, gy, 1, block, stream, ev);
+  if (kj == 21) return launch_group(conv_stem_kernel<float, 21>, conv_stem_kernel_bands<float, 21>, ps, m, gx, gy, 1, block, stream, ev);
+  return launch_group(conv_stem_kernel<float, 0>, conv_stem_kernel_bands<float, 0>, ps, m, gx, gy, 1, block, stream, ev);
+}
+
+hipError_t launch_stem(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
+  return launch_stem_bands(&L, 1, stream, ev);
 }
 
 int stem_describe(const OpLaunch& L, char* name, size_t size) {

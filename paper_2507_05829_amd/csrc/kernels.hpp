@@ -70,6 +70,18 @@ struct KernelEvents {
 
 // Enqueue the kernel(s) for one operator on `stream`; `ev` (optional) times them.
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev = nullptr);
+// The same operator on several bands of one layer as one launch (the operation batching of
+// Sec. IV-D): n descriptors that differ in slabs and rows only; bands that compute nothing are
+// skipped. op_batchable: whether the operator's kernel has such a form (the 1x1 streaming kernel
+// and the register-blocked depthwise kernel take one band at a time).
+constexpr int kMaxBandsPerLaunch = 16;
+bool op_batchable(const OpLaunch& L);
+hipError_t launch_op_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev = nullptr);
+int describe_op_bands(const OpLaunch* Ls, int n, char* name, size_t size);
+size_t conv_workspace_bytes_bands(const OpLaunch* Ls, int n);
+hipError_t launch_convpool_bands(const OpLaunch* convs, const OpLaunch* pools, int n, hipStream_t stream,
+                                 KernelEvents* ev = nullptr);
+int convpool_describe_bands(const OpLaunch* convs, const OpLaunch* pools, int n, char* name, size_t size);
 // Whether launch_op's kernel for this operator honours OpLaunch::y2.
 bool stores_second_output(const OpLaunch& L);
 // The first-layer kernel (very few input channels, a short reduction axis, vector ALUs):

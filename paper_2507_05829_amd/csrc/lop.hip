@@ -7,6 +7,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <string>
 #include <utility>
 #include <vector>
 
@@ -31,6 +32,11 @@ hipError_t launch_mbconv(const OpLaunch& e, const OpLaunch& d, const OpLaunch& p
 int pointwise_describe(const OpLaunch& L, char* name, size_t size);
 int conv_igemm_describe(const OpLaunch& L, char* name, size_t size);
 int rowwise_describe(const OpLaunch& L, char* name, size_t size);
+hipError_t launch_conv_igemm_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev);
+int conv_igemm_describe_bands(const OpLaunch* Ls, int n, char* name, size_t size);
+hipError_t launch_rowwise_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev);
+bool rowwise_batchable(const OpLaunch& L);
+hipError_t launch_stem_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev);
 
 hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
   if (L.out_hi <= L.out_lo) return hipSuccess;
@@ -43,6 +49,34 @@ hipError_t launch_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
 
 bool stores_second_output(const OpLaunch& L) {
   return L.op != LOP_CONV2D || stem_applies(L) || !pointwise_applies(L);
+}
+
+bool op_batchable(const OpLaunch& L) {
+  if (L.op == LOP_CONV2D) return stem_applies(L) || !pointwise_applies(L);
+  return rowwise_batchable(L);
+}
+
+hipError_t launch_op_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev) {
+  if (n < 1 || n > kMaxBandsPerLaunch) return hipErrorInvalidValue;
+  if (n == 1) return launch_op(Ls[0], stream, ev);
+  if (!op_batchable(Ls[0])) return hipErrorInvalidValue;
+  if (Ls[0].op == LOP_CONV2D)
+    return stem_applies(Ls[0]) ? launch_stem_bands(Ls, n, stream, ev) : launch_conv_igemm_bands(Ls, n, stream, ev);
+  return launch_rowwise_bands(Ls, n, stream, ev);
+}
+
+int describe_op_bands(const OpLaunch* Ls, int n, char* name, size_t size) {
+  if (n == 1 || Ls[0].op != LOP_CONV2D || stem_applies(Ls[0])) {
+    const int k = describe_op(Ls[0], name, size);
+    if (n > 1 && name && size) {   // the form that takes several bands carries _bands in its name
+      std::string s(name);
+      const size_t at = s.find('<');
+      s.insert(at == std::string::npos ? s.size() : at, "_bands");
+      snprintf(name, size, "%s", s.c_str());
+    }
+    return k;
+  }
+  return conv_igemm_describe_bands(Ls, n, name, size);
 }
 
 int describe_op(const OpLaunch& L, char* name, size_t size) {
@@ -223,8 +257,10 @@ void size_scratch(lop_plan_t* P) {
     }
     worst = off;
   } else {
+    size_t base = 0;
     for (int b = 0; b < t.n_bands; ++b) {
-      size_t off = 0;
+      // (with batched launches all bands' slabs are live at once: one band's follow the other's)
+      size_t off = P->batched ? base : 0;
       for (int l = 0; l + 1 < nl; ++l) {  // the last layer writes the caller's output
         const lop_rows_t r = t.bands[b].need[l + 1];
         P->slab_off[b][l] = off;
@@ -232,6 +268,7 @@ void size_scratch(lop_plan_t* P) {
           off += align_up((size_t)t.in.n * (r.hi - r.lo) * t.row_elems(l) * t.esz(), 256);
       }
       worst = off > worst ? off : worst;
+      base = off;
     }
   }
   P->arena_bytes = worst;
@@ -252,6 +289,32 @@ void size_workspace(lop_plan_t* P) {
       const size_t need = lop::pointwise_applies(o) ? 0 : lop::conv_workspace_bytes(o);
       P->conv_ws_bytes = std::max(need, P->conv_ws_bytes);
     }
+  if (P->batched)   // a layer's launch for all bands keeps every band's partial sums at once
+    for (int l = 0; l < P->t.n_layers(); ++l) {
+      if (P->t.layers[l].d.op != LOP_CONV2D || P->fused_away[l] || P->fuse_head[l] >= 0) continue;
+      std::vector<lop::OpLaunch> group;
+      for (int b = 0; b < P->t.n_bands; ++b) {
+        const lop_rows_t rr = P->t.bands[b].compute[l];
+        if (rr.hi > rr.lo) group.push_back(make_launch(P, b, l, nullptr, nullptr));
+      }
+      if (group.empty() || lop::pointwise_applies(group[0])) continue;
+      P->conv_ws_bytes = std::max(lop::conv_workspace_bytes_bands(group.data(), (int)group.size()), P->conv_ws_bytes);
+    }
+}
+
+// Whether every launch of the plan has a kernel form that takes several bands.
+bool all_launches_batchable(const lop_plan_t* P) {
+  const lop::Tables& t = P->t;
+  if (t.n_bands > lop::kMaxBandsPerLaunch) return false;
+  for (int l = 0; l < t.n_layers(); ++l) {
+    if (P->fused_away[l]) continue;
+    if (P->fuse_head[l] >= 0) {
+      if (P->fuse_head[l] != l - 1) return false;   // an inverted-residual block
+      continue;
+    }
+    if (!lop::op_batchable(lop::describe_layer(P, l))) return false;
+  }
+  return true;
 }
 
 lop::Slab slab_of(const lop_plan_t* P, int band, int tensor, const void* d_in, void* d_out) {
@@ -620,7 +683,7 @@ int setup_device(lop_plan_t* P) {
   for (int b = 0; b < nb; ++b) live += band_empty(P, b) ? 0 : 1;
   int want = (int)((P->flags >> 8) & 0xff);
   if (want == 0) want = LOP_DEFAULT_LANES;
-  const int n_lanes = P->t.reuse ? std::max(1, want) : std::max(1, std::min(want, live));
+  const int n_lanes = P->t.reuse || P->batched ? std::max(1, want) : std::max(1, std::min(want, live));
   P->lanes.assign(n_lanes, Lane{});
   // Long band copies (stores into host memory, paced by the link) get a lane of their own.
   // On a compute lane a copy holds up that lane's next band, and because the bands are equal
@@ -641,7 +704,7 @@ int setup_device(lop_plan_t* P) {
   // output per call: 215 calls/s with the copy lane, 350 with copies on every lane, which
   // together reach the link's rate). The plan does not know the kernels' time; the bound on the
   // bytes stands for it.
-  P->copy_lane = !P->t.reuse && n_lanes >= 3 && longest_copy > kDirectHostStoreMax &&
+  P->copy_lane = !P->t.reuse && !P->batched && n_lanes >= 3 && longest_copy > kDirectHostStoreMax &&
                  all_copies <= kCopyLaneMaxBytes &&
                  !(P->flags & (LOP_FLAG_NO_D2H | LOP_FLAG_DMA_COPY));
   for (Lane& L : P->lanes) {
@@ -760,6 +823,109 @@ int enqueue_chain_reuse(lop_plan_t* P, const void* d_in, void* d_out, void* h_ou
   return LOP_OK;
 }
 
+// The descriptors of layer l's launch for all bands (convs: the conv of a conv + pooling group,
+// else empty). y2 of band b is its direct host target when h_out is given (last layer only).
+void batched_group(lop_plan_t* P, int l, const void* d_in, void* d_out, void* h_out,
+                   std::vector<lop::OpLaunch>* group, std::vector<lop::OpLaunch>* convs,
+                   std::vector<char>* direct) {
+  group->clear();
+  convs->clear();
+  for (int b = 0; b < P->t.n_bands; ++b) {
+    const lop_rows_t r = launch_rows(P, b, l);
+    if (r.hi <= r.lo) continue;
+    lop::OpLaunch o = make_launch(P, b, l, d_in, d_out);
+    if (h_out) {
+      o.y2 = direct_host_target(P, b, h_out);
+      if (direct) (*direct)[b] = o.y2 != nullptr;
+    }
+    if (ends_convpool(P, l)) {
+      lop::OpLaunch conv, pool;
+      convpool_launches(P, b, l, d_in, d_out, &conv, &pool);
+      pool.y2 = o.y2;
+      convs->push_back(conv);
+      group->push_back(pool);
+    } else {
+      group->push_back(o);
+    }
+  }
+}
+
+// One launch (plus its finish kernel, if the reduction is cut) for layer l of every band.
+hipError_t launch_layer_batched(lop_plan_t* P, int l, const void* d_in, void* d_out, hipStream_t cs,
+                                lop::KernelEvents* ev, void* h_out, std::vector<char>* direct) {
+  if (P->fused_away[l]) return hipSuccess;
+  std::vector<lop::OpLaunch> group, convs;
+  batched_group(P, l, d_in, d_out, h_out, &group, &convs, direct);
+  if (group.empty()) return hipSuccess;
+  if (ends_convpool(P, l)) return lop::launch_convpool_bands(convs.data(), group.data(), (int)group.size(), cs, ev);
+  return lop::launch_op_bands(group.data(), (int)group.size(), cs, ev);
+}
+
+// Kernel name and reduction slices of that launch.
+int describe_layer_batched(const lop_plan_t* P, int l, char* name, size_t size) {
+  if (P->fused_away[l]) return 0;
+  std::vector<lop::OpLaunch> group, convs;
+  batched_group(const_cast<lop_plan_t*>(P), l, nullptr, nullptr, nullptr, &group, &convs, nullptr);
+  if (group.empty()) return 0;
+  if (ends_convpool(P, l)) return lop::convpool_describe_bands(convs.data(), group.data(), (int)group.size(), name, size);
+  return lop::describe_op_bands(group.data(), (int)group.size(), name, size);
+}
+
+// The band a batched plan's launch of layer l is attributed to in per-band queries: the first
+// band that computes rows of it (-1: nobody does).
+int batched_owner(const lop_plan_t* P, int l) {
+  for (int b = 0; b < P->t.n_bands; ++b) {
+    const lop_rows_t r = launch_rows(P, b, l);
+    if (r.hi > r.lo) return b;
+  }
+  return -1;
+}
+
+// A chain whose launches are batched over the bands (Sec. IV-D operation batching), on one
+// lane: per layer one launch that computes every band's rows on that band's slabs, then the
+// bands' rows to the host (through the last launch's own stores where a band is small enough,
+// else by copies behind it).
+int enqueue_chain_batched(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, bool timing,
+                          bool capturing) {
+  Lane& L = P->lanes[P->cur_lane];
+  hipStream_t cs = L.stream;
+  const int nb = P->t.n_bands, nl = P->t.n_layers();
+  const bool copy = h_out && !(P->flags & LOP_FLAG_NO_D2H);
+  if (!capturing)
+    for (int b = 0; b < nb; ++b)
+      if (P->copied_valid[b]) {  // these rows of d_out may still be on their way to the host
+        LOP_HIP(hipStreamWaitEvent(cs, P->ev_copied[b], 0));
+        P->copied_valid[b] = 0;
+      }
+  if (P->flags & LOP_FLAG_POISON_SCRATCH) {
+    LOP_HIP(lop::launch_fill_words(P->arena_of(0), align_up(P->arena_bytes, 256), 0xFFFFFFFFu, cs));
+    LOP_HIP(lop::launch_fill_words(P->ws_of(0), P->conv_ws_bytes / 16 * 16, 0xFFFFFFFFu, cs));
+  }
+  if (timing)
+    for (int b = 0; b < nb; ++b)
+      if (!band_empty(P, b)) LOP_HIP(hipEventRecord(P->ev_c0[b], cs));
+  std::vector<char> direct(nb, 0);
+  for (int l = 0; l < nl; ++l)
+    LOP_HIP(launch_layer_batched(P, l, d_in, d_out, cs, nullptr, l == nl - 1 && copy ? h_out : nullptr, &direct));
+  for (int b = 0; b < nb; ++b) {
+    if (band_empty(P, b)) continue;
+    if (timing) {
+      LOP_HIP(hipEventRecord(P->ev_c1[b], cs));
+      LOP_HIP(hipEventRecord(P->ev_d0[b], cs));
+    }
+    if (copy && !direct[b]) {
+      int rc = enqueue_band_copy(P, b, d_out, h_out, cs);
+      if (rc != LOP_OK) return rc;
+    }
+    if (timing) LOP_HIP(hipEventRecord(P->ev_d1[b], cs));
+    if (copy && !capturing) {
+      LOP_HIP(hipEventRecord(P->ev_copied[b], cs));
+      P->copied_valid[b] = 1;
+    }
+  }
+  return LOP_OK;
+}
+
 // The bands of lane `lane` of an independent-mode chain, in order, on that lane's stream.
 int enqueue_lane(lop_plan_t* P, int lane, const void* d_in, void* d_out, void* h_out, bool capturing) {
   hipStream_t cs = P->lanes[lane].stream;
@@ -777,7 +943,7 @@ int enqueue_lane(lop_plan_t* P, int lane, const void* d_in, void* d_out, void* h
 // caller's business).
 int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipStream_t ms,
                  int lane_only = -1, int band_only = -1) {
-  const int lane = P->t.reuse ? P->cur_lane : (lane_only >= 0 ? lane_only : -1);
+  const int lane = P->t.reuse || P->batched ? P->cur_lane : (lane_only >= 0 ? lane_only : -1);
   // an eager run may still have copies of the output rows in flight (on a copy stream that the
   // graph's stream is not ordered behind): a replay, and the first capture, wait for them
   for (int b = 0; b < P->t.n_bands; ++b)
@@ -795,6 +961,7 @@ int launch_graph(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, hipS
   hipGraph_t graph = nullptr;
   LOP_HIP(hipStreamBeginCapture(ms, hipStreamCaptureModeThreadLocal));
   int rc = band_only >= 0 ? enqueue_band_kernels(P, band_only, d_in, d_out, ms)
+           : P->batched  ? enqueue_chain_batched(P, d_in, d_out, h_out, false, true)
            : P->t.reuse  ? enqueue_chain_reuse(P, d_in, d_out, h_out, false, true)
            : lane_only >= 0 ? enqueue_lane(P, lane_only, d_in, d_out, h_out, true)
                             : enqueue_chain(P, d_in, d_out, h_out, ms, false, true);
@@ -870,6 +1037,11 @@ int lop_plan(const lop_layer_t* layers, int n_layers, const lop_tensor_desc_t* i
                                               d.residual_from != LOP_NO_RESIDUAL);
   }
   find_fused_groups(P);
+  if (flags & LOP_FLAG_BATCH_BANDS) {
+    if (flags & LOP_FLAG_REUSE) { delete P; return LOP_ERR_INVALID_ARG; }
+    if (!all_launches_batchable(P)) { delete P; return LOP_ERR_UNSUPPORTED; }
+    P->batched = true;
+  }
   size_scratch(P);
   size_workspace(P);
   if (!(flags & LOP_FLAG_PLAN_ONLY)) {
@@ -1060,7 +1232,7 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
     }
     return LOP_OK;
   }
-  if (P->t.reuse) {
+  if (P->t.reuse || P->batched) {
     // the whole chain runs on one lane; chains of consecutive calls rotate over the lanes
     // and overlap unless the caller's stream orders them
     P->cur_lane = P->next_lane;
@@ -1073,7 +1245,8 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
     if (timing) LOP_HIP(hipEventRecord(P->ev_t0, L.stream));
     int rc = ((P->flags & LOP_FLAG_GRAPH) && !timing)
                  ? launch_graph(P, d_in, d_out, h_out, L.stream)
-                 : enqueue_chain_reuse(P, d_in, d_out, h_out, timing != nullptr, false);
+                 : P->batched ? enqueue_chain_batched(P, d_in, d_out, h_out, timing != nullptr, false)
+                              : enqueue_chain_reuse(P, d_in, d_out, h_out, timing != nullptr, false);
     if (rc != LOP_OK) return rc;
     if (timing) LOP_HIP(hipEventRecord(P->ev_t1, L.stream));
     if (compute_stream) {
@@ -1185,7 +1358,12 @@ int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, 
   int slices = 0;
   // (a plan-only plan has uploaded no weights, and which kernel takes a layer depends on the
   // packings that exist: it names none rather than a kernel the ready plan would not launch)
-  if (!(P->flags & LOP_FLAG_PLAN_ONLY)) slices = describe_layer_launch(P, band, layer, name, size);
+  if (P->flags & LOP_FLAG_PLAN_ONLY) {
+  } else if (P->batched) {   // one launch per layer for all bands: named at the first band that takes part
+    if (batched_owner(P, layer) == band) slices = describe_layer_batched(P, layer, name, size);
+  } else {
+    slices = describe_layer_launch(P, band, layer, name, size);
+  }
   if (k_slices) *k_slices = slices;
   return LOP_OK;
 }
@@ -1213,11 +1391,13 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
         for (int l = 0; l < nl; ++l) {
           const lop_rows_t r = launch_rows(P, b, l);
           if (r.hi <= r.lo) continue;
+          if (P->batched && batched_owner(P, l) != b) continue;  // (timed with the band that owns the launch)
           const size_t i = ((size_t)b * nl + l) * 4;
           lop::KernelEvents ke;
           ke.start[0] = ev[i]; ke.stop[0] = ev[i + 1];
           ke.start[1] = ev[i + 2]; ke.stop[1] = ev[i + 3];
-          LOP_HIP(launch_layer(P, b, l, d_in, d_out, cs, &ke));
+          if (P->batched) LOP_HIP(launch_layer_batched(P, l, d_in, d_out, cs, &ke, nullptr, nullptr));
+          else LOP_HIP(launch_layer(P, b, l, d_in, d_out, cs, &ke));
           used[b * nl + l] = ke.n;
         }
       LOP_HIP(hipStreamSynchronize(cs));

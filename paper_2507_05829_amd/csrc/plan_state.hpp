@@ -80,7 +80,8 @@ struct lop_plan_s {
   int n_lanes() const { return (int)lanes.size() - (copy_lane ? 1 : 0); }  // lanes that compute
   // Independent bands are dealt to the lanes round robin; in reuse mode a whole chain (all
   // bands, in order) runs on one lane and consecutive chains rotate over the lanes.
-  int lane_index(int band) const { return t.reuse ? cur_lane : band % n_lanes(); }
+  bool batched = false;  // LOP_FLAG_BATCH_BANDS: one launch per layer for all bands, a chain per lane
+  int lane_index(int band) const { return t.reuse || batched ? cur_lane : band % n_lanes(); }
   Lane& lane_of(int band) { return lanes[lane_index(band)]; }
   const Lane& lane_of(int band) const { return lanes[lane_index(band)]; }
   // While lop_run_chain_static enqueues, scratch comes from the library's static device array

@@ -97,8 +97,8 @@ __device__ __forceinline__ void load_f32(const float* p, float* v) {
 
 // OP: 0 depthwise conv, 1 max pool, 2 element-wise
 template <typename T, int VEC, int OP>
-__global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void rowwise_kernel_body(const RowParams& p, const int bx) {
+  const long gid = (long)bx * 256 + threadIdx.x;
   if (gid >= p.total) return;
   const int cv = p.C / VEC;
   const int c = (int)(gid % cv) * VEC;
@@ -155,6 +155,17 @@ __global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
   const size_t yo = ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C + c;
   Vec<T, VEC>::store((T*)p.y + yo, acc);
   if (p.y2) Vec<T, VEC>::store((T*)p.y2 + yo, acc);
+}
+
+template <typename T, int VEC, int OP>
+__global__ __launch_bounds__(256) void rowwise_kernel(const RowParams p) {
+  rowwise_kernel_body<T, VEC, OP>(p, blockIdx.x);
+}
+// The same for several bands of one layer in one grid (band b owns blocks first[b] .. first[b + 1]).
+template <typename T, int VEC, int OP>
+__global__ __launch_bounds__(256) void rowwise_kernel_bands(const Batch<RowParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  rowwise_kernel_body<T, VEC, OP>(t.p[b], blockIdx.x - t.first[b]);
 }
 
 
@@ -300,20 +311,24 @@ inline int dw3_vec(const RowParams& p, int op, int dtype) {
 }
 
 template <typename T, int VEC>
-hipError_t launch_rowwise(RowParams& p, int op, hipStream_t s, KernelEvents* ev) {
-  p.total = (long)p.N * p.R * p.W_out * (p.C / VEC);
-  if (p.total <= 0) return hipSuccess;
-  const unsigned grid = (unsigned)((p.total + 255) / 256);
+hipError_t launch_rowwise(RowParams* ps, int n, int op, hipStream_t s, KernelEvents* ev) {
+  unsigned gx[kMaxBatch];
+  int m = 0;
+  for (int b = 0; b < n; ++b) {
+    ps[b].total = (long)ps[b].N * ps[b].R * ps[b].W_out * (ps[b].C / VEC);
+    if (ps[b].total <= 0) continue;
+    ps[m] = ps[b];
+    gx[m++] = (unsigned)((ps[b].total + 255) / 256);
+  }
+  if (m == 0) return hipSuccess;
   if (op == LOP_DWCONV2D)
-    return launch_kernel(rowwise_kernel<T, VEC, 0>, dim3(grid), dim3(256), s, ev, p);
+    return launch_group(rowwise_kernel<T, VEC, 0>, rowwise_kernel_bands<T, VEC, 0>, ps, m, gx, 1, 1, dim3(256), s, ev);
   if (op == LOP_MAXPOOL2D)
-    return launch_kernel(rowwise_kernel<T, VEC, 1>, dim3(grid), dim3(256), s, ev, p);
-  return launch_kernel(rowwise_kernel<T, VEC, 2>, dim3(grid), dim3(256), s, ev, p);
+    return launch_group(rowwise_kernel<T, VEC, 1>, rowwise_kernel_bands<T, VEC, 1>, ps, m, gx, 1, 1, dim3(256), s, ev);
+  return launch_group(rowwise_kernel<T, VEC, 2>, rowwise_kernel_bands<T, VEC, 2>, ps, m, gx, 1, 1, dim3(256), s, ev);
 }
 
-}  // namespace
-
-hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
+RowParams make_row_params(const OpLaunch& L) {
   RowParams p;
   p.x = L.x.ptr; p.y = L.y.ptr; p.y2 = L.y2; p.res = L.res.ptr; p.w = (const float*)L.w; p.bias = L.bias;
   p.x_row0 = L.x.row0; p.x_rows = L.x.rows; p.W = L.x.w; p.C = L.x.c;
@@ -322,15 +337,39 @@ hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents
   p.kh = L.kh; p.kw = L.kw; p.sh = L.sh; p.sw = L.sw; p.ph = L.ph; p.pw = L.pw;
   p.dh = L.dh; p.dw = L.dw;
   p.act = L.act; p.out_lo = L.out_lo; p.R = L.out_hi - L.out_lo; p.N = L.x.n;
+  p.total = 0;
+  return p;
+}
+
+}  // namespace
+
+// Whether launch_rowwise_bands has a kernel for this operator (the register-blocked depthwise
+// kernel takes one band at a time).
+bool rowwise_batchable(const OpLaunch& L) {
+  const RowParams p = make_row_params(L);
+  return dw3_vec(p, L.op, L.dtype) == 0;
+}
+
+hipError_t launch_rowwise_bands(const OpLaunch* Ls, int n, hipStream_t stream, KernelEvents* ev) {
+  if (n < 1 || n > kMaxBatch) return hipErrorInvalidValue;
+  RowParams ps[kMaxBatch];
+  for (int b = 0; b < n; ++b) ps[b] = make_row_params(Ls[b]);
+  const OpLaunch& L = Ls[0];
+  RowParams& p = ps[0];
   if (const int v = dw3_vec(p, L.op, L.dtype)) {
+    if (n != 1) return hipErrorInvalidValue;
     if (L.dtype != LOP_BF16) return launch_dw3<float, 4>(p, stream, ev);
     return v == 8 ? launch_dw3<__bf16, 8>(p, stream, ev) : launch_dw3<__bf16, 4>(p, stream, ev);
   }
   if (L.dtype == LOP_BF16)
-    return p.C % 8 == 0 ? launch_rowwise<__bf16, 8>(p, L.op, stream, ev)
-                        : launch_rowwise<__bf16, 1>(p, L.op, stream, ev);
-  return p.C % 4 == 0 ? launch_rowwise<float, 4>(p, L.op, stream, ev)
-                      : launch_rowwise<float, 1>(p, L.op, stream, ev);
+    return p.C % 8 == 0 ? launch_rowwise<__bf16, 8>(ps, n, L.op, stream, ev)
+                        : launch_rowwise<__bf16, 1>(ps, n, L.op, stream, ev);
+  return p.C % 4 == 0 ? launch_rowwise<float, 4>(ps, n, L.op, stream, ev)
+                      : launch_rowwise<float, 1>(ps, n, L.op, stream, ev);
+}
+
+hipError_t launch_rowwise_op(const OpLaunch& L, hipStream_t stream, KernelEvents* ev) {
+  return launch_rowwise_bands(&L, 1, stream, ev);
 }
 
 namespace {

@@ -37,6 +37,7 @@ LOP_FLAG_REUSE = 16
 LOP_FLAG_INDEPENDENT = 0
 LOP_FLAG_NO_FUSE = 32
 LOP_FLAG_POISON_SCRATCH = 64
+LOP_FLAG_BATCH_BANDS = 128
 LOP_LINK_INDEPENDENT, LOP_LINK_QUEUED = 0, 1
 
 

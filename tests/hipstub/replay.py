@@ -89,8 +89,13 @@ def named_workloads():
         t = workloads.make_tensors(chain, zero_bias=False)
         for flags in (0, lop.LOP_FLAG_REUSE, lop.LOP_FLAG_GRAPH, lop.LOP_FLAG_GRAPH | lop.LOP_FLAG_REUSE,
                       lop.LOP_FLAG_DMA_COPY, lop.LOP_FLAG_NO_D2H, lop.LOP_FLAG_NO_FUSE, lop.LOP_FLAG_LANES(1),
-                      lop.LOP_FLAG_LANES(1) | lop.LOP_FLAG_GRAPH, lop.LOP_FLAG_LANES(7) | lop.LOP_FLAG_REUSE):
-            plan = lop.Plan(chain, t, None, flags)
+                      lop.LOP_FLAG_LANES(1) | lop.LOP_FLAG_GRAPH, lop.LOP_FLAG_LANES(7) | lop.LOP_FLAG_REUSE,
+                      lop.LOP_FLAG_BATCH_BANDS, lop.LOP_FLAG_BATCH_BANDS | lop.LOP_FLAG_GRAPH):
+            try:
+                plan = lop.Plan(chain, t, None, flags)
+            except lop.LopError as e:      # chains with an operator whose kernel takes one band at a time
+                assert e.code == lop.LOP_ERR_UNSUPPORTED and flags & lop.LOP_FLAG_BATCH_BANDS
+                continue
             d_in, d_out, h_out = buffers(chain, plan)
             pageable = np.zeros_like(h_out)
             for rep in range(3):                      # graph: capture once, replay twice
@@ -119,7 +124,7 @@ def named_workloads():
                     plan.layer_kernel(b, l)
                     plan.layer_work(b, l)
             plan.stats()
-            if hasattr(lop, "lop_run_chain_static") and not flags & lop.LOP_FLAG_REUSE:
+            if hasattr(lop, "lop_run_chain_static") and not flags & (lop.LOP_FLAG_REUSE | lop.LOP_FLAG_BATCH_BANDS):
                 try:
                     lop.lop_run_chain_static(plan.handle, d_in, d_out, None)
                 except lop.LopError as e:   # layer by layer the large chain needs more than the array holds

@@ -798,6 +798,92 @@ def test_random_chains(oracle, dtype, reuse, base):
         done += 1
 
 
+# ---- launches batched over the bands (Sec. IV-D operation batching) ----
+def _run_batched(chain, t, graph, calls=3):
+    """lop_run_chain `calls` times on the same buffers of a LOP_FLAG_BATCH_BANDS plan; returns
+    (device result, host result, kernel names per layer)."""
+    flags = lop.LOP_FLAG_BATCH_BANDS | (lop.LOP_FLAG_GRAPH if graph else 0)
+    plan = lop.Plan(chain, t, None, flags)
+    try:
+        names = [[plan.layer_kernel(b, l)[0] for b in range(plan.n_bands)] for l in range(plan.n_layers)]
+        d_in = to_device_nhwc(t.x, chain.dtype)
+        d_out = empty_out(plan.out_shape(), chain.dtype)
+        h_out = empty_out(plan.out_shape(), chain.dtype, pinned=True)
+        for _ in range(calls):
+            plan.run_chain(d_in, d_out, h_out)
+        plan.synchronize()
+        check_margins(d_out, h_out)
+        return to_nchw(d_out), to_nchw(h_out), names
+    finally:
+        plan.destroy()
+
+
+@pytest.mark.parametrize("graph", [0, 1])
+@pytest.mark.parametrize("name,kw", [("tiny", dict()), ("resnet18", dict(h=64, w=48)), ("vgg16", dict(h=64, w=64)),
+                                     ("detector720p", dict(h=96, w=64)), ("resnet18", dict()), ("vgg16", dict()),
+                                     ("detector720p", dict())])
+def test_batched_launches(oracle, name, kw, graph):
+    """Independent bands with one launch per layer for all bands: every layer is launched once
+    (named at one band only, by a kernel's several-bands form wherever more than one band
+    computes rows), the result equals the oracle and the per-band schedule's tolerance, on
+    scaled and full-size chains, eagerly and as a replayed graph."""
+    if kw or name == "tiny":
+        chain = workloads.CONFIGS[name](**kw)
+        t = workloads.make_tensors(chain, zero_bias=False)
+        want = oracle.run_chain(chain, t)
+    else:
+        chain, t, want = _full_size_case(oracle, name)
+    dev, host, names = _run_batched(chain, t, graph)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL[chain.dtype]
+    launched = 0
+    for per_band in names:
+        named = [n for n in per_band if n]
+        assert len(named) <= 1, per_band
+        launched += len(named)
+        if named and chain.n_bands > 1 and name != "tiny":
+            assert "_bands" in named[0] or per_band.count("") == len(per_band) - 1
+    assert launched >= 1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_chains_with_batched_launches(oracle, dtype):
+    rng = np.random.Generator(np.random.PCG64(2468 + (dtype == "bf16")))
+    done = unsupported = 0
+    while done < 16:
+        chain = _random_conv_chain(rng, dtype)
+        if chain is None:
+            continue
+        t = workloads.make_tensors(chain, zero_bias=False, seed=int(rng.integers(1, 1 << 30)))
+        desc = [(L.op, L.c_in, L.c_out, L.k, L.s, L.p, L.d, L.act, L.residual_from) for L in chain.layers]
+        try:
+            dev, host, _ = _run_batched(chain, t, graph=done % 2, calls=2)
+        except lop.LopError as e:   # an operator whose kernel takes one band at a time
+            assert e.code == lop.LOP_ERR_UNSUPPORTED, desc
+            unsupported += 1
+            assert unsupported < 200
+            continue
+        want = oracle.run_chain(chain, t)
+        np.testing.assert_array_equal(dev, host, err_msg=str((chain.in_shape, chain.n_bands, desc)))
+        assert rel_err(dev, want) <= TOL[dtype], (chain.in_shape, chain.n_bands, desc)
+        done += 1
+
+
+def test_batched_launches_are_refused_where_a_kernel_takes_one_band():
+    """The inverted-residual block kernel (and, layer by layer, the 3 x 3 depthwise kernel) has
+    no several-bands form; reuse mode and batching exclude each other."""
+    chain = workloads.mbv2_chain(h=48, w=40, n=2)
+    t = workloads.make_tensors(chain)
+    for flags in (lop.LOP_FLAG_BATCH_BANDS, lop.LOP_FLAG_BATCH_BANDS | lop.LOP_FLAG_NO_FUSE):
+        with pytest.raises(lop.LopError) as e:
+            lop.Plan(chain, t, None, flags)
+        assert e.value.code == lop.LOP_ERR_UNSUPPORTED
+    tiny = workloads.tiny_chain()
+    with pytest.raises(lop.LopError) as e:
+        lop.Plan(tiny, workloads.make_tensors(tiny), None, lop.LOP_FLAG_BATCH_BANDS | lop.LOP_FLAG_REUSE)
+    assert e.value.code == lop.LOP_ERR_INVALID_ARG
+
+
 # ---- two parties executing a schedule (Sec. IV-D, Alg. 1 / Alg. 2) ----
 def _heights(chain):
     return [s[2] for s in planner.infer_shapes(chain)]
