@@ -1180,6 +1180,7 @@ __device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f
 
 constexpr int kNarrowWaves = 16;
 constexpr int kLdsStagesBf16 = 4, kLdsStagesF32 = 8;  // stages of 128 bytes per row in LDS per workgroup
+constexpr long kLdsMaxLoopCycles = 25000;  // see lds_applies (40000 and 15000 measured: the fp32 chain gains down to 15000, the bf16 chains lose below 25000)
 constexpr int kLdsMinTiles = 48;   // below this the operand-direct kernels (one round of latency) win; 96 and 20 measured slower
 
 template <typename T>
@@ -1508,7 +1509,17 @@ Choice choose(const ConvParams& p, int dtype) {
 LdsChoice lds_applies(const ConvParams& p, int dtype, const Choice& c, const DirectChoice& d) {
   if (c.shape == S256x256 || (c.splits == 1 && (c.shape == S128x128 || c.shape == S128x64))) return {0, 0, 0};
   if (d.wk && d.narrow) return {0, 0, 0};
-  return choose_lds(p, dtype);
+  const LdsChoice ld = choose_lds(p, dtype);
+  // A workgroup of this kernel walks the whole reduction axis by itself, pulling BM + BN rows of
+  // 128 bytes per stage at what one compute unit gets from the L2s (about 25 bytes per clock). A
+  // layer of few pixels and a long reduction (512 -> 512 channels at 7 x 7) leaves most compute
+  // units idle while the few walk for tens of microseconds: cutting the reduction across
+  // workgroups (the operand-direct kernel and its finish kernel) is faster there.
+  if (ld.bm && ld.tiles < kComputeUnits && d.wk && d.z > 1) {
+    const long stages = (long)p.k_pad * (dtype == LOP_BF16 ? 2 : 4) / 128;
+    if (stages * (ld.bm + ld.bn) * 128 / 25 > kLdsMaxLoopCycles) return {0, 0, 0};
+  }
+  return ld;
 }
 
 template <typename T>
