@@ -518,6 +518,9 @@ def main():
         # image is 1-2 us at the link's rate, which a difference of two timed runs cannot resolve)
         "d2h_hidden": None if head["d2h"]["within_noise"] else head["d2h"]["hidden_vs_link_rate"],
         "d2h_exposed_us_per_chain": head["d2h"]["exposed_us_per_chain"],
+        # the same independent bands with every layer launched once for all bands (operation
+        # batching, Sec. IV-D), and reuse mode: detail under "modes"
+        "images_per_s_by_mode": {m: r["images_per_s"] for m, r in {a.mode: head, **seconds}.items()},
         "measured_ceilings": ceil,
         "modes": {a.mode: head, **seconds},
         "also": also,
