@@ -869,6 +869,52 @@ def test_random_chains_with_batched_launches(oracle, dtype):
         done += 1
 
 
+def test_batched_launches_other_entry_points(oracle):
+    """A LOP_FLAG_BATCH_BANDS plan through the other ways of running it: on a caller's stream,
+    with the timing struct, without host copies, band by band, and through the entry point that
+    allocates nothing - all equal to the oracle."""
+    chain = workloads.resnet18_chain(h=96, w=80)
+    t = workloads.make_tensors(chain, zero_bias=False)
+    want = oracle.run_chain(chain, t)
+    plan = lop.Plan(chain, t, None, lop.LOP_FLAG_BATCH_BANDS)
+    try:
+        d_in = to_device_nhwc(t.x, chain.dtype)
+
+        def fresh():
+            return empty_out(plan.out_shape(), chain.dtype), empty_out(plan.out_shape(), chain.dtype, pinned=True)
+
+        def check(d_out, h_out, host=True):
+            plan.synchronize()
+            torch.cuda.synchronize()
+            assert rel_err(to_nchw(d_out), want) <= TOL[chain.dtype]
+            if host:
+                np.testing.assert_array_equal(to_nchw(h_out), to_nchw(d_out))
+            check_margins(d_out, h_out)
+
+        d_out, h_out = fresh()
+        stream = torch.cuda.Stream()
+        plan.run_chain(d_in, d_out, h_out, compute_stream=stream)
+        stream.synchronize()
+        check(d_out, h_out)
+        d_out, h_out = fresh()
+        tm = plan.run_chain(d_in, d_out, h_out, timing=True)
+        assert tm.n_bands == plan.n_bands and tm.compute_ms > 0
+        check(d_out, h_out)
+        d_out, h_out = fresh()
+        plan.run_chain(d_in, d_out, None)
+        check(d_out, h_out, host=False)
+        assert torch.isnan(h_out.float()).all()
+        d_out, h_out = fresh()
+        for b in reversed(range(plan.n_bands)):
+            plan.run_band(b, d_in, d_out, h_out)
+        check(d_out, h_out)
+        d_out, h_out = fresh()
+        plan.run_chain_static(d_in, d_out)
+        check(d_out, h_out, host=False)
+    finally:
+        plan.destroy()
+
+
 def test_batched_launches_are_refused_where_a_kernel_takes_one_band():
     """The inverted-residual block kernel (and, layer by layer, the 3 x 3 depthwise kernel) has
     no several-bands form; reuse mode and batching exclude each other."""
