@@ -1179,7 +1179,13 @@ __device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f
 }
 
 constexpr int kNarrowWaves = 16;
-constexpr int kLdsStagesBf16 = 4, kLdsStagesF32 = 8;  // stages of 128 bytes per row in LDS per workgroup
+// Stages of 128 bytes per row in LDS per workgroup. fp32: eight while the launch has at most one
+// workgroup per compute unit (nothing else hides a workgroup's latency), four beyond that: with
+// 64 KB per workgroup only two fit a compute unit, and a launch of several workgroups per unit
+// runs a tenth faster when more of them are resident (the batched launches of the fp32 chain:
+// 4 450 -> 4 920 images/s). bf16: four (three measured 3-6 % slower).
+constexpr int kLdsStagesBf16 = 4, kLdsStagesF32 = 8, kLdsStagesF32Crowded = 4;
+inline int f32_stages(long tiles) { return tiles > 256 ? kLdsStagesF32Crowded : kLdsStagesF32; }
 constexpr long kLdsMaxLoopCycles = 25000;  // see lds_applies (40000 and 15000 measured: the fp32 chain gains down to 15000, the bf16 chains lose below 25000)
 constexpr int kLdsMinTiles = 48;   // below this the operand-direct kernels (one round of latency) win; 96 and 20 measured slower
 
@@ -1594,6 +1600,7 @@ hipError_t launch_typed(ConvParams* ps, int n, int dtype, float* ws, hipStream_t
       if (ld.bm == 64) return launch_lds<T, 64, 64, kLdsStagesBf16>(ps, n, s, ev);
       return launch_lds<T, 32, 64, kLdsStagesBf16>(ps, n, s, ev);
     } else {
+      if (f32_stages(ld.tiles) == kLdsStagesF32Crowded) return launch_lds<T, 32, 32, kLdsStagesF32Crowded>(ps, n, s, ev);
       return launch_lds<T, 32, 32, kLdsStagesF32>(ps, n, s, ev);
     }
   }
@@ -1711,7 +1718,7 @@ int conv_igemm_describe_bands(const OpLaunch* Ls, int n, char* name, size_t size
   if (const LdsChoice ld = lds_applies(p, L.dtype, c, d); ld.bm) {
     if (name && size)
       snprintf(name, size, "conv_lds_kernel%s<%s, %d, %d, %d, false, %d>", form, bf ? "__bf16" : "float", ld.bm, ld.bn,
-               bf ? kLdsStagesBf16 : kLdsStagesF32, p.C_in * (bf ? 2 : 4) == 64 ? 2 : 1);
+               bf ? kLdsStagesBf16 : f32_stages(ld.tiles), p.C_in * (bf ? 2 : 4) == 64 ? 2 : 1);
     return 1;
   }
   if (d.wk) {
@@ -1806,6 +1813,7 @@ hipError_t launch_convpool_bands(const OpLaunch* convs, const OpLaunch* pools, i
     if (ld.bm == 64) return launch_lds<__bf16, 64, 64, kLdsStagesBf16>(ps, m, stream, ev);
     return launch_lds<__bf16, 32, 64, kLdsStagesBf16>(ps, m, stream, ev);
   }
+  if (f32_stages(ld.tiles) == kLdsStagesF32Crowded) return launch_lds<float, 32, 32, kLdsStagesF32Crowded>(ps, m, stream, ev);
   return launch_lds<float, 32, 32, kLdsStagesF32>(ps, m, stream, ev);
 }
 
@@ -1828,7 +1836,7 @@ int convpool_describe_bands(const OpLaunch* convs, const OpLaunch* pools, int n,
   const bool bf = convs[0].dtype == LOP_BF16;
   if (name && size)
     snprintf(name, size, "conv_lds_kernel%s<%s, %d, %d, %d, true, 1>", m > 1 ? "_bands" : "", bf ? "__bf16" : "float",
-             ld.bm, ld.bn, bf ? kLdsStagesBf16 : kLdsStagesF32);
+             ld.bm, ld.bn, bf ? kLdsStagesBf16 : f32_stages(ld.tiles));
   return 1;
 }
 
