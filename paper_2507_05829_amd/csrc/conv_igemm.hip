@@ -854,15 +854,19 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
   const unsigned char* __restrict__ wg = (const unsigned char*)p.w;
   const int ns = p.k_pad / SKE;             // stages
 
-  // ---- what this lane fetches: row (lane >> 3) of an 8-row group, chunk (lane & 7) ^ row
+  // ---- what this lane fetches: row (lane >> 3) of an 8-row group, chunk (lane & 7) ^ row ^
+  // (group & 1). A wavefront takes the groups wave, wave + 4, ..., which all have its parity.
+  // (With the row alone as key, rows r and r + 8 of a fragment read share their banks where the
+  // LDS serves 256 bytes per clock: the bank-conflict counter read 2.8-3.3 conflict cycles per
+  // active LDS cycle, as much as a 4-way conflicting read pattern elsewhere.)
   const int lrow = lane >> 3;
-  const int chunk = (lane & 7) ^ lrow;
+  const int chunk = (lane & 7) ^ lrow ^ (wave & 1);
   constexpr int CPT = 8 / TPS;              // 16-byte chunks of one tap inside a stage
   const bool second = chunk >= CPT;         // TPS == 2: this lane fetches the stage's second tap
   int a_off[A_LD], a_ih0[A_LD], a_iw0[A_LD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
-    const int m = m0 + (wave * A_LD + i) * 8 + lrow;
+    const int m = m0 + (wave + 4 * i) * 8 + lrow;
     const bool ok = m < p.M;
     const int mm = ok ? (POOL ? m >> 2 : m) : 0;
     const int ow = mm % p.W_out;
@@ -879,7 +883,7 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
   unsigned b_off[B_LD];
 #pragma unroll
   for (int i = 0; i < B_LD; ++i)
-    b_off[i] = (unsigned)(((co0 + (wave * B_LD + i) * 8 + lrow) * p.k_pad + chunk * KE) * (int)sizeof(T));
+    b_off[i] = (unsigned)(((co0 + (wave + 4 * i) * 8 + lrow) * p.k_pad + chunk * KE) * (int)sizeof(T));
   const int tap_row = p.dh * p.W * p.C_in * (int)sizeof(T), tap_col = p.dw * p.C_in * (int)sizeof(T);
 
   // Workgroups that share an operand tile (the same pixels, or the same channels) would all ask
@@ -925,12 +929,12 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
       const bool ok = (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows) & (iw >= 0) & (iw < p.W) & tap_ok;
       const unsigned char* src = ok ? xg + (a_off[j] + toff) : zero_src;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                       (__attribute__((address_space(3))) void*)(dst + (wave * A_LD + j) * 1024),
+                                       (__attribute__((address_space(3))) void*)(dst + (wave + 4 * j) * 1024),
                                        16, 0, 0);
     } else {
       const int i = j - A_LD;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wg + b_off[i] + koff),
-                                       (__attribute__((address_space(3))) void*)(dst + A_BYTES + (wave * B_LD + i) * 1024),
+                                       (__attribute__((address_space(3))) void*)(dst + A_BYTES + (wave + 4 * i) * 1024),
                                        16, 0, 0);
     }
   };
@@ -960,7 +964,7 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
   // operand fragment of this lane inside a 32-row tile of a stage: row = lane & 31, chunks
   // 2 * wave + (lane >> 5)
   const int frow = lane & 31, fchunk = 2 * wave + (lane >> 5);
-  const int foff = (frow >> 3) * 1024 + ((frow & 7) * 8 + (fchunk ^ (frow & 7))) * 16;
+  const int foff = (frow >> 3) * 1024 + ((frow & 7) * 8 + (fchunk ^ (frow & 7) ^ ((frow >> 3) & 1))) * 16;
   // The operand reads are written as instructions: reads the compiler can see make it wait for
   // EVERY global -> LDS load in flight before each of them (it cannot tell which stage a read
   // touches), which would leave one stage in flight instead of NST - 1. The waits are placed by
