@@ -1107,7 +1107,10 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
       if (m >= p.M || co >= p.C_out) continue;   // (M is a multiple of 4: whole windows)
       float best[VE];
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub) {
+      for (int turn = 0; turn < 4; ++turn) {
+        // (neighbouring windows start at different positions of their window: four rows apart
+        // they would read the same LDS banks at the same time)
+        const int sub = (turn + win) & 3;
         float v[VE];
 #pragma unroll
         for (int j = 0; j < VE; ++j) v[j] = 0.f;
@@ -1119,7 +1122,7 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
             v[j] += q.x; v[j + 1] += q.y; v[j + 2] += q.z; v[j + 3] += q.w;
           }
 #pragma unroll
-        for (int j = 0; j < VE; ++j) best[j] = sub == 0 ? v[j] : fmaxf(best[j], v[j]);
+        for (int j = 0; j < VE; ++j) best[j] = turn == 0 ? v[j] : fmaxf(best[j], v[j]);
       }
       finish_vec<T, VE>(p, m >> 2, co, best);
     }
