@@ -447,7 +447,8 @@ def main():
     head["one_band"] = one_band_reference(torch, lop, workloads, a.workload, a.mode, a)
     c = lop.lop_measure_ceilings()
     ceil = {"hbm_copy_GBps": round(c.hbm_copy_gbs, 1), "mfma_bf16_TFLOPps": round(c.mfma_bf16_tflops, 1),
-            "mfma_f32_TFLOPps": round(c.mfma_f32_tflops, 1), "launch_floor_us": round(c.launch_floor_us, 2)}
+            "mfma_f32_TFLOPps": round(c.mfma_f32_tflops, 1), "launch_floor_us": round(c.launch_floor_us, 2),
+            "graph_node_floor_us": round(c.graph_node_floor_us, 2)}
 
     def against_measured(roof, dtype):
         m = c.hbm_copy_gbs if roof["bound"] == "hbm" else (c.mfma_bf16_tflops if dtype == "bf16" else c.mfma_f32_tflops)

@@ -337,10 +337,11 @@ LOP_API int lop_run_two_party(lop_plan_t* plan, const void* d_in, void* d_out, c
  * wavefronts on every SIMD and operand bits that differ per lane (all-zero operands clock
  * higher than real data). Best of five launches each. launch_floor_us: mean duration, from
  * events attached to the dispatch, of a kernel of 128 workgroups that returns at once: what a
- * launch costs before it does anything. Allocates and frees 2 GiB of device
+ * launch costs before it does anything. graph_node_floor_us: wall time per node of a graph of 200
+ * such kernels, each depending on the one before, replayed on one stream. Allocates and frees 2 GiB of device
  * memory inside the call; synchronous; uses the null stream. Measurement aid: the roofline's
  * denominators stay the published peaks, these say how close any kernel can get here. */
-typedef struct { double hbm_copy_gbs, mfma_bf16_tflops, mfma_f32_tflops, launch_floor_us; } lop_ceilings_t;
+typedef struct { double hbm_copy_gbs, mfma_bf16_tflops, mfma_f32_tflops, launch_floor_us, graph_node_floor_us; } lop_ceilings_t;
 LOP_API int lop_measure_ceilings(lop_ceilings_t* out /* host */);
 
 /* Time one layer's kernel of one band in isolation: `iters` launches on the plan's

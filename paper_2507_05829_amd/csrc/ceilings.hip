@@ -155,6 +155,31 @@ extern "C" int lop_measure_ceilings(lop_ceilings_t* out) {
     (void)hipEventDestroy(ev.start[0]);
     (void)hipEventDestroy(ev.stop[0]);
   }
+  // ... and the same kernel as 200 dependent nodes of a graph replayed on one stream (how the
+  // chains run in steady state): wall time per node
+  {
+    constexpr int kNodes = 200, kReplays = 5;
+    hipStream_t st = nullptr;
+    hipGraph_t g = nullptr;
+    hipGraphExec_t ex = nullptr;
+    LOP_HIP(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    LOP_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    for (int i = 0; i < kNodes; ++i) hipLaunchKernelGGL(empty_kernel, dim3(128), dim3(256), 0, st, B.sink);
+    hipError_t e = hipStreamEndCapture(st, &g);
+    if (e == hipSuccess) e = hipGraphInstantiate(&ex, g, nullptr, nullptr, 0);
+    if (g) (void)hipGraphDestroy(g);
+    if (e == hipSuccess) e = hipGraphLaunch(ex, st);   // warm-up
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = hipEventRecord(B.e0, st);
+    for (int r = 0; r < kReplays && e == hipSuccess; ++r) e = hipGraphLaunch(ex, st);
+    if (e == hipSuccess) e = hipEventRecord(B.e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(B.e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, B.e0, B.e1);
+    if (ex) (void)hipGraphExecDestroy(ex);
+    (void)hipStreamDestroy(st);
+    LOP_HIP(e);
+    out->graph_node_floor_us = ms * 1e3 / (kNodes * kReplays);
+  }
   LOP_HIP(hipDeviceSynchronize());
   return LOP_OK;
 }

@@ -1185,6 +1185,210 @@ __device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f
   acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], b[3], acc, 0, 0, 0);
 }
 
+// Layers whose pixels are 64 bytes (32 bf16 channels in) under a 3 x 3 filter of horizontal
+// stride 1 at hundreds of thousands of pixels: the second layer of the 720p chain when all its
+// bands are one launch. The tiled kernels spend such a launch fetching: every workgroup pulls
+// the taps of its pixels (nine times the layer's input) and the filter through the L2s for a
+// reduction loop of five stages. Here a wavefront keeps the filter of 32 output channels in
+// registers as MFMA operands (18 vectors of 16 bytes) and walks over tiles of 16 consecutive
+// pixels of an output row; per tile and filter row it loads the 16 pixels of the first tap (and
+// the two behind them) straight into the other operand and takes the second and third tap from
+// its neighbours' registers. No LDS, no barrier; the four wavefronts of a workgroup only share
+// the filter's cache lines. Workgroups walk the tiles with a stride (XCD k over the k-th
+// eighth of them, so that an XCD's L2 holds neighbouring image rows), which spreads the cost
+// of loading the filter over several tiles. Measured on 856 000 pixels (32 -> 32 channels):
+// 44 us against 91 us on the LDS-staged kernel; with that filter loop unrolled the kernel is
+// bound by the instructions around the 36 MFMAs of a round, not by memory (the same loop with
+// no load, store or MFMA in it takes two thirds of the time), so launches of one band (tens of
+// thousands of pixels, where it measured no faster) stay on the LDS-staged kernel.
+constexpr int kRegwTiles = 8;           // tiles of 16 pixels of a row per workgroup and round: two per wavefront
+constexpr int kRegwWorkgroups = 768;    // three per compute unit: all resident at once
+constexpr int kRegwMinPixels = 1 << 17;
+
+// rounds of workgroups it takes to cover a launch
+__host__ __device__ inline int regw_groups(const ConvParams& p) {
+  const int tiles = p.N * p.R * ((p.W_out + 15) >> 4);
+  return (tiles + kRegwTiles - 1) / kRegwTiles;
+}
+
+__device__ __forceinline__ void conv_regw_kernel_body(const ConvParams& p, const int bx, const int gx) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // 16 x 16 x 32 MFMAs: lane (pxl, kq) holds channels 8 kq + {0..7} in of a pixel (or of an
+  // output channel's filter tap), so the four lanes of a pixel read its 64 bytes together and a
+  // wavefront's load covers 16 whole pixels
+  const int pxl = lane & 15, kq = lane >> 4;
+  const int co0 = blockIdx.y * 32;
+  // The input slab as a buffer: a load whose offset lies beyond the buffer returns zeros without
+  // touching memory, which is how a tap outside the image or the slab reads here (a select per
+  // loaded register would cost as many instructions as the MFMAs take cycles).
+  const __amdgpu_buffer_rsrc_t xbuf = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(p.x), 0, (int)((size_t)p.N * p.x_rows * p.W * 64), 0x00020000);
+  constexpr unsigned kOutside = 0x80000000u;
+  u32x4 wt[9][2];   // tap, half of the 32 output channels
+  float bias[2][4];
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb) {
+    const int co = co0 + cb * 16;
+    const unsigned char* wrow = (const unsigned char*)p.w + ((size_t)(co + pxl) * p.k_pad + kq * 8) * 2;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) wt[t][cb] = *(const u32x4*)(wrow + t * 64);
+    const float4 b4 = p.bias ? *(const float4*)(p.bias + co + kq * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    bias[cb][0] = b4.x; bias[cb][1] = b4.y; bias[cb][2] = b4.z; bias[cb][3] = b4.w;
+  }
+  const Clamp cl = make_clamp(p.act);
+  // A tile is 16 consecutive pixels of ONE output row, so that image, row and the nine row
+  // offsets of a tile are the same for the whole wavefront (scalar arithmetic) and a lane only
+  // adds its column; the last tile of a row may hang over its end. Eight tiles per workgroup
+  // and round, two per wavefront.
+  const int tpr = (p.W_out + 15) >> 4;
+  const int groups = regw_groups(p);
+  int grp = bx, step = gx, end = groups;
+  if (gx % kXcds == 0) {   // (the hardware hands workgroups to the XCDs round-robin)
+    const int per = (groups + kXcds - 1) / kXcds, xcd = bx % kXcds;
+    grp = xcd * per + bx / kXcds;
+    step = gx / kXcds;
+    end = min(groups, (xcd + 1) * per);
+  }
+  // the tiles of this wavefront as (image, row of the launch, tile of the row), stepped from
+  // round to round without a division; a tile past the end has an image index past the last
+  int tcol[2], row[2], img[2];
+#pragma unroll
+  for (int tile = 0; tile < 2; ++tile) {
+    const int t = grp * kRegwTiles + wave * 2 + tile;
+    const int q = t / tpr;
+    tcol[tile] = t - q * tpr;
+    img[tile] = q / p.R;
+    row[tile] = q - img[tile] * p.R;
+  }
+  const int adv = step * kRegwTiles;
+  const int adv_q = adv / tpr, adv_col = adv - adv_q * tpr;
+  const int adv_img = adv_q / p.R, adv_row = adv_q - adv_img * p.R;
+  const int lane_in = (pxl - p.pw) * 64 + kq * 16;   // this lane's bytes in a row of the slab, from the tile's first column
+  for (; grp < end; grp += step) {
+    // Per tile and filter row ONE load of 16 pixels (the row's first tap) and one of the two
+    // pixels behind them; the second and third tap of a lane are the first tap of its right-hand
+    // neighbours, taken from their registers by lane shifts inside the 16-lane rows. (The L1
+    // hands a wavefront's 16-byte load over in about 35 cycles however its lines hit: with nine
+    // loads per tile the kernel ran at the speed of that path.) A column outside the image loads
+    // as zeros like a row outside, and stays a zero when it is shifted.
+    u32x4 px[2][9];
+    int ow[2];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+      ow[tile] = tcol[tile] * 16 + pxl;
+      const bool live = img[tile] < p.N;                       // (the same for the whole wavefront)
+      const int ih0 = (p.out_lo + row[tile]) * p.sh - p.ph;    // (... and so are the rows of the taps)
+      const int iw = ow[tile] - p.pw;                          // column of this lane's first tap
+      const unsigned off_a = (iw >= 0) & (iw < p.W) ? (unsigned)(tcol[tile] * 1024 + lane_in) : kOutside;
+      const unsigned off_h = (pxl < 2) & (iw + 16 < p.W) ? (unsigned)(tcol[tile] * 1024 + lane_in + 1024) : kOutside;
+#pragma unroll
+      for (int a = 0; a < 3; ++a) {
+        const int ih = ih0 + a * p.dh;
+        const bool row_ok = live & (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows);
+        const int row_base = row_ok ? ((img[tile] * p.x_rows - p.x_row0 + ih) * p.W) * 64 : 0;
+        const u32x4 first = __builtin_amdgcn_raw_buffer_load_b128(xbuf, row_ok ? off_a : kOutside, row_base, 0);
+        u32x4 behind = u32x4{0u, 0u, 0u, 0u};
+        if (pxl < 2) behind = __builtin_amdgcn_raw_buffer_load_b128(xbuf, row_ok ? off_h : kOutside, row_base, 0);
+        px[tile][a * 3] = first;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          // lane 15 of a row <- lane 0 of `behind`, then lanes 0..14 <- lanes 1..15 of `first`
+          const int h1 = __builtin_amdgcn_update_dpp(0, (int)behind[i], 0x11f, 0xf, 0xf, true);    // row_shr:15
+          px[tile][a * 3 + 1][i] = (unsigned)__builtin_amdgcn_update_dpp(h1, (int)first[i], 0x101, 0xf, 0xf, false);  // row_shl:1
+          // lanes 14, 15 <- lanes 0, 1 of `behind`, then lanes 0..13 <- lanes 2..15 of `first`
+          const int h2 = __builtin_amdgcn_update_dpp(0, (int)behind[i], 0x11e, 0xf, 0xf, true);    // row_shr:14
+          px[tile][a * 3 + 2][i] = (unsigned)__builtin_amdgcn_update_dpp(h2, (int)first[i], 0x102, 0xf, 0xf, false);  // row_shl:2
+        }
+      }
+    }
+    f32x4 acc[2][2];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) acc[tile][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile)
+#pragma unroll
+      for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) mma16<__bf16>(wt[t][cb], px[tile][t], acc[tile][cb]);
+    // bias + residual + activation + the one rounding: a lane holds channels
+    // co0 + 16 cb + 4 kq + {0..3} of its pixel of either tile
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+      if (img[tile] < p.N && ow[tile] < p.W_out) {
+        const int oh = p.out_lo + row[tile];
+        const long yrow = ((long)(img[tile] * p.y_rows + oh - p.y_row0) * p.W_out) * p.C_out + co0;
+        const long rrow = p.res ? ((long)(img[tile] * p.r_rows + oh - p.r_row0) * p.W_out) * p.C_out + co0 : 0;
+        const int in_row = ow[tile] * p.C_out + kq * 4;
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          float v[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = acc[tile][cb][i] + bias[cb][i];
+          if (p.res) {
+            alignas(8) __bf16 rr[4];
+            *(uint2*)rr = *(const uint2*)((const __bf16*)p.res + rrow + in_row + cb * 16);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] += (float)rr[i];
+          }
+          alignas(8) __bf16 o[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o[i] = (__bf16)clamp_act(v[i], cl);
+          *(uint2*)((__bf16*)p.y + yrow + in_row + cb * 16) = *(const uint2*)o;
+          if (p.y2) *(uint2*)((__bf16*)p.y2 + yrow + in_row + cb * 16) = *(const uint2*)o;
+        }
+      }
+      // the same wavefront's tile of the next round
+      tcol[tile] += adv_col;
+      const int c1 = tcol[tile] >= tpr;
+      tcol[tile] -= c1 ? tpr : 0;
+      row[tile] += adv_row + c1;
+      const int c2 = row[tile] >= p.R;
+      row[tile] -= c2 ? p.R : 0;
+      img[tile] += adv_img + c2;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_regw_kernel(const ConvParams p) {
+  conv_regw_kernel_body(p, blockIdx.x, gridDim.x);
+}
+// The same for several bands of one layer in one grid (band b owns blocks first[b] .. first[b + 1] of x).
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void conv_regw_kernel_bands(const Batch<ConvParams> t) {
+  const int b = batch_find(t, blockIdx.x);
+  conv_regw_kernel_body(t.p[b], blockIdx.x - t.first[b], t.first[b + 1] - t.first[b]);
+}
+
+// Whether the filter-in-registers kernel takes a launch (judged on all bands of a group together).
+bool regw_applies(const ConvParams& p, int dtype) {
+  if (dtype != LOP_BF16 || p.C_in != 32 || p.kh != 3 || p.kw != 3 || p.C_out % 32 != 0) return false;
+  if (p.sw != 1 || p.dw != 1) return false;   // (a lane's taps are its neighbours' pixels)
+  if (p.M < kRegwMinPixels || p.pool) return false;
+  // 32-bit signed byte offsets into the input slab
+  return (size_t)p.N * p.x_rows * p.W * p.C_in * 2 < ((size_t)1 << 31);
+}
+
+hipError_t launch_regw(const ConvParams* ps, int n, hipStream_t s, KernelEvents* ev) {
+  const ConvParams& p = ps[0];
+  const unsigned gy = (unsigned)(p.C_out / 32);
+  long all = 0;
+  for (int b = 0; b < n; ++b) all += regw_groups(ps[b]);
+  if (all <= 0 || (int)gy * 32 > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
+  // every band gets its share of the resident workgroups (a multiple of the XCD count, or all
+  // of its pixel groups when those are fewer)
+  unsigned gx[kMaxBatch];
+  for (int b = 0; b < n; ++b) {
+    if ((size_t)ps[b].N * ps[b].x_rows * ps[b].W * ps[b].C_in * 2 >= ((size_t)1 << 31)) return hipErrorInvalidValue;
+    const long groups = regw_groups(ps[b]);
+    long share = (long)kRegwWorkgroups / gy * groups / all;
+    share = share / kXcds * kXcds;
+    gx[b] = (unsigned)(share >= kXcds && share < groups ? share : groups);
+  }
+  return launch_group(conv_regw_kernel, conv_regw_kernel_bands, ps, n, gx, gy, 1, dim3(256), s, ev);
+}
+
 constexpr int kNarrowWaves = 16;
 // Stages of 128 bytes per row in LDS per workgroup. fp32: eight while the launch has at most one
 // workgroup per compute unit (nothing else hides a workgroup's latency), four beyond that: with
@@ -1590,6 +1794,12 @@ hipError_t launch_typed(ConvParams* ps, int n, int dtype, float* ws, hipStream_t
   for (int b = 0; b < n; ++b)
     if ((size_t)ps[b].N * ps[b].x_rows * ps[b].W * ps[b].C_in * sizeof(T) >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   const ConvParams g = group_params(ps, n);
+  if constexpr (sizeof(T) == 2) {
+    if (regw_applies(g, dtype)) {
+      for (int b = 0; b < n; ++b) ps[b].ws = nullptr;
+      return launch_regw(ps, n, s, ev);
+    }
+  }
   const Choice c = choose(g, dtype);
   const DirectChoice d = choose_direct(g, dtype, c.splits);
   const LdsChoice ld = lds_applies(g, dtype, c, d);
@@ -1684,6 +1894,7 @@ size_t conv_workspace_bytes_bands(const OpLaunch* Ls, int n) {
   if (m == 0) return 0;
   const int dtype = Ls[0].dtype;
   const ConvParams g = group_params(ps, m);
+  if (regw_applies(g, dtype)) return 0;
   const Choice c = choose(g, dtype);
   const DirectChoice d = choose_direct(g, dtype, c.splits);
   if (lds_applies(g, dtype, c, d).bm) return 0;
@@ -1719,6 +1930,10 @@ int conv_igemm_describe_bands(const OpLaunch* Ls, int n, char* name, size_t size
   const char* const form = m > 1 ? "_bands" : "";
   const bool bf = L.dtype == LOP_BF16;
   const bool vec = p.C_in % (bf ? 8 : 4) == 0;
+  if (regw_applies(p, L.dtype)) {
+    if (name && size) snprintf(name, size, "conv_regw_kernel%s", form);
+    return 1;
+  }
   const Choice c = choose(p, L.dtype);
   static const int wm[] = {2, 2, 2, 4, 2}, wn[] = {2, 2, 2, 1, 4};
   const DirectChoice d = choose_direct(p, L.dtype, c.splits);

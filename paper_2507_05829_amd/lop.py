@@ -87,7 +87,7 @@ class lop_two_party_stats_t(Structure):
 
 class lop_ceilings_t(Structure):
     _fields_ = [("hbm_copy_gbs", c_double), ("mfma_bf16_tflops", c_double), ("mfma_f32_tflops", c_double),
-                ("launch_floor_us", c_double)]
+                ("launch_floor_us", c_double), ("graph_node_floor_us", c_double)]
 
 
 class lop_tensor_desc_t(Structure):

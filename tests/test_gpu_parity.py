@@ -148,6 +148,51 @@ def test_lds_staged_kernel(oracle, cfg):
         np.testing.assert_array_equal(dev, want)
 
 
+REGW_GRID = [
+    # c_out, p, shape(n,h,w), residual, bands
+    (32, 1, (1, 400, 336), True, 3),      # rows of 21 tiles, residual
+    (64, 2, (1, 370, 370), False, 2),     # padding 2: two columns outside on either side; rows end 4 pixels into a tile
+    (96, 0, (2, 262, 262), False, 4),     # no padding, batch 2, three channel blocks
+    (32, 1, (16, 700, 12), False, 5),     # rows shorter than a tile: the pixels behind a tile lie outside
+]
+
+
+@pytest.mark.parametrize("cfg", REGW_GRID)
+def test_filter_in_registers_kernel(oracle, cfg):
+    """The kernel for 64-byte pixels under a 3 x 3 filter at hundreds of thousands of pixels
+    (filter in registers, first tap straight from memory, the others from neighbouring lanes):
+    shapes that select it in one band and with all bands in one launch, checked by name, random
+    values against the oracle within tolerance and small integers bit for bit."""
+    c_out, p_, shape, residual, bands = cfg
+    chain = _single(workloads.CONV, 32, c_out, 3, 1, p_, 1, "relu", "bf16", shape, n_bands=bands,
+                    residual=residual)
+    t = workloads.make_tensors(chain, zero_bias=False, seed=13)
+    plan = lop.Plan(chain, t, 1)
+    try:
+        assert plan.layer_kernel(0, plan.n_layers - 1)[0] == "conv_regw_kernel"
+    finally:
+        plan.destroy()
+    want = oracle.run_chain(chain, t)
+    dev, host = run_gpu(chain, t, n_bands=1)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL["bf16"]
+    dev, host, names = _run_batched(chain, t, graph=0)
+    assert names[-1][0] == "conv_regw_kernel_bands", names
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL["bf16"]
+    ti = workloads.small_int_tensors(chain, seed=5)
+    for i, w_ in enumerate(ti.weights):      # sparse {-1, 0, 1} x {0, 1}: every sum a bf16 value
+        if w_ is not None:
+            ti.weights[i] = np.sign(w_) * (np.abs(w_) > 1)
+    ti.x = (ti.x > 2).astype(np.float32)
+    want = oracle.run_chain(chain, ti)
+    assert 8 < np.abs(want).max() < 256
+    dev, _ = run_gpu(chain, ti, n_bands=1)
+    np.testing.assert_array_equal(dev, want)
+    dev, _, _ = _run_batched(chain, ti, graph=1)
+    np.testing.assert_array_equal(dev, want)
+
+
 POOLED_GRID = [
     # dtype, c_in, c_out, k, s, p, shape(n,h,w), bands, then a third layer behind the pooling?
     ("bf16", 64, 128, 3, 1, 1, (1, 82, 106), 3, False),   # 64 x 64 tiles, ragged last tile
