@@ -186,6 +186,8 @@ LOP_API int lop_plan_layer_work(const lop_plan_t* plan, int band, int layer, dou
  *          captured graph (LOP_FLAG_GRAPH) holds the addresses it was captured with: a buffer
  *          passed here must stay allocated, and of the same kind, for as long as the plan lives.
  *   compute_stream, copy_stream  hipStream_t or NULL (= the plan's own streams)
+ * d_in, d_out and h_out start on a 16-byte boundary (the kernels move 16-byte vectors), in this
+ * and every other call that takes them; an address that does not is LOP_ERR_INVALID_ARG.
  * Bands b and b' with b = b' (mod lanes) share scratch memory: give them the same
  * compute stream (or NULL). Bands of different lanes may run concurrently. */
 LOP_API int lop_run_band(lop_plan_t* plan, int band, const void* d_in, void* d_out, void* h_out,

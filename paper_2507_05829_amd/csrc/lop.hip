@@ -2,6 +2,8 @@
 // scheduler (compute stream + copy stream + one event per band) and the queries.
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
+
 #include <algorithm>
 #include <chrono>
 #include <cstring>
@@ -1194,9 +1196,13 @@ int lop_plan_layer_work(const lop_plan_t* P, int band, int layer, double* flop, 
   return LOP_OK;
 }
 
+// The kernels move 16-byte vectors: tensors start on a 16-byte boundary.
+static bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
 int lop_run_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h_out,
                  void* compute_stream, void* copy_stream) {
   if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
+  if (misaligned(d_in) || misaligned(d_out) || misaligned(h_out)) return LOP_ERR_INVALID_ARG;
   if (band < 0 || band >= P->t.n_bands) return LOP_ERR_BAND_RANGE;
   if (!P->ready) return LOP_ERR_NOT_READY;
   if (band_empty(P, band)) return LOP_OK;
@@ -1210,6 +1216,7 @@ int lop_run_band(lop_plan_t* P, int band, const void* d_in, void* d_out, void* h
 int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, void* compute_stream,
                   lop_timing_t* timing) {
   if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
+  if (misaligned(d_in) || misaligned(d_out) || misaligned(h_out)) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   hipStream_t ms = compute_stream ? (hipStream_t)compute_stream : P->s_main;
   if (compute_stream) P->last_user_stream = ms;
@@ -1295,6 +1302,7 @@ int lop_run_chain(lop_plan_t* P, const void* d_in, void* d_out, void* h_out, voi
 
 int lop_run_chain_static(lop_plan_t* P, const void* d_in, void* d_out, void* stream) {
   if (!P || !d_in || !d_out) return LOP_ERR_INVALID_ARG;
+  if (misaligned(d_in) || misaligned(d_out)) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   const size_t arena = align_up(P->arena_bytes, 256);
   if (arena + P->conv_ws_bytes > (size_t)LOP_STATIC_SCRATCH_BYTES) return LOP_ERR_TOO_LARGE;
@@ -1329,6 +1337,7 @@ int lop_synchronize(lop_plan_t* P) {
 int lop_time_layer(lop_plan_t* P, int band, int layer, const void* d_in, void* d_out, int iters,
                    float* ms_per_launch) {
   if (!P || !d_in || !d_out || !ms_per_launch || iters < 1) return LOP_ERR_INVALID_ARG;
+  if (misaligned(d_in) || misaligned(d_out)) return LOP_ERR_INVALID_ARG;
   if (band < 0 || band >= P->t.n_bands || layer < 0 || layer >= P->t.n_layers())
     return LOP_ERR_BAND_RANGE;
   if (!P->ready) return LOP_ERR_NOT_READY;
@@ -1371,6 +1380,7 @@ int lop_plan_layer_kernel(const lop_plan_t* P, int band, int layer, char* name, 
 int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, float* layer_ms,
                       float* finish_ms) {
   if (!P || !d_in || !d_out || !layer_ms || iters < 1) return LOP_ERR_INVALID_ARG;
+  if (misaligned(d_in) || misaligned(d_out)) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   const int nb = P->t.n_bands, nl = P->t.n_layers();
   int rc = lop_synchronize(P);
@@ -1420,6 +1430,7 @@ int lop_profile_chain(lop_plan_t* P, const void* d_in, void* d_out, int iters, f
 
 int lop_copy_chain(lop_plan_t* P, const void* d_out, void* h_out) {
   if (!P || !d_out || !h_out) return LOP_ERR_INVALID_ARG;
+  if (misaligned(d_out) || misaligned(h_out)) return LOP_ERR_INVALID_ARG;
   if (!P->ready) return LOP_ERR_NOT_READY;
   if (!device_view_of_host(P, h_out)) return LOP_ERR_INVALID_ARG;
   for (int b = 0; b < P->t.n_bands; ++b) {

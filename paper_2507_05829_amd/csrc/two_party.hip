@@ -4,6 +4,8 @@
 // for latency + bytes / bandwidth. An emulation for studying schedules, not the hot path.
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
+
 #include <algorithm>
 #include <vector>
 
@@ -95,6 +97,7 @@ extern "C" int lop_run_two_party(lop_plan_t* P, const void* d_in, void* d_out, c
                                  int n_sched, const lop_loss_layer_t* costs, double bandwidth,
                                  double latency, lop_two_party_stats_t* stats) {
   if (!P || !d_in || !d_out || !sched) return LOP_ERR_INVALID_ARG;
+  if ((((uintptr_t)d_in | (uintptr_t)d_out) & 15u) != 0) return LOP_ERR_INVALID_ARG;   // 16-byte vectors
   const lop::Tables& t = P->t;
   const int nl = t.n_layers();
   if (n_sched != nl || !(bandwidth > 0.0) || latency < 0.0) return LOP_ERR_INVALID_ARG;

@@ -125,14 +125,21 @@ def test_band_range_and_not_ready():
             lop.lop_plan_band_layer_rows(h, 0, 1)
         assert e.value.code == lop.LOP_ERR_BAND_RANGE
         with pytest.raises(lop.LopError) as e:
-            lop.lop_run_band(h, 0, 1, 1)          # dummy non-null addresses, never touched
+            lop.lop_run_band(h, 0, 16, 16)        # dummy non-null addresses, never touched
         assert e.value.code == lop.LOP_ERR_NOT_READY
         with pytest.raises(lop.LopError) as e:
-            lop.lop_run_chain(h, 1, 1)
+            lop.lop_run_chain(h, 16, 16)
         assert e.value.code == lop.LOP_ERR_NOT_READY
         with pytest.raises(lop.LopError) as e:
-            lop.lop_run_chain(h, None, 1)
+            lop.lop_run_chain(h, None, 16)
         assert e.value.code == lop.LOP_ERR_INVALID_ARG
+        # tensors start on a 16-byte boundary
+        for call in (lambda: lop.lop_run_band(h, 0, 24, 16), lambda: lop.lop_run_band(h, 0, 16, 16, 8),
+                     lambda: lop.lop_run_chain(h, 16, 40), lambda: lop.lop_run_chain(h, 16, 16, 4),
+                     lambda: lop.lop_run_chain_static(h, 2, 16)):
+            with pytest.raises(lop.LopError) as e:
+                call()
+            assert e.value.code == lop.LOP_ERR_INVALID_ARG
     finally:
         lop.lop_plan_destroy(h)
     lop.lop_plan_destroy(None)                   # destroying NULL is a no-op
@@ -213,7 +220,7 @@ def test_two_party_schedule_is_checked_on_the_host():
 
     def code(sched, bandwidth=1e9, latency=0.0):
         try:
-            lop.lop_run_two_party(h, 1, 1, sched, bandwidth, latency)
+            lop.lop_run_two_party(h, 16, 16, sched, bandwidth, latency)
         except lop.LopError as e:
             return e.code
         return 0
