@@ -91,6 +91,7 @@ bool stem_shape_applies(int c_in, int c_out, int kh, int kw, int sw, int dh, int
 bool stem_applies(const OpLaunch& L);
 hipError_t launch_stem(const OpLaunch& L, hipStream_t stream, KernelEvents* ev = nullptr);
 int stem_describe(const OpLaunch& L, char* name, size_t size);
+int stem_describe_bands(const OpLaunch* Ls, int n, char* name, size_t size);
 // A dense convolution and the 2 x 2 stride-2 max pooling that reads it, as one launch: whether
 // the pair qualifies (descriptors without slabs suffice), the launch (conv: input slab, weights,
 // hyper-parameters; pool: output slab, y2 and the pooled rows out_lo..out_hi) and its kernel name.

@@ -68,7 +68,8 @@ hipError_t launch_op_bands(const OpLaunch* Ls, int n, hipStream_t stream, Kernel
 }
 
 int describe_op_bands(const OpLaunch* Ls, int n, char* name, size_t size) {
-  if (n == 1 || Ls[0].op != LOP_CONV2D || stem_applies(Ls[0])) {
+  if (n > 1 && Ls[0].op == LOP_CONV2D && stem_applies(Ls[0])) return stem_describe_bands(Ls, n, name, size);
+  if (n == 1 || Ls[0].op != LOP_CONV2D) {
     const int k = describe_op(Ls[0], name, size);
     if (n > 1 && name && size) {   // the form that takes several bands carries _bands in its name
       std::string s(name);
@@ -168,10 +169,11 @@ int upload_weights(lop_plan_t* P) {
       LOP_HIP(lop::dev_alloc(&P->d_w[l], host.size()));
       LOP_HIP(hipMemcpy(P->d_w[l], host.data(), host.size(), hipMemcpyHostToDevice));
       if (P->has_wstem[l]) {
-        // fp32 [c_out / 4][k][4], k = (a*kw + b)*c_in + ci: four weights of one reduction
-        // element are one 16-byte load whose address a whole wavefront shares
+        // fp32 [c_out / 4][k][4] and, behind it, [c_out / 16][k][16], k = (a*kw + b)*c_in + ci:
+        // four (sixteen) weights of one reduction element lie together at an address a whole
+        // wavefront shares
         const size_t K = (size_t)d.c_in * d.kh * d.kw;
-        std::vector<float> q((size_t)d.c_out * K);
+        std::vector<float> q(2 * (size_t)d.c_out * K);
         for (int co = 0; co < d.c_out; ++co)
           for (size_t k = 0; k < K; ++k) {
             float v;
@@ -185,6 +187,7 @@ int upload_weights(lop_plan_t* P) {
               std::memcpy(&v, src, 4);
             }
             q[((size_t)(co / 4) * K + k) * 4 + co % 4] = v;
+            q[(size_t)d.c_out * K + ((size_t)(co / 16) * K + k) * 16 + co % 16] = v;
           }
         LOP_HIP(lop::dev_alloc(&P->d_wstem[l], q.size() * 4));
         LOP_HIP(hipMemcpy(P->d_wstem[l], q.data(), q.size() * 4, hipMemcpyHostToDevice));

@@ -253,6 +253,47 @@ STEM_GRID = [
 ]
 
 
+STEM_LANE_GRID = [
+    # dtype, c_in, c_out, k, s, p, shape(n,h,w), bands
+    ("bf16", 3, 32, 3, 2, 1, (2, 720, 1280), 5),   # the 720p chain's first layer, batch 2
+    ("f32", 3, 64, 7, 2, 3, (4, 448, 448), 3),     # 7 x 7 stride 2 (unrolled row of 21), two channel halves
+    ("bf16", 3, 64, 3, 1, 1, (1, 500, 520), 4),    # stride 1, rows end 8 pixels into a tile
+    ("f32", 3, 16, 5, 1, 2, (2, 300, 500), 2),     # 5 x 5: the generic loop, 16 channels per lane
+    ("f32", 1, 32, 3, 1, 0, (1, 600, 500), 3),     # one input channel, no padding
+]
+
+
+@pytest.mark.parametrize("cfg", STEM_LANE_GRID)
+def test_first_layer_kernel_at_large_sizes(oracle, cfg):
+    """First layers with thousands of 64-pixel tiles run on the form in which a lane owns a
+    pixel (checked by name), in one band and with all bands in one launch: random values against
+    the oracle within tolerance, small integers bit for bit."""
+    dtype, c_in, c_out, k, s_, p_, shape, bands = cfg
+    chain = workloads.Chain("stem", (shape[0], c_in, shape[1], shape[2]), dtype, bands)
+    chain.add(workloads.CONV, c_in, c_out, k, s_, p_, 1, "relu")
+    t = workloads.make_tensors(chain, zero_bias=False, seed=37)
+    plan = lop.Plan(chain, t, 1)
+    try:
+        assert plan.layer_kernel(0, 0)[0].startswith("conv_stem_lane_kernel<"), plan.layer_kernel(0, 0)
+    finally:
+        plan.destroy()
+    want = oracle.run_chain(chain, t)
+    dev, host = run_gpu(chain, t, n_bands=1)
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL[dtype]
+    dev, host, names = _run_batched(chain, t, graph=0)
+    assert names[0][0].startswith("conv_stem_lane_kernel_bands<"), names
+    np.testing.assert_array_equal(dev, host)
+    assert rel_err(dev, want) <= TOL[dtype]
+    ti = workloads.small_int_tensors(chain, seed=9)
+    want = oracle.run_chain(chain, ti)
+    assert np.abs(want).max() < (256 if dtype == "bf16" else 2 ** 24)
+    dev, _ = run_gpu(chain, ti, n_bands=1)
+    np.testing.assert_array_equal(dev, want)
+    dev, _, _ = _run_batched(chain, ti, graph=1)
+    np.testing.assert_array_equal(dev, want)
+
+
 @pytest.mark.parametrize("reuse", [0, 1])
 @pytest.mark.parametrize("cfg", STEM_GRID)
 def test_first_layer_kernel(oracle, cfg, reuse):
