@@ -1398,6 +1398,7 @@ constexpr int kNarrowWaves = 16;
 constexpr int kLdsStagesBf16 = 4, kLdsStagesF32 = 8, kLdsStagesF32Crowded = 4;
 inline int f32_stages(long tiles) { return tiles > 256 ? kLdsStagesF32Crowded : kLdsStagesF32; }
 constexpr long kLdsMaxLoopCycles = 25000;  // see lds_applies (40000 and 15000 measured: the fp32 chain gains down to 15000, the bf16 chains lose below 25000)
+constexpr long kLdsOverTiledMaxTiles = 4 * 256;   // see lds_applies (2 048 and more measured slower than the tiled kernel)
 constexpr int kLdsMinTiles = 48;   // below this the operand-direct kernels (one round of latency) win; 96 and 20 measured slower
 
 template <typename T>
@@ -1724,7 +1725,13 @@ Choice choose(const ConvParams& p, int dtype) {
 // (the tiled kernel keeps the layers large enough for its 128-wide tiles to cover the chip)
 // unless the 16 x 16-tile kernel finishes it in one round of workgroups.
 LdsChoice lds_applies(const ConvParams& p, int dtype, const Choice& c, const DirectChoice& d) {
-  if (c.shape == S256x256 || (c.splits == 1 && (c.shape == S128x128 || c.shape == S128x64))) return {0, 0, 0};
+  if (c.shape == S256x256) return {0, 0, 0};
+  if (c.splits == 1 && (c.shape == S128x128 || c.shape == S128x64)) {
+    // (a layer that just covers the chip with 128-wide tiles: up to four rounds of this kernel's
+    // tiles it is still the faster one - 256 -> 256 channels on 9 800 pixels 34 against 39 us)
+    const LdsChoice few = choose_lds(p, dtype);
+    return few.bm && few.tiles <= kLdsOverTiledMaxTiles ? few : LdsChoice{0, 0, 0};
+  }
   if (d.wk && d.narrow) return {0, 0, 0};
   const LdsChoice ld = choose_lds(p, dtype);
   // A workgroup of this kernel walks the whole reduction axis by itself, pulling BM + BN rows of
