@@ -84,7 +84,8 @@ def named_workloads():
     n = 0
     scaled = [workloads.tiny_chain(), workloads.resnet18_chain(h=64, w=48), workloads.vgg16_chain(h=64, w=64),
               workloads.detector_chain(h=96, w=64), workloads.mbv2_chain(h=32, w=32, n=2, n_bands=4),
-              workloads.mbv2_chain(h=192, w=192, n=8, n_bands=2)]   # long band copies: the copy lane
+              workloads.mbv2_chain(h=192, w=192, n=8, n_bands=2),   # long band copies: the copy lane
+              workloads.detector_chain()]   # full size: the kernels that only large launches take
     for chain in scaled:
         t = workloads.make_tensors(chain, zero_bias=False)
         for flags in (0, lop.LOP_FLAG_REUSE, lop.LOP_FLAG_GRAPH, lop.LOP_FLAG_GRAPH | lop.LOP_FLAG_REUSE,
