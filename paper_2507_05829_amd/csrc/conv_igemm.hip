@@ -1781,6 +1781,15 @@ ConvParams group_params(const ConvParams* ps, int n) {
   return g;
 }
 
+// Whether the filter-in-registers kernel takes a group of bands: the layer and the group's
+// pixels qualify and every band's slab is within reach of its 32-bit offsets.
+bool regw_takes(const ConvParams* ps, int n, int dtype) {
+  if (!regw_applies(group_params(ps, n), dtype)) return false;
+  for (int b = 0; b < n; ++b)
+    if ((size_t)ps[b].N * ps[b].x_rows * ps[b].W * ps[b].C_in * 2 >= ((size_t)1 << 31)) return false;
+  return true;
+}
+
 // Split-K partial sums of the bands of a group, one region after the other in the workspace.
 size_t assign_workspace(ConvParams* ps, int n, int splits, int kc_per_split, float* ws) {
   size_t at = 0;
@@ -1802,7 +1811,7 @@ hipError_t launch_typed(ConvParams* ps, int n, int dtype, float* ws, hipStream_t
     if ((size_t)ps[b].N * ps[b].x_rows * ps[b].W * ps[b].C_in * sizeof(T) >= ((size_t)1 << 32)) return hipErrorInvalidValue;
   const ConvParams g = group_params(ps, n);
   if constexpr (sizeof(T) == 2) {
-    if (regw_applies(g, dtype)) {
+    if (regw_takes(ps, n, dtype)) {
       for (int b = 0; b < n; ++b) ps[b].ws = nullptr;
       return launch_regw(ps, n, s, ev);
     }
@@ -1901,7 +1910,7 @@ size_t conv_workspace_bytes_bands(const OpLaunch* Ls, int n) {
   if (m == 0) return 0;
   const int dtype = Ls[0].dtype;
   const ConvParams g = group_params(ps, m);
-  if (regw_applies(g, dtype)) return 0;
+  if (regw_takes(ps, m, dtype)) return 0;
   const Choice c = choose(g, dtype);
   const DirectChoice d = choose_direct(g, dtype, c.splits);
   if (lds_applies(g, dtype, c, d).bm) return 0;
@@ -1937,7 +1946,7 @@ int conv_igemm_describe_bands(const OpLaunch* Ls, int n, char* name, size_t size
   const char* const form = m > 1 ? "_bands" : "";
   const bool bf = L.dtype == LOP_BF16;
   const bool vec = p.C_in % (bf ? 8 : 4) == 0;
-  if (regw_applies(p, L.dtype)) {
+  if (regw_takes(ps, m, L.dtype)) {
     if (name && size) snprintf(name, size, "conv_regw_kernel%s", form);
     return 1;
   }
