@@ -1191,23 +1191,26 @@ __device__ __forceinline__ void mma16<float>(const u32x4& wa, const u32x4& px, f
 // the taps of its pixels (nine times the layer's input) and the filter through the L2s for a
 // reduction loop of five stages. Here a wavefront keeps the filter of 32 output channels in
 // registers as MFMA operands (18 vectors of 16 bytes) and walks over tiles of 16 consecutive
-// pixels of an output row; per tile and filter row it loads the 16 pixels of the first tap (and
-// the two behind them) straight into the other operand and takes the second and third tap from
-// its neighbours' registers. No LDS, no barrier; the four wavefronts of a workgroup only share
-// the filter's cache lines. Workgroups walk the tiles with a stride (XCD k over the k-th
+// pixels of an input row; per tile and filter row it loads those 16 pixels once, straight into
+// the other operand, multiplies them with each of the row's three filter columns into sums kept
+// per column, and puts an output pixel together from the column sums of three neighbouring
+// lanes: 14 output pixels per tile. No LDS, no barrier; the four wavefronts of a workgroup
+// only share the filter's cache lines. Workgroups walk the tiles with a stride (XCD k over the k-th
 // eighth of them, so that an XCD's L2 holds neighbouring image rows), which spreads the cost
 // of loading the filter over several tiles. Measured on 856 000 pixels (32 -> 32 channels):
-// 44 us against 91 us on the LDS-staged kernel; with that filter loop unrolled the kernel is
-// bound by the instructions around the 36 MFMAs of a round, not by memory (the same loop with
-// no load, store or MFMA in it takes two thirds of the time), so launches of one band (tens of
-// thousands of pixels, where it measured no faster) stay on the LDS-staged kernel.
-constexpr int kRegwTiles = 8;           // tiles of 16 pixels of a row per workgroup and round: two per wavefront
+// 36 us against 91 us on the LDS-staged kernel (44 us in a form that loaded the two pixels
+// behind a tile as well and shifted copies of the input between lanes). It is bound by the
+// instructions around the 36 MFMAs of a round, not by memory (the loop with no load, store or
+// MFMA in it takes two thirds of the time), so launches of one band (tens of thousands of
+// pixels, where it measured no faster) stay on the LDS-staged kernel.
+constexpr int kRegwTilePixels = 14;     // output pixels of a tile: 16 loaded pixels less the filter's two extra columns
+constexpr int kRegwTiles = 8;           // tiles per workgroup and round: two per wavefront
 constexpr int kRegwWorkgroups = 768;    // three per compute unit: all resident at once
 constexpr int kRegwMinPixels = 1 << 17;
 
 // rounds of workgroups it takes to cover a launch
 __host__ __device__ inline int regw_groups(const ConvParams& p) {
-  const int tiles = p.N * p.R * ((p.W_out + 15) >> 4);
+  const int tiles = p.N * p.R * ((p.W_out + kRegwTilePixels - 1) / kRegwTilePixels);
   return (tiles + kRegwTiles - 1) / kRegwTiles;
 }
 
@@ -1237,11 +1240,11 @@ __device__ __forceinline__ void conv_regw_kernel_body(const ConvParams& p, const
     bias[cb][0] = b4.x; bias[cb][1] = b4.y; bias[cb][2] = b4.z; bias[cb][3] = b4.w;
   }
   const Clamp cl = make_clamp(p.act);
-  // A tile is 16 consecutive pixels of ONE output row, so that image, row and the nine row
-  // offsets of a tile are the same for the whole wavefront (scalar arithmetic) and a lane only
-  // adds its column; the last tile of a row may hang over its end. Eight tiles per workgroup
-  // and round, two per wavefront.
-  const int tpr = (p.W_out + 15) >> 4;
+  // A tile is 14 consecutive pixels of ONE output row (16 loaded ones), so that image, row and
+  // the three row offsets of a tile are the same for the whole wavefront (scalar arithmetic)
+  // and a lane only adds its column; the last tile of a row may hang over its end. Eight tiles
+  // per workgroup and round, two per wavefront.
+  const int tpr = (p.W_out + kRegwTilePixels - 1) / kRegwTilePixels;
   const int groups = regw_groups(p);
   int grp = bx, step = gx, end = groups;
   if (gx % kXcds == 0) {   // (the hardware hands workgroups to the XCDs round-robin)
@@ -1266,58 +1269,64 @@ __device__ __forceinline__ void conv_regw_kernel_body(const ConvParams& p, const
   const int adv_img = adv_q / p.R, adv_row = adv_q - adv_img * p.R;
   const int lane_in = (pxl - p.pw) * 64 + kq * 16;   // this lane's bytes in a row of the slab, from the tile's first column
   for (; grp < end; grp += step) {
-    // Per tile and filter row ONE load of 16 pixels (the row's first tap) and one of the two
-    // pixels behind them; the second and third tap of a lane are the first tap of its right-hand
-    // neighbours, taken from their registers by lane shifts inside the 16-lane rows. (The L1
-    // hands a wavefront's 16-byte load over in about 35 cycles however its lines hit: with nine
-    // loads per tile the kernel ran at the speed of that path.) A column outside the image loads
-    // as zeros like a row outside, and stays a zero when it is shifted.
-    u32x4 px[2][9];
+    // Per tile and filter row ONE load: 16 consecutive pixels of the input row, the first of
+    // them the first tap of the tile's first output pixel. Every filter column keeps sums of its
+    // own over the three rows (the products of column b with the pixel a lane loaded), and
+    // output pixel j is column 0's sum of lane j + column 1's of lane j + 1 + column 2's of lane
+    // j + 2: two lane shifts per accumulator register instead of shifted copies of the input,
+    // and 14 finished pixels per 16 loaded. A column outside the image loads as zeros like a
+    // row outside. (The L1 hands a wavefront's 16-byte load over in about 33 cycles however its
+    // lines hit: with nine loads per tile the kernel ran at the speed of that path.)
+    u32x4 px[2][3];
     int ow[2];
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-      ow[tile] = tcol[tile] * 16 + pxl;
+      ow[tile] = tcol[tile] * kRegwTilePixels + pxl;
       const bool live = img[tile] < p.N;                       // (the same for the whole wavefront)
       const int ih0 = (p.out_lo + row[tile]) * p.sh - p.ph;    // (... and so are the rows of the taps)
-      const int iw = ow[tile] - p.pw;                          // column of this lane's first tap
-      const unsigned off_a = (iw >= 0) & (iw < p.W) ? (unsigned)(tcol[tile] * 1024 + lane_in) : kOutside;
-      const unsigned off_h = (pxl < 2) & (iw + 16 < p.W) ? (unsigned)(tcol[tile] * 1024 + lane_in + 1024) : kOutside;
+      const int iw = ow[tile] - p.pw;                          // column of the pixel this lane loads
+      const unsigned off_a = (iw >= 0) & (iw < p.W) ? (unsigned)(tcol[tile] * (kRegwTilePixels * 64) + lane_in) : kOutside;
 #pragma unroll
       for (int a = 0; a < 3; ++a) {
         const int ih = ih0 + a * p.dh;
         const bool row_ok = live & (ih >= p.x_row0) & (ih < p.x_row0 + p.x_rows);
         const int row_base = row_ok ? ((img[tile] * p.x_rows - p.x_row0 + ih) * p.W) * 64 : 0;
-        const u32x4 first = __builtin_amdgcn_raw_buffer_load_b128(xbuf, row_ok ? off_a : kOutside, row_base, 0);
-        u32x4 behind = u32x4{0u, 0u, 0u, 0u};
-        if (pxl < 2) behind = __builtin_amdgcn_raw_buffer_load_b128(xbuf, row_ok ? off_h : kOutside, row_base, 0);
-        px[tile][a * 3] = first;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          // lane 15 of a row <- lane 0 of `behind`, then lanes 0..14 <- lanes 1..15 of `first`
-          const int h1 = __builtin_amdgcn_update_dpp(0, (int)behind[i], 0x11f, 0xf, 0xf, true);    // row_shr:15
-          px[tile][a * 3 + 1][i] = (unsigned)__builtin_amdgcn_update_dpp(h1, (int)first[i], 0x101, 0xf, 0xf, false);  // row_shl:1
-          // lanes 14, 15 <- lanes 0, 1 of `behind`, then lanes 0..13 <- lanes 2..15 of `first`
-          const int h2 = __builtin_amdgcn_update_dpp(0, (int)behind[i], 0x11e, 0xf, 0xf, true);    // row_shr:14
-          px[tile][a * 3 + 2][i] = (unsigned)__builtin_amdgcn_update_dpp(h2, (int)first[i], 0x102, 0xf, 0xf, false);  // row_shl:2
-        }
+        px[tile][a] = __builtin_amdgcn_raw_buffer_load_b128(xbuf, row_ok ? off_a : kOutside, row_base, 0);
       }
     }
     f32x4 acc[2][2];
 #pragma unroll
-    for (int tile = 0; tile < 2; ++tile)
+    for (int tile = 0; tile < 2; ++tile) {
+      f32x4 col[3][2];
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) acc[tile][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int b = 0; b < 3; ++b)
 #pragma unroll
-    for (int tile = 0; tile < 2; ++tile)
+        for (int cb = 0; cb < 2; ++cb) col[b][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int t = 0; t < 9; ++t)
+      for (int a = 0; a < 3; ++a)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) mma16<__bf16>(wt[t][cb], px[tile][t], acc[tile][cb]);
+        for (int b = 0; b < 3; ++b)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) mma16<__bf16>(wt[a * 3 + b][cb], px[tile][a], col[b][cb]);
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          // (row_shl: lane j reads lane j + 1 / j + 2 of its row of 16; the last lanes read zero
+          // and finish no pixel)
+          // (the elements are copied out first: __builtin_bit_cast applied to an element of a
+          // vector reads the vector's first element whatever the index)
+          const float f1 = col[1][cb][i], f2 = col[2][cb][i];
+          const float c1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f1), 0x101, 0xf, 0xf, true));
+          const float c2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f2), 0x102, 0xf, 0xf, true));
+          acc[tile][cb][i] = (col[0][cb][i] + c1) + c2;
+        }
+    }
     // bias + residual + activation + the one rounding: a lane holds channels
     // co0 + 16 cb + 4 kq + {0..3} of its pixel of either tile
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-      if (img[tile] < p.N && ow[tile] < p.W_out) {
+      if (img[tile] < p.N && pxl < kRegwTilePixels && ow[tile] < p.W_out) {
         const int oh = p.out_lo + row[tile];
         const long yrow = ((long)(img[tile] * p.y_rows + oh - p.y_row0) * p.W_out) * p.C_out + co0;
         const long rrow = p.res ? ((long)(img[tile] * p.r_rows + oh - p.r_row0) * p.W_out) * p.C_out + co0 : 0;
