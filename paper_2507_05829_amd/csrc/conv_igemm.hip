@@ -36,6 +36,22 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // array of them that is filled from memory stays in private memory)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Division of a pixel index by a width or a row count that only the host knows: q = (mulhi(n,
+// mul) + n) >> shift for 0 <= n < 2^31 (Granlund and Montgomery's division by an invariant
+// integer), three instructions where the integer division of two registers takes about forty,
+// and a wavefront issues one instruction in four cycles or more.
+struct FastDiv { unsigned mul; int shift; };
+inline FastDiv make_fastdiv(int d) {
+  FastDiv f{1u, 0};
+  if (d < 1) return f;
+  while ((1L << f.shift) < d) ++f.shift;
+  f.mul = (unsigned)((((unsigned long long)1 << 32) * (((unsigned long long)1 << f.shift) - (unsigned long long)d)) / (unsigned long long)d + 1);
+  return f;
+}
+__device__ __forceinline__ int fastdiv(int n, const FastDiv& f) {
+  return (int)((__umulhi((unsigned)n, f.mul) + (unsigned)n) >> f.shift);
+}
+
 struct ConvParams {
   const void* x;
   void* y;
@@ -55,7 +71,9 @@ struct ConvParams {
   int K, k_pad;
   int splits, kc_per_split;
   int pool;  // conv_lds_kernel<..., true>: R, out_lo, W_out and y describe the 2 x 2 max-pooled tensor
+  FastDiv by_w, by_r;  // division by W_out and by R
 };
+static_assert(sizeof(Batch<ConvParams>) <= 4096, "the parameters of all bands of a launch travel as kernel arguments");
 
 __device__ __forceinline__ float apply_act(float v, int act) {
   return clamp_act(v, make_clamp(act));
@@ -99,10 +117,19 @@ __device__ __forceinline__ void lds_wave_order() {
 struct PixelAddr {
   size_t y, r;
 };
+// Output pixel m of a launch -> image, row of the launch, column.
+struct PixelAt { int n, r, ow; };
+__device__ __forceinline__ PixelAt pixel_at(const ConvParams& p, int m) {
+  PixelAt a;
+  const int q = fastdiv(m, p.by_w);
+  a.ow = m - q * p.W_out;
+  a.n = fastdiv(q, p.by_r);
+  a.r = q - a.n * p.R;
+  return a;
+}
 __device__ __forceinline__ PixelAddr pixel_addr(const ConvParams& p, int m) {
-  const int ow = m % p.W_out;
-  const int t = m / p.W_out;
-  const int r = t % p.R, n = t / p.R;
+  const PixelAt at = pixel_at(p, m);
+  const int ow = at.ow, r = at.r, n = at.n;
   const int oh = p.out_lo + r;
   PixelAddr a;
   a.y = ((size_t)(n * p.y_rows + oh - p.y_row0) * p.W_out + ow) * p.C_out;
@@ -244,9 +271,8 @@ __device__ __forceinline__ void conv_igemm_kernel_body(const ConvParams& p, cons
     const int m = m0 + row;
     a_ok[i] = m < p.M && (BM % RPP == 0 || row < BM);
     const int mm = a_ok[i] ? m : 0;
-    const int ow = mm % p.W_out;
-    const int t = mm / p.W_out;
-    const int r = t % p.R, n = t / p.R;
+    const PixelAt at = pixel_at(p, mm);
+    const int ow = at.ow, r = at.r, n = at.n;
     a_ih0[i] = (p.out_lo + r) * p.sh - p.ph;
     a_iw0[i] = ow * p.sw - p.pw;
     a_nrow[i] = n * p.x_rows - p.x_row0;
@@ -658,9 +684,8 @@ __device__ __forceinline__ void conv_direct_kernel_body(const ConvParams& p, con
   int ih0, iw0, nrow;
   {
     const int mm = m_ok ? m : 0;
-    const int ow = mm % p.W_out;
-    const int q = mm / p.W_out;
-    const int r = q % p.R, n = q / p.R;
+    const PixelAt at = pixel_at(p, mm);
+    const int ow = at.ow, r = at.r, n = at.n;
     ih0 = (p.out_lo + r) * p.sh - p.ph;
     iw0 = ow * p.sw - p.pw;
     nrow = n * p.x_rows - p.x_row0;
@@ -869,9 +894,8 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
     const int m = m0 + (wave + 4 * i) * 8 + lrow;
     const bool ok = m < p.M;
     const int mm = ok ? (POOL ? m >> 2 : m) : 0;
-    const int ow = mm % p.W_out;
-    const int t = mm / p.W_out;
-    const int r = t % p.R, n = t / p.R;
+    const PixelAt at = pixel_at(p, mm);
+    const int ow = at.ow, r = at.r, n = at.n;
     // the convolution's output pixel behind this row of the tile
     const int oy = POOL ? (p.out_lo + r) * 2 + ((m >> 1) & 1) : p.out_lo + r;
     const int ox = POOL ? ow * 2 + (m & 1) : ow;
@@ -1457,9 +1481,8 @@ __device__ __forceinline__ void conv_narrow_kernel_body(const ConvParams& p, con
   int ih0, iw0, nrow;
   {
     const int mm = m_ok ? m : 0;
-    const int ow = mm % p.W_out;
-    const int q = mm / p.W_out;
-    const int r = q % p.R, n = q / p.R;
+    const PixelAt at = pixel_at(p, mm);
+    const int ow = at.ow, r = at.r, n = at.n;
     ih0 = (p.out_lo + r) * p.sh - p.ph;
     iw0 = ow * p.sw - p.pw;
     nrow = n * p.x_rows - p.x_row0;
@@ -1884,6 +1907,8 @@ ConvParams make_params(const OpLaunch& L) {
   p.dh = L.dh; p.dw = L.dw;
   p.act = L.act; p.out_lo = L.out_lo; p.R = L.out_hi - L.out_lo; p.N = L.x.n;
   p.M = p.N * p.R * p.W_out;
+  p.by_w = make_fastdiv(p.W_out);
+  p.by_r = make_fastdiv(p.R);
   p.K = L.x.c * L.kh * L.kw;
   p.k_pad = L.k_pad;
   p.splits = 1;
