@@ -72,6 +72,7 @@ struct ConvParams {
   int splits, kc_per_split;
   int pool;  // conv_lds_kernel<..., true>: R, out_lo, W_out and y describe the 2 x 2 max-pooled tensor
   FastDiv by_w, by_r;  // division by W_out and by R
+  FastDiv by_group;    // ... by kGroupM x the launch's channel tiles (xcd_tile), set by the launchers that use it
 };
 static_assert(sizeof(Batch<ConvParams>) <= 4096, "the parameters of all bands of a launch travel as kernel arguments");
 
@@ -211,20 +212,26 @@ __device__ __forceinline__ void finish_vec(const ConvParams& p, int m, int co, f
 // 8 x 8 tiles that shares 8 pixel tiles and 8 weight tiles. Reduction slices are outermost.
 struct TileId { int m, n, z; };
 constexpr int kXcds = 8, kGroupM = 8;
-__device__ __forceinline__ TileId xcd_tile(int bx, int mx, int ny, int nz) {
+// (by_group: division by kGroupM * ny, made on the host; the other divisions of this walk are by
+// constants or lie behind conditions that hold for few workgroups)
+__device__ __forceinline__ TileId xcd_tile(int bx, int mx, int ny, int nz, const FastDiv& by_group) {
   const int total = mx * ny * nz;
   const int launch = bx + mx * (blockIdx.y + ny * blockIdx.z);
   const int xcd = launch % kXcds, slot = launch / kXcds;
   const int q = total / kXcds, r = total % kXcds;
   const int v = xcd * q + min(xcd, r) + slot;  // XCD k owns q (+1 for the first r) consecutive tiles
-  const int per_z = mx * ny;
-  const int z = v / per_z, t = v - z * per_z;
-  const int group = t / (kGroupM * ny), in_group = t - group * (kGroupM * ny);
+  int z = 0, t = v;
+  if (nz > 1) {
+    const int per_z = mx * ny;
+    z = v / per_z;
+    t = v - z * per_z;
+  }
+  const int group = fastdiv(t, by_group), in_group = t - group * (kGroupM * ny);
   const int first = group * kGroupM;
   const int gm = min(kGroupM, mx - first);
   TileId id;
   id.z = z;
-  id.n = in_group / gm;
+  id.n = gm == kGroupM ? in_group / kGroupM : in_group / gm;
   id.m = first + in_group - id.n * gm;
   return id;
 }
@@ -251,7 +258,7 @@ __device__ __forceinline__ void conv_igemm_kernel_body(const ConvParams& p, cons
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
-  const TileId tile = xcd_tile(bx, gx, gridDim.y, gridDim.z);
+  const TileId tile = xcd_tile(bx, gx, gridDim.y, gridDim.z, p.by_group);
   const int m0 = tile.m * BM, co0 = tile.n * BN;
   const int lrow = tid / CH, chunk = tid % CH;
   const T* __restrict__ xg = (const T*)p.x;
@@ -873,7 +880,7 @@ __device__ __forceinline__ void conv_lds_kernel_body(const ConvParams& p, const 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // every XCD takes a contiguous stretch of the tiles (a few pixel tiles times the channel
   // tiles), so that its L2 pulls a part of each operand instead of all of both
-  const TileId tile = xcd_tile(bx, gx, gridDim.y, 1);
+  const TileId tile = xcd_tile(bx, gx, gridDim.y, 1, p.by_group);
   const int m0 = tile.m * BM, co0 = tile.n * BN;
   const unsigned char* __restrict__ xg = (const unsigned char*)p.x;
   const unsigned char* __restrict__ wg = (const unsigned char*)p.w;
@@ -1602,13 +1609,24 @@ inline void blocks_per_band(const ConvParams* ps, int n, int per, unsigned* gx) 
   for (int b = 0; b < n; ++b) gx[b] = (unsigned)((ps[b].M + per - 1) / per);
 }
 
+// Copies of the bands' parameters that know the launch's channel-tile count (xcd_tile's divisor).
+inline void with_tile_walk(const ConvParams* ps, int n, unsigned gy, ConvParams* out) {
+  for (int b = 0; b < n; ++b) {
+    out[b] = ps[b];
+    out[b].by_group = make_fastdiv(kGroupM * (int)gy);
+  }
+}
+
 template <typename T, int BM, int BN, int NST>
-hipError_t launch_lds(const ConvParams* ps, int n, hipStream_t s, KernelEvents* ev) {
-  const ConvParams& p = ps[0];
+hipError_t launch_lds(const ConvParams* ps_in, int n, hipStream_t s, KernelEvents* ev) {
+  if (n < 1 || n > kMaxBatch) return hipErrorInvalidValue;
+  const ConvParams& p = ps_in[0];
   unsigned gx[kMaxBatch];
-  blocks_per_band(ps, n, BM, gx);
+  blocks_per_band(ps_in, n, BM, gx);
   const unsigned gy = (unsigned)((p.C_out + BN - 1) / BN);
   if ((int)gy * BN > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
+  ConvParams ps[kMaxBatch];
+  with_tile_walk(ps_in, n, gy, ps);
   const int row_bytes = p.C_in * (int)sizeof(T);
   if (row_bytes == 64) {
     if (p.pool) return hipErrorInvalidValue;
@@ -1786,11 +1804,14 @@ hipError_t launch_finish(const ConvParams* ps, int n, hipStream_t s, KernelEvent
 }
 
 template <typename T, int BM, int BN, int WM, int WN>
-hipError_t launch_shape(const ConvParams* ps, int n, bool vec_a, hipStream_t s, KernelEvents* ev) {
-  const ConvParams& p = ps[0];
+hipError_t launch_shape(const ConvParams* ps_in, int n, bool vec_a, hipStream_t s, KernelEvents* ev) {
+  if (n < 1 || n > kMaxBatch) return hipErrorInvalidValue;
+  const ConvParams& p = ps_in[0];
   unsigned gx[kMaxBatch];
-  blocks_per_band(ps, n, BM, gx);
+  blocks_per_band(ps_in, n, BM, gx);
   const unsigned gy = (unsigned)((p.C_out + BN - 1) / BN);
+  ConvParams ps[kMaxBatch];
+  with_tile_walk(ps_in, n, gy, ps);
   const dim3 block(64 * WM * WN);
   // weight loads are unguarded: the channel tiles must end inside the padded packing
   if ((int)gy * BN > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
@@ -1881,8 +1902,9 @@ hipError_t launch_typed(ConvParams* ps, int n, int dtype, float* ws, hipStream_t
   if (c.shape == S256x256) {
     if constexpr (sizeof(T) == 2) {
       if (n != 1) return hipErrorInvalidValue;   // (chosen for single launches of at least 256 tiles only)
-      const ConvParams& p = ps[0];
-      dim3 grid((p.M + 255) / 256, (p.C_out + 255) / 256, 1);
+      dim3 grid((ps[0].M + 255) / 256, (ps[0].C_out + 255) / 256, 1);
+      ConvParams p;
+      with_tile_walk(ps, 1, grid.y, &p);
       if ((int)grid.y * 256 > conv_cout_pad(p.C_out)) return hipErrorInvalidValue;
       return launch_kernel(conv_igemm_kernel<T, 256, 256, 2, 4, kBigBKB, kStages, true>, grid, dim3(512), s, ev, p);
     }
@@ -1909,6 +1931,7 @@ ConvParams make_params(const OpLaunch& L) {
   p.M = p.N * p.R * p.W_out;
   p.by_w = make_fastdiv(p.W_out);
   p.by_r = make_fastdiv(p.R);
+  p.by_group = make_fastdiv(1);
   p.K = L.x.c * L.kh * L.kw;
   p.k_pad = L.k_pad;
   p.splits = 1;
