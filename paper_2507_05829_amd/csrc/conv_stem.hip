@@ -4,16 +4,19 @@
 // element; the arithmetic itself is small enough for the vector ALUs (Sec. IV-A local operator:
 // every output pixel depends on a kh x kw window of the input only).
 //
-// A lane owns one output pixel and CPL (16 or 32) output channels; a wavefront owns 64 consecutive
-// pixels of one output row. The lane loads the kw * C_in contiguous elements of every row of its
-// window itself (neighbouring lanes read overlapping bytes: the L1 serves them) and, for every
-// element of the reduction axis, multiplies it into its CPL accumulators with weights whose
-// address is the same for the whole wavefront (the compiler turns those loads into scalar loads,
-// and the multiply-adds take the weights from scalar registers). The weights are packed
-// [C_out / 16][K][16] fp32 for that (behind the [C_out / 4][K][4] packing of the form below). No LDS and no barrier: an earlier form staged the input
-// window of 64 pixels x 16 channels per workgroup in LDS and spent more time launching its
-// 27 000 workgroups and waiting for their one batch of loads than computing. KJ: kw * C_in when
-// it is one of the usual values (the loop over a kernel row is then unrolled), else 0.
+// Two forms. For launches of thousands of 64-pixel tiles (conv_stem_lane_kernel): a lane owns one
+// output pixel and CPL (16 or 32) output channels, a wavefront 64 consecutive pixels of one
+// output row. The lane loads the kw * C_in contiguous elements of every row of its window itself
+// (neighbouring lanes read overlapping bytes: the L1 serves them) and, for every element of the
+// reduction axis, multiplies it into its CPL accumulators with weights whose address is the same
+// for the whole wavefront (the compiler turns those loads into scalar loads, and the
+// multiply-adds take the weights from scalar registers). The weights are packed
+// [C_out / 16][K][16] fp32 for that, behind the [C_out / 4][K][4] packing of the other form. No
+// LDS and no barrier: at these sizes the other form spends more time launching its tens of
+// thousands of workgroups and waiting for their one batch of loads than computing. For smaller
+// launches (conv_stem_kernel, further down) the window of 64 pixels is staged in LDS and four
+// wavefronts share its pixels. KJ: kw * C_in when it is one of the usual values (the loop over
+// a kernel row is then unrolled), else 0.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
